@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the gradient data-reduction hot path on one MI355X.
+
+A step = one nsml_compress + one nsml_decompress over one worker's whole synthetic gradient,
+inputs resident in HBM.  Prints ONE JSON line:
+  value     GB/s of input fp32 gradient per step (4n / t_step), whole job (one GPU)
+  roofline  the dominant kernel (ef_hist: reads grad and residual, writes the accumulator:
+            12 algorithmic bytes per element) against the 8 TB/s HBM peak, its duration
+            measured with HIP events by the library on the stream it is launched on
+  cpu_baseline  the CPU oracle timed on this host's cores on a bounded sample of the workload
+Workloads (all synthetic, seeded; see paper_2506_16235_amd/workloads.py):
+  llama7b   6,738,415,616 elements in 258 buckets of 25 Mi, Student-t(3)*1e-4, ratio 0.001,
+            int4, residual carried across steps      (default: the largest single-GPU config)
+  bert      109,482,240 elements in 199 per-tensor buckets, Laplace(0,1e-4), 95 % zero
+            embedding rows, ratio 0.01 int8 (override with --ratio / --bits)
+  resnet50  25,557,032 elements in 161 buckets, N(0, sigma_l), ratio 0.05 int8
+  cfg1      1,048,576 elements, one bucket, N(0,1e-3), ratio 0.01 int8
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+EF_HIST_BYTES_PER_ELEM = 12.0     # read grad, read residual, write accumulator
+
+DEFAULTS = {          # workload -> (ratio, bits, distinct gradients kept in HBM)
+    "llama7b": (0.001, 4, 2),
+    "bert": (0.01, 8, 2),
+    "resnet50": (0.05, 8, 4),
+    "cfg1": (0.01, 8, 1),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_grads(workload, count, dev):
+    import torch
+    from paper_2506_16235_amd import workloads as W
+    grads = []
+    off = None
+    for s in range(count):
+        t0 = time.time()
+        if workload == "llama7b":
+            g, off = W.llama7b_grad(s, dev)
+        elif workload == "bert":
+            g, off = W.bert_grad(s, dev)
+        elif workload == "resnet50":
+            g, off = W.resnet50_grad(s, dev)
+        else:
+            g, off = W.cfg1(dev)
+        torch.cuda.synchronize()
+        log(f"[bench] gradient {s} of {workload}: {g.numel()} elements in {time.time() - t0:.1f}s")
+        grads.append(g)
+    return grads, off
+
+
+def cpu_baseline(workload, grads, off, ratio, bits, chunk):
+    """The oracle, as it stands, on a bounded sample: whole buckets of the first gradient (zero
+    residual) chosen to give roughly 10-30 s of CPU work, one bucket per thread."""
+    import numpy as np
+    import oracle
+    cores = min(16, os.cpu_count() or 1)
+    sizes = (off[1:] - off[:-1]).astype(np.int64)
+    budget = 8_000_000 * cores if workload != "llama7b" else 0
+    if workload == "llama7b":
+        pick = list(range(min(cores, len(sizes))))
+        what = f"first {len(pick)} of {len(sizes)} buckets (25 Mi elements each)"
+    else:
+        order = list(range(len(sizes)))
+        pick, tot = [], 0
+        for b in order:
+            if tot + sizes[b] > max(budget, sizes[b]) and pick:
+                break
+            pick.append(b)
+            tot += sizes[b]
+            if tot >= budget:
+                break
+        what = f"first {len(pick)} of {len(sizes)} buckets"
+    lo, hi = int(off[pick[0]]), int(off[pick[-1] + 1])
+    g = grads[0][lo:hi].cpu().numpy()
+    sub_off = (off[pick[0]:pick[-1] + 2] - off[pick[0]]).astype(np.uint64)
+    r = np.zeros_like(g)
+    oracle.lib()
+    t0 = time.perf_counter()
+    idx, val, sc = oracle.compress(g, r, sub_off, ratio, bits, chunk, nthreads=cores)
+    oracle.decompress(idx, val, sc, g.size, sub_off, ratio, bits, chunk, nthreads=cores)
+    dt = time.perf_counter() - t0
+    used = min(cores, len(pick))
+    return {"value": round(4.0 * g.size / dt / 1e9, 4), "unit": "GB/s", "cores": used,
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"{what}, {g.size} elements, zero residual, compress+decompress, "
+                      f"one bucket per thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama7b", choices=sorted(DEFAULTS))
+    ap.add_argument("--ratio", type=float, default=None)
+    ap.add_argument("--bits", type=int, default=None)
+    ap.add_argument("--chunk", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one worker's pipeline on ONE GPU; a run with "
+              "--gpus > 1 is not defined (no collectives are part of the path).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2506_16235_amd import binding as nsml
+
+    dev = "cuda:0"
+    ratio, bits, ngrads = DEFAULTS[args.workload]
+    ratio = args.ratio if args.ratio is not None else ratio
+    bits = args.bits if args.bits is not None else bits
+    chunk = args.chunk
+
+    grads, off = make_grads(args.workload, ngrads, dev)
+    n = grads[0].numel()
+    B = len(off) - 1
+    ctx = nsml.Context(n, B, chunk)
+    k_b, K, vb, ns = nsml.payload_layout(off, ratio, bits, chunk)
+    payload = 4 * K + vb + 4 * ns
+    idx, val, sc = ctx.alloc_payload(off, ratio, bits)
+    residual = torch.zeros(n, dtype=torch.float32, device=dev)
+    dense = torch.empty(n, dtype=torch.float32, device=dev)
+    log(f"[bench] {args.workload}: n={n} B={B} ratio={ratio} bits={bits} K={K} payload={payload} B "
+        f"workspace={ctx.workspace_bytes / 2**30:.2f} GiB")
+
+    step_no = [0]
+
+    def step():
+        g = grads[step_no[0] % len(grads)]
+        step_no[0] += 1
+        ctx.compress(g, residual, off, ratio, bits, idx, val, sc)
+        ctx.decompress(idx, val, sc, n, off, ratio, bits, dense)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K steps between two synchronisations
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # ---- the same K steps again with every kernel bracketed by HIP events (library side,
+    #      on the launch stream) for the per-kernel durations
+    ctx.profile_enable(True)
+    ctx.profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall_prof = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    kernels = {k: {"launches": c, "avg_ms": round(ms / c, 5)} for k, (c, ms) in prof.items()}
+    ef = prof.get("ef_hist")
+    ef_ms = ef[1] / ef[0]
+    achieved = EF_HIST_BYTES_PER_ELEM * n / (ef_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_ef_hist_{args.workload}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    value = 4.0 * n / (ms_per_step * 1e-3) / 1e9
+    floor_bytes = 16.0 * n + 2.0 * payload
+    out = {
+        "metric": "compress+decompress GB/s of fp32 gradient per step; % of HBM roofline",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "elements": n, "buckets": B, "ratio": ratio,
+                   "bits": bits, "chunk": chunk, "survivors": K, "payload_bytes": payload,
+                   "distinct_gradients": len(grads), "residual": "carried across steps"},
+        "hbm_roofline_frac": round(floor_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
+        "floor_bytes_per_step": floor_bytes,
+        "roofline": {"kernel": "ef_hist", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "avg_ms": round(ef_ms, 5),
+                     "algorithmic_bytes_per_launch": EF_HIST_BYTES_PER_ELEM * n},
+        "kernels": kernels,
+        "ms_per_step_profiled": round(wall_prof / args.steps * 1e3, 4),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload, grads, off, ratio, bits, chunk)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

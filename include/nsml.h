@@ -1,0 +1,193 @@
+/*
+ * nsml.h -- C ABI of libnsml: the per-step gradient data-reduction pipeline that one
+ * data-parallel NetSenseML worker runs on its own gradient before communication,
+ * for AMD MI355X (gfx950).
+ *
+ *   nsml_choose_ratio   host   Algorithm 1 + Eq. (1)-(3): network sensing -> ratio;
+ *                              Algorithm 2 Step 1: the value width for the step
+ *   nsml_compress       GPU    Sec. 4.2 Step 3 / Algorithm 2 Step 3: local accumulation
+ *                              (error feedback), exact top-k by magnitude, then the value
+ *                              coding and index/value/scale payload of the build contract
+ *   nsml_decompress     GPU    receiver side of "transmit the sparsified gradient":
+ *                              payload -> dense gradient
+ *
+ * Conventions
+ *   - Every function returns int: NSML_OK (0) or a negative NSML_E* code.  Nothing throws,
+ *     aborts or prints.
+ *   - "dev" pointers are device memory on the context's GPU, allocated and owned by the
+ *     caller; "host" pointers are ordinary host memory.  The library allocates only its own
+ *     workspace, once, in nsml_create.
+ *   - GPU entry points enqueue work on the caller's HIP stream and return without waiting.
+ *     A context serves one stream at a time: calls that use the same context must be
+ *     ordered on one stream (or separated by a synchronisation).
+ *   - A gradient of n fp32 elements is split into B consecutive buckets by the host array
+ *     bucket_off[0..B], bucket_off[0] = 0, bucket_off[B] = n, non-decreasing.  Buckets are
+ *     compressed independently (the DDP hook of Sec. 5.1 is called per bucket); a bucket has
+ *     fewer than 2^32 elements; empty buckets are allowed.
+ *   - grad, residual and dense_out must be 16-byte aligned, idx/scales/val 4-byte aligned.
+ *     No two of the buffers passed to one call may overlap.
+ */
+#ifndef NSML_H
+#define NSML_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NSML_OK        0
+#define NSML_EINVAL   (-1)  /* null pointer, n == 0, ratio outside (0,1], bits not in {4,8,16,32},
+                               offsets not ascending or not covering [0,n), bucket >= 2^32,
+                               chunk not a positive multiple of 8, misaligned buffer */
+#define NSML_ECAP     (-2)  /* n, B or chunk exceed what the context was created for */
+#define NSML_EHIP     (-3)  /* a HIP call failed; see nsml_last_hip_error */
+#define NSML_ENOTIMPL (-4)
+#define NSML_ENOMEM   (-5)  /* host allocation failed */
+
+const char *nsml_strerror(int code);
+
+/* ------------------------------------------------------------------ controller (host) */
+
+/* Parameters of Algorithm 1 / Eq. (3) and of the gate of Algorithm 2 Step 1.
+ * The paper prints alpha = 0.5, beta2 = 0.01, the initial ratio 0.01, the floor 0.005, the cap 1
+ * and the trigger 0.9 * BDP; the remaining defaults are this library's readings. */
+typedef struct nsml_ctl_params {
+    double alpha;       /* 0.5   multiplicative decrease, Eq. (3) */
+    double beta1;       /* 0.1   start-up increment, Algorithm 1 Step 1 (value not printed) */
+    double beta2;       /* 0.01  additive increase, Eq. (3) */
+    double floor;       /* 0.005 lower bound of the ratio, Eq. (3) */
+    double cap;         /* 1.0   upper bound of the ratio, Eq. (3) */
+    double init;        /* 0.01  initial ratio, Algorithm 1 Step 1 */
+    double bdp_frac;    /* 0.9   congestion trigger as a fraction of BDP, Eq. (3) */
+    double rtt_excess;  /* 2.0   start-up ends when the last transmission time exceeds this
+                                 multiple of RTprop ("excessive RTT") */
+    double tr_q;        /* 0.1   Algorithm 2 Step 1: quantize when ratio < tr_q ... */
+    double tr_q4;       /* 0.01  ... with 4-bit codes when ratio < tr_q4 (quant_mode 0) */
+    double tr_d;        /* 0.0   ... and the gradient L2 norm exceeds tr_d */
+    int32_t startup_max;/* 10    start-up lasts at most this many increments */
+    int32_t win_bw;     /* 10    BtlBw = max EBB over the last win_bw intervals; 0 = all time */
+    int32_t win_rt;     /* 100   RTprop = min RTT over the last win_rt intervals; 0 = all time */
+    int32_t quant_mode; /* 0: int8 / int4 codes; 1: binary16, the paper's own cast; 2: never */
+} nsml_ctl_params;
+
+#define NSML_CTL_MAX_WIN 128
+
+/* Controller state: plain data, can be copied, saved and restored with memcpy. */
+typedef struct nsml_ctl_state {
+    nsml_ctl_params p;
+    double ratio;        /* the controller's own ratio (before the gate's doubling) */
+    double btlbw;        /* bytes / second, max EBB in the window */
+    double rtprop;       /* seconds, min transmission time in the window */
+    double bdp;          /* bytes, Eq. (2) */
+    double all_max_ebb;  /* running extremes for window 0 */
+    double all_min_rtt;
+    double ebb[NSML_CTL_MAX_WIN];   /* ring buffers, newest at (count - 1) % NSML_CTL_MAX_WIN */
+    double rtt[NSML_CTL_MAX_WIN];
+    int64_t count;       /* measurements seen */
+    int32_t phase;       /* 0 start-up, 1 NetSense */
+    int32_t startup_steps;
+} nsml_ctl_state;
+
+/* Fill *p with the defaults listed above. */
+int nsml_ctl_default_params(nsml_ctl_params *p);
+
+/* Start a controller: ratio = p->init, start-up phase.  p == NULL uses the defaults.
+ * NSML_EINVAL if a window exceeds NSML_CTL_MAX_WIN or a bound is inconsistent. */
+int nsml_ctl_init(nsml_ctl_state *s, const nsml_ctl_params *p);
+
+/* One decision before a transmission (Algorithm 1, one iteration).
+ *   last_payload_bytes, last_tx_seconds  size and transmission time of the interval just
+ *       finished (data_size_{i-1}, RTT_{i-1}); both <= 0 means "nothing measured yet" and
+ *       leaves the ratio unchanged.
+ *   dense_bytes   size of the uncompressed gradient; informational (ignored by the update).
+ *   last_l2norm   L2 norm of the gradient for the density test of Algorithm 2 Step 1;
+ *                 negative = unknown, which passes the test.
+ *   ratio_out     ratio to hand to nsml_compress (already doubled when values are quantized)
+ *   bits_out      32, 16, 8 or 4
+ * Host only, O(window). */
+int nsml_choose_ratio(nsml_ctl_state *s, double last_payload_bytes, double last_tx_seconds,
+                      double dense_bytes, double last_l2norm, double *ratio_out, int *bits_out);
+
+/* ------------------------------------------------------------------ payload geometry */
+
+/* Pure host function.  k_b = min(n_b, max(1, ceil(ratio * n_b))) survivors per non-empty
+ * bucket (Algorithm 2 Step 3).  Payload of a call:
+ *   idx     uint32[K]           bucket-local indices, ascending inside each bucket, buckets
+ *                               in order (bucket b starts at sum of k_b' for b' < b)
+ *   val     val_bytes bytes     per bucket, byte-aligned: bits 32: float[k_b]; 16: binary16[k_b];
+ *                               8: int8[k_b]; 4: ceil(k_b/2) bytes, survivor 2t in the low
+ *                               nibble of byte t, survivor 2t+1 in the high nibble, two's
+ *                               complement, unused high nibble of an odd tail = 0
+ *   scales  float[n_scales]     bits 8/4 only: one per `chunk` consecutive survivors of a
+ *                               bucket (last chunk of a bucket may be short); scale =
+ *                               absmax / 127 (8) or / 7 (4); n_scales = 0 for bits 16/32
+ * Any of k_b (host, B entries), K, val_bytes, n_scales may be NULL. */
+int nsml_payload_layout(const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                        uint32_t chunk, uint64_t *k_b, uint64_t *K, uint64_t *val_bytes,
+                        uint64_t *n_scales);
+
+/* ------------------------------------------------------------------ GPU path */
+
+typedef struct nsml_ctx nsml_ctx;
+
+/* Allocate a context and its device workspace on GPU `device` for gradients of up to max_n
+ * elements in up to max_buckets buckets, quantized in chunks of `chunk` survivors (2048 in
+ * the benchmark configurations; a positive multiple of 8).  Workspace: about 4 bytes per
+ * element of max_n plus 33 KiB per bucket.  NSML_EHIP if the device or its memory is not
+ * available (there is no CPU fallback). */
+int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
+int nsml_destroy(nsml_ctx *ctx);
+
+/* hipError_t of the last failed HIP call made through this context (0 = none). */
+int nsml_last_hip_error(const nsml_ctx *ctx);
+/* Bytes of device workspace the context holds. */
+uint64_t nsml_workspace_bytes(const nsml_ctx *ctx);
+
+/* Compress one gradient.
+ *   grad      dev, const, float[n]
+ *   residual  dev, in/out, float[n]: on entry what earlier steps did not send, on return what
+ *             this step does not send: residual'[i] = grad[i] + residual[i] for elements not
+ *             selected, and (value - decoded value) for selected ones, so that
+ *             decompressed + residual' == grad + residual element by element
+ *   n, bucket_off (host, B+1), B   the bucketed gradient
+ *   ratio     in (0, 1]; k_b as in nsml_payload_layout.  Survivors of a bucket are its k_b
+ *             largest |grad + residual|; equal magnitudes (+0 and -0 are equal) go to the
+ *             lower index; exactly k_b are kept, zeros included if needed
+ *   bits      32, 16, 8 or 4
+ *   idx, val, scales  dev, out, sized by nsml_payload_layout (scales may be NULL for 16/32)
+ *   stream    hipStream_t (NULL = the default stream)
+ * Errors found while enqueuing are returned; the outputs are complete when the stream
+ * reaches the end of the enqueued work. */
+int nsml_compress(nsml_ctx *ctx, const float *grad, float *residual, uint64_t n,
+                  const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                  uint32_t *idx, void *val, float *scales, void *stream);
+
+/* Decompress a payload produced with the same (bucket_off, B, ratio, bits, chunk):
+ *   dense_out  dev, out, float[n], fully overwritten: +0 everywhere except
+ *              dense_out[bucket_off[b] + idx[j]] = decoded value j
+ * The indices of each bucket must be ascending and inside the bucket, as nsml_compress
+ * writes them; other index lists give unspecified values in dense_out (never an access
+ * outside dense_out). */
+int nsml_decompress(nsml_ctx *ctx, const uint32_t *idx, const void *val, const float *scales,
+                    uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                    float *dense_out, void *stream);
+
+/* ------------------------------------------------------------------ measurement */
+
+#define NSML_MAX_KERNELS 16
+
+/* When enabled, every kernel launch of the context is bracketed by HIP events on the caller's
+ * stream.  nsml_profile_read synchronises those events and returns, for each kernel id,
+ * the number of launches and their summed duration in milliseconds since the last read
+ * (arrays of NSML_MAX_KERNELS entries), then resets the record.  At most 4096 launches are
+ * kept between reads. */
+int nsml_profile_enable(nsml_ctx *ctx, int on);
+int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
+/* Name of kernel id (NULL beyond the last). */
+const char *nsml_kernel_name(int id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NSML_H */

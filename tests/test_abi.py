@@ -1,0 +1,128 @@
+"""CPU-side checks of the C ABI: every declared symbol is exported, the host-only entry points
+(controller, payload geometry) agree with the oracle, argument errors are reported."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_16235_amd import binding as nsml
+from paper_2506_16235_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(nsml_[a-z0-9_]+)\s*\(", text))
+    assert {"nsml_choose_ratio", "nsml_compress", "nsml_decompress"} <= names
+    lib = nsml.raw()
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_header():
+    # 11 doubles + 4 int32; state = params + 6 doubles + 2*128 doubles + int64 + 2 int32
+    assert C.sizeof(nsml.CtlParams) == 11 * 8 + 4 * 4
+    assert C.sizeof(nsml.CtlState) == C.sizeof(nsml.CtlParams) + 6 * 8 + 2 * 128 * 8 + 8 + 8
+
+
+@pytest.mark.parametrize("bits", [4, 8, 16, 32])
+def test_payload_layout_matches_oracle(bits):
+    rng = np.random.default_rng(bits)
+    for sizes in (W.resnet50_sizes(), W.bert_base_sizes(), [0, 5, 0, 100000, 1],
+                  list(rng.integers(0, 50000, 40))):
+        off = W.offsets_of(sizes)
+        for ratio in (1.0, 0.1, 0.05, 0.01, 0.001, 0.0037):
+            k1, K1, v1, s1 = nsml.payload_layout(off, ratio, bits, 2048)
+            k2, K2, v2, s2 = oracle.layout(off, ratio, bits, 2048)
+            assert np.array_equal(k1, k2) and (K1, v1, s1) == (K2, v2, s2)
+
+
+def test_layout_rejects_bad_arguments():
+    off = np.array([0, 10], dtype=np.uint64)
+    for args in ((0.0, 8, 2048), (1.5, 8, 2048), (0.5, 5, 2048), (0.5, 8, 0), (0.5, 8, 12)):
+        with pytest.raises(nsml.NsmlError) as e:
+            nsml.payload_layout(off, *args)
+        assert e.value.code == nsml.EINVAL
+    with pytest.raises(nsml.NsmlError):
+        nsml.payload_layout(np.array([0, 10, 5], dtype=np.uint64), 0.5, 8)
+
+
+def _drive(ctl_lib, ctl_orc, steps, seed, dense_elems=25_557_032):
+    """Closed loop over the simulated link: both controllers see the same measurements."""
+    bw = W.bandwidth_trace(steps, seed)
+    last_bytes, last_t = 0.0, 0.0
+    for i in range(steps):
+        a = ctl_lib.choose_ratio(last_bytes, last_t, 4.0 * dense_elems, -1.0)
+        b = oracle.choose_ratio(ctl_orc, last_bytes, last_t, 4.0 * dense_elems, -1.0)
+        assert a == b, (i, a, b)
+        s = ctl_lib.state
+        assert (s.ratio, s.btlbw, s.rtprop, s.bdp, s.phase) == \
+               (ctl_orc.ratio, ctl_orc.btlbw, ctl_orc.rtprop, ctl_orc.bdp, ctl_orc.phase)
+        ratio, bits = a
+        last_bytes = float(ratio * dense_elems * (4 + bits / 8))
+        last_t = W.simulated_tx_seconds(last_bytes, bw[i])
+    return ctl_lib.state.ratio
+
+
+@pytest.mark.parametrize("kw", [
+    {}, {"quant_mode": 1}, {"quant_mode": 2, "win_bw": 0, "win_rt": 0},
+    {"startup_max": 0, "win_bw": 3, "win_rt": 128}, {"beta1": 0.25, "rtt_excess": 1.2, "tr_d": 0.5},
+])
+def test_controller_matches_oracle_on_traces(kw):
+    for seed in range(4):
+        lib_ctl = nsml.Controller(**kw)
+        orc_ctl = oracle.ctl_init(oracle.CtlParams(**kw))
+        _drive(lib_ctl, orc_ctl, 400, 1000 + seed)
+
+
+def test_controller_defaults_are_the_printed_constants():
+    p = nsml.default_params()
+    assert (p.alpha, p.beta2, p.floor, p.cap, p.init, p.bdp_frac) == (0.5, 0.01, 0.005, 1.0, 0.01, 0.9)
+    o = oracle.CtlParams()
+    for f, _ in nsml.CtlParams._fields_:
+        assert getattr(p, f) == getattr(o, f), f
+
+
+def test_controller_rejects_bad_parameters():
+    with pytest.raises(nsml.NsmlError):
+        nsml.Controller(win_bw=129)
+    with pytest.raises(nsml.NsmlError):
+        nsml.Controller(alpha=1.5)
+    with pytest.raises(nsml.NsmlError):
+        nsml.Controller(init=2.0)
+
+
+def test_controller_state_is_plain_data():
+    a = nsml.Controller()
+    for i in range(20):
+        a.choose_ratio(1e6 * (i + 1), 0.01 + 1e-3 * i)
+    b = nsml.Controller()
+    C.memmove(C.byref(b.state), C.byref(a.state), C.sizeof(nsml.CtlState))   # checkpoint / resume
+    assert a.choose_ratio(3e6, 0.02) == b.choose_ratio(3e6, 0.02)
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful without a GPU")
+def test_create_fails_loudly_without_gpu():
+    with pytest.raises(nsml.NsmlError) as e:
+        nsml.Context(1024, 1)
+    assert e.value.code == nsml.EHIP
+
+
+def test_create_rejects_bad_arguments():
+    h = C.c_void_p()
+    lib = nsml.raw()
+    assert lib.nsml_create(C.byref(h), 0, 0, 1, 2048) == nsml.EINVAL
+    assert lib.nsml_create(C.byref(h), 0, 1024, 0, 2048) == nsml.EINVAL
+    assert lib.nsml_create(C.byref(h), 0, 1024, 1, 12) == nsml.EINVAL
+    assert lib.nsml_create(None, 0, 1024, 1, 2048) == nsml.EINVAL
+    assert lib.nsml_compress(None, None, None, 0, None, 0, 0.5, 8, None, None, None, None) == nsml.EINVAL
+    assert lib.nsml_decompress(None, None, None, None, 0, None, 0, 0.5, 8, None, None) == nsml.EINVAL

@@ -1,0 +1,188 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on
+the same seeded inputs.  Sizes here span several tiles, ragged tails and unaligned bucket
+starts while the oracle still finishes in seconds."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_16235_amd import binding as nsml
+from paper_2506_16235_amd import workloads as W
+from gpu_util import DEV, Case, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand(n, seed, sigma=1e-3):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return torch.randn(n, generator=g, device=DEV) * sigma
+
+
+def test_cfg1_single_vector():
+    """Configuration 1: 1,048,576 x N(0, 1e-3), ratio 0.01 (k = 10,486), int8, chunk 2048."""
+    g, off = W.cfg1(DEV)
+    c = Case(g, off)
+    K, vb, ns = c.step(0.01, 8)
+    assert (K, vb, ns) == (10486, 10486, 6)
+
+
+@pytest.mark.parametrize("bits", [4, 8, 16, 32])
+def test_ragged_unaligned_buckets(bits):
+    """Bucket starts at every alignment mod 4, an empty bucket, 1-element buckets, a bucket that
+    ends one element into a tile, several tiles per bucket."""
+    sizes = [1, 64, 2048, 0, 4095, 4097, 3, 17889, 8192, 12289, 1, 50001, 7, 131072 + 5]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    say("ragged", bits, n)
+    c = Case(_rand(n, 100 + bits), off, chunk=64)
+    for step, ratio in enumerate((0.3, 0.05, 0.002, 1.0)):
+        c.set_grad(_rand(n, 200 + 10 * bits + step))
+        c.step(ratio, bits)
+
+
+@pytest.mark.parametrize("ratio,bits", [(0.1, 8), (0.01, 4), (0.5, 32), (1.0, 32), (1.0, 4)])
+def test_heavy_ties_and_zeros(ratio, bits):
+    """Magnitudes drawn from a handful of values, 60 % exact zeros of both signs: the threshold
+    sits inside a huge group of equal keys and ties must go to the lowest indices."""
+    n = 300_000
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(7)
+    lv = torch.randint(-3, 4, (n,), generator=gen, device=DEV).float() * 0.25
+    z = torch.rand(n, generator=gen, device=DEV)
+    lv[z < 0.6] = 0.0
+    lv[z < 0.3] = -0.0
+    off = W.offsets_of([100_000, 150_001, 49_999])
+    c = Case(lv, off, chunk=256)
+    c.step(ratio, bits)
+
+
+def test_all_zero_and_constant_buckets():
+    n = 40_000
+    g = torch.zeros(n, device=DEV)
+    g[10_000:20_000] = 3.0
+    g[20_000:30_000] = -1e-30          # subnormal-scale products must not be flushed
+    g[30_000:] = torch.arange(10_000, device=DEV).float() * 1e-42    # subnormals
+    off = W.offsets_of([10_000] * 4)
+    for bits in (8, 4, 16, 32):
+        c = Case(g.clone(), off, chunk=8)
+        c.step(0.01, bits)
+        c.step(0.37, bits)             # residual carried
+
+
+def test_identity_ratio1_bits32():
+    n = 70_001
+    g = _rand(n, 3)
+    c = Case(g, W.offsets_of([n]))
+    idx, val, sc = c.ctx.compress(c.g, c.r, c.off, 1.0, 32)
+    assert torch.equal(idx.view(torch.int32), torch.arange(n, device=DEV, dtype=torch.int32))
+    assert torch.equal(val[:4 * n].view(torch.float32), g)
+    assert torch.count_nonzero(c.r) == 0
+    d = c.ctx.decompress(idx, val, sc, n, c.off, 1.0, 32)
+    assert torch.equal(d, g)
+
+
+def test_error_feedback_conservation_on_gpu():
+    """decompressed + new residual == grad + old residual, exactly, on the GPU's own outputs."""
+    n = 500_000
+    c = Case(_rand(n, 11), W.offsets_of([123_457, 376_543]))
+    c.set_residual(_rand(n, 12).cpu().numpy())
+    acc = c.g + c.r
+    for bits in (4, 8, 16):
+        r0 = c.r.clone()
+        acc = c.g + r0
+        idx, val, sc = c.ctx.compress(c.g, c.r, c.off, 0.02, bits)
+        d = c.ctx.decompress(idx, val, sc, n, c.off, 0.02, bits)
+        assert torch.equal(d + c.r, acc)
+
+
+def test_resnet50_shaped_scaled_ef_steps():
+    """Configuration 2 at 1/16 scale: 161 buckets (107 tiny), sigma_l per layer, ratio 0.05,
+    int8, residual carried over 4 steps with a fresh gradient each step."""
+    sizes = W.scaled_model_like(W.resnet50_sizes(), 16)
+    off = W.offsets_of(sizes)
+    sig = W.resnet50_sigmas()
+    n = int(off[-1])
+    c = None
+    for step in range(4):
+        g = torch.empty(n, device=DEV)
+        for b, nb in enumerate(sizes):
+            g[int(off[b]):int(off[b + 1])] = W._normal(nb, float(sig[b]), W._gen(DEV, W.make_seed(2, step, b)), DEV)
+        if c is None:
+            c = Case(g, off)
+        else:
+            c.set_grad(g)
+        c.step(0.05, 8)
+
+
+@pytest.mark.parametrize("ratio", [0.1, 0.01, 0.001])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_bert_shaped_scaled(ratio, bits):
+    """Configuration 3 at 1/24 scale in every tensor but with the embedding's structure kept:
+    95 % of its rows exactly zero, so at ratio 0.1 the cut falls among the zeros."""
+    sizes = W.scaled_model_like(W.bert_base_sizes(), 24)
+    rows = 30522 // 24
+    sizes[0] = rows * 768
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    g = torch.empty(n, device=DEV)
+    for b, nb in enumerate(sizes):
+        gen = W._gen(DEV, W.make_seed(3, 0, b))
+        if b == 0:
+            emb = g[:nb].view(rows, 768)
+            emb.zero_()
+            nz = torch.randperm(rows, generator=gen, device=DEV)[: rows // 20]
+            emb[nz] = W._laplace(len(nz) * 768, 1e-4, gen, DEV).view(len(nz), 768)
+        else:
+            g[int(off[b]):int(off[b + 1])] = W._laplace(nb, 1e-4, gen, DEV)
+    c = Case(g, off)
+    c.step(ratio, bits)
+
+
+def test_same_input_twice_gives_identical_bytes():
+    """Determinism (the practical race detector): two runs, byte-identical outputs."""
+    sizes = [300_000, 17, 200_003]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    g = (_rand(n, 21) * 1e3).round() * 1e-3        # many ties
+    outs = []
+    for _ in range(2):
+        ctx = nsml.Context(n, 3, 128)
+        r = torch.zeros(n, device=DEV)
+        idx, val, sc = ctx.compress(g, r, off, 0.03, 4)
+        d = ctx.decompress(idx, val, sc, n, off, 0.03, 4)
+        torch.cuda.synchronize()
+        _, K, vb, ns = nsml.payload_layout(off, 0.03, 4, 128)
+        outs.append([x.clone() for x in (idx[:K], val[:vb], sc[:ns], r, d)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_context_reuse_across_layouts_and_ratios():
+    """One context, changing bucket layout, ratio and width between calls."""
+    ctx = nsml.Context(200_000, 8, 64)
+    for i, (sizes, ratio, bits) in enumerate([([200_000], 0.01, 8), ([50_000] * 4, 0.2, 4),
+                                              ([1, 199_999], 0.003, 16), ([200_000], 0.01, 8)]):
+        off = W.offsets_of(sizes)
+        c = Case(_rand(200_000, 40 + i), off, chunk=64, ctx=ctx)
+        c.step(ratio, bits)
+
+
+def test_gpu_argument_errors():
+    ctx = nsml.Context(10_000, 2, 64)
+    g = _rand(10_000, 1)
+    r = torch.zeros_like(g)
+    off = W.offsets_of([10_000])
+    with pytest.raises(nsml.NsmlError) as e:
+        ctx.compress(g, r, off, 0.0, 8)
+    assert e.value.code == nsml.EINVAL
+    with pytest.raises(nsml.NsmlError) as e:
+        ctx.compress(g, r, W.offsets_of([5_000] * 3)[:4], 0.5, 8)          # 3 buckets > max 2
+    assert e.value.code == nsml.ECAP
+    big = _rand(20_000, 2)
+    with pytest.raises(nsml.NsmlError) as e:
+        ctx.compress(big, torch.zeros_like(big), W.offsets_of([20_000]), 0.5, 8)
+    assert e.value.code == nsml.ECAP
+    with pytest.raises(nsml.NsmlError) as e:
+        ctx.compress(g[1:], r[1:], W.offsets_of([9_999]), 0.5, 8)          # misaligned
+    assert e.value.code == nsml.EINVAL
