@@ -4,7 +4,7 @@
 A step = one nsml_compress + one nsml_decompress over one worker's whole synthetic gradient,
 inputs resident in HBM.  Prints ONE JSON line:
   value     GB/s of input fp32 gradient per step (4n / t_step), whole job (one GPU)
-  roofline  the dominant kernel (ef_hist: reads grad and residual, writes the accumulator:
+  roofline  the dominant kernel (ef_emit: reads grad and residual, writes the accumulator:
             12 algorithmic bytes per element) against the 8 TB/s HBM peak, its duration
             measured with HIP events by the library on the stream it is launched on
   cpu_baseline  the CPU oracle timed on this host's cores on a bounded sample of the workload
@@ -173,12 +173,12 @@ def main():
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     kernels = {k: {"launches": c, "avg_ms": round(ms / c, 5)} for k, (c, ms) in prof.items()}
-    ef = prof.get("ef_hist")
+    ef = prof.get("ef_emit")
     ef_ms = ef[1] / ef[0]
     achieved = EF_HIST_BYTES_PER_ELEM * n / (ef_ms * 1e-3) / 1e9
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_ef_hist_{args.workload}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_ef_emit_{args.workload}.json")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
@@ -197,7 +197,7 @@ def main():
                    "distinct_gradients": len(grads), "residual": "carried across steps"},
         "hbm_roofline_frac": round(floor_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "floor_bytes_per_step": floor_bytes,
-        "roofline": {"kernel": "ef_hist", "bound": "hbm", "achieved": round(achieved, 1),
+        "roofline": {"kernel": "ef_emit", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "avg_ms": round(ef_ms, 5),
                      "algorithmic_bytes_per_launch": EF_HIST_BYTES_PER_ELEM * n},

@@ -133,8 +133,8 @@ typedef struct nsml_ctx nsml_ctx;
 
 /* Allocate a context and its device workspace on GPU `device` for gradients of up to max_n
  * elements in up to max_buckets buckets, quantized in chunks of `chunk` survivors (2048 in
- * the benchmark configurations; a positive multiple of 8).  Workspace: about 4 bytes per
- * element of max_n plus 33 KiB per bucket.  NSML_EHIP if the device or its memory is not
+ * the benchmark configurations; a positive multiple of 8).  Workspace: about 6 bytes per
+ * element of max_n (survivor values, candidate staging) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
  * available (there is no CPU fallback). */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 int nsml_destroy(nsml_ctx *ctx);
@@ -175,7 +175,7 @@ int nsml_decompress(nsml_ctx *ctx, const uint32_t *idx, const void *val, const f
 
 /* ------------------------------------------------------------------ measurement */
 
-#define NSML_MAX_KERNELS 16
+#define NSML_MAX_KERNELS 32
 
 /* When enabled, every kernel launch of the context is bracketed by HIP events on the caller's
  * stream.  nsml_profile_read synchronises those events and returns, for each kernel id,
@@ -184,6 +184,10 @@ int nsml_decompress(nsml_ctx *ctx, const uint32_t *idx, const void *val, const f
  * kept between reads. */
 int nsml_profile_enable(nsml_ctx *ctx, int on);
 int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
+/* Diagnostics for the last nsml_compress of the context: how many non-empty buckets were
+ * decided from the single streaming pass (fast) and how many needed the extra dense passes
+ * (fallback).  Both give identical results.  Synchronises the device. */
+int nsml_path_stats(nsml_ctx *ctx, uint32_t *fast_buckets, uint32_t *fallback_buckets);
 /* Name of kernel id (NULL beyond the last). */
 const char *nsml_kernel_name(int id);
 

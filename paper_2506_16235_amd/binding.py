@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libnsml.so")
 
 OK, EINVAL, ECAP, EHIP, ENOTIMPL, ENOMEM = 0, -1, -2, -3, -4, -5
-MAX_KERNELS = 16
+MAX_KERNELS = 32
 CTL_MAX_WIN = 128
 
 if not os.path.exists(LIB_PATH):
@@ -62,6 +62,8 @@ _lib.nsml_compress.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, 
 _lib.nsml_decompress.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp]
 _lib.nsml_profile_enable.argtypes = [_vp, _i32]
 _lib.nsml_profile_read.argtypes = [_vp, _vp, _vp]
+_lib.nsml_path_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
+_lib.nsml_path_stats.restype = _i32
 _lib.nsml_kernel_name.argtypes = [_i32]
 _lib.nsml_kernel_name.restype = C.c_char_p
 for _f in ("nsml_ctl_default_params", "nsml_ctl_init", "nsml_choose_ratio", "nsml_payload_layout",
@@ -207,6 +209,12 @@ class Context:
                                   _ptr(out), _stream(self.device))
         _check(rc, "nsml_decompress", self._h)
         return out
+
+    def path_stats(self):
+        """-> (fast buckets, fallback buckets) of the last compress call (synchronises)."""
+        a, b = _u32(), _u32()
+        _check(_lib.nsml_path_stats(self._h, C.byref(a), C.byref(b)), "nsml_path_stats", self._h)
+        return a.value, b.value
 
     def profile_enable(self, on: bool = True):
         _check(_lib.nsml_profile_enable(self._h, 1 if on else 0), "nsml_profile_enable", self._h)

@@ -7,27 +7,35 @@
  * streaming pass bound by HBM bandwidth, so the work is organised around coalesced 16-byte
  * accesses, LDS histograms and 64-lane ballots, not MFMA.
  *
- * Selection is a three-level radix select on the 31-bit magnitude key
- * (binary32 pattern with the sign cleared):  12 + 12 + 7 bits.
- *   ef_hist   acc = grad + residual (written over residual) + level-0 histogram   12 B/elem
- *   pick0     per bucket: level-0 bin that holds the k-th largest key
- *   refine1/2 histogram of the next digit over elements inside the chosen bin      4 B/elem each
- *   pick1/2   -> exact threshold key T_b and the number e_b of elements equal to T_b to admit
- *   count     per 4096-element tile: #(key > T), #(key == T)                       4 B/elem
- *   scan      per bucket exclusive scan of the tile counts
- *   write     survivors to their final, index-ordered slots (idx, value)           4 B/elem
+ * Selection is an exact radix select on the 31-bit magnitude key (binary32 pattern with the
+ * sign cleared), digits of 12 + 12 + 7 bits, arranged so that the gradient is read ONCE:
+ *
+ *   sample    level-0 histogram of a 1/64 sample of grad + residual (small buckets: all of it)
+ *   predict   per bucket: a level-0 digit whose lower edge L_b is, with a wide margin, below
+ *             the k-th largest key
+ *   ef_emit   acc = grad + residual (written over residual), exact level-0 histogram, and
+ *             every element with key >= L_b appended, in index order, to a per-wavefront
+ *             staging segment ("candidates")                                  12 B/element
+ *   plan      per bucket: exact level-0 digit b0 of the k-th key; the candidates are a
+ *             superset of the top k iff digit(L_b) <= b0 and no staging segment overflowed
+ *   crefine1/2, pick1/2   remaining digits from the candidates only -> threshold key T_b and
+ *             e_b = how many elements equal to T_b are admitted (lowest indices first)
+ *   ccount, cscan, cwrite  survivors to their final, index-ordered slots
+ *   fb_*      buckets whose candidates are not a superset (huge groups of equal keys, ratio
+ *             near 1, an unlucky sample) take the same steps over the dense accumulator
+ *             instead: four more reads of that bucket only.  Results are identical.
  *   quant     per chunk of survivors: absmax scale, codes, packing, residual update
- *   decomp    payload -> dense, each output line written once, tile staged in LDS  4 B/elem
+ *   decomp    payload -> dense, each output line written once, tile staged in LDS
  *
  * Geometry: a bucket [lo, hi) is cut into tiles of 4096 elements starting at lo rounded down
  * to a multiple of 4, so every 16-byte access is aligned; elements of an edge tile outside
- * [lo, hi) are masked.  A workgroup (256 threads = 4 wavefronts) owns a span of consecutive
- * tiles of one bucket.  Inside a tile, thread t owns the four quads (u*256 + t)*4, u = 0..3,
- * which makes every load instruction of a wavefront one contiguous 1 KiB run.
+ * [lo, hi) are masked.  A workgroup (256 threads = 4 wavefronts) owns a span of up to 16
+ * consecutive tiles of one bucket.
  */
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -40,37 +48,66 @@
 namespace {
 
 constexpr int WG = 256;
-constexpr int TILE = 4096;
+constexpr int TILE = 4096;        /* elements per tile */
+constexpr int WTILE = 1024;       /* elements one wavefront covers per iteration in ef_emit */
 constexpr int NB0 = 4096, NB1 = 4096, NB2 = 128;
 constexpr int SH0 = 19;   /* key >> 19         : level-0 digit (sign-less exponent + 4 mantissa bits) */
 constexpr int SH1 = 7;    /* (key >> 7) & 4095 : level-1 digit;  key & 127 : level-2 digit */
 constexpr int MAX_SPAN_TILES = 16;
+constexpr uint32_t NONE = 0xFFFFFFFFu;
+constexpr uint32_t SAMPLE_ALL_BELOW = 262144;  /* buckets smaller than this are sampled in full */
+constexpr uint32_t SAMPLE_STRIDE = 64;         /* larger ones: 32 elements out of every 2048 */
+constexpr uint32_t RUNS_PER_WG = 512;          /* sample runs (32 elements each) per workgroup */
+constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
 
 enum KernelId {
-    KID_SETUP = 0, KID_CLEAR, KID_EF_HIST, KID_PICK0, KID_REFINE1, KID_PICK1, KID_REFINE2,
-    KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE, KID_QUANT, KID_DECOMP, KID_N
+    KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN,
+    KID_CREFINE1, KID_PICK1, KID_CREFINE2, KID_PICK2, KID_CCOUNT, KID_CSCAN, KID_CWRITE,
+    KID_FB_PLAN, KID_FB_REFINE1, KID_FB_PICK1, KID_FB_REFINE2, KID_FB_PICK2, KID_FB_COUNT,
+    KID_FB_SCAN, KID_FB_WRITE, KID_QUANT, KID_DECOMP, KID_N
 };
 const char *const kKernelNames[KID_N] = {
-    "setup", "clear", "ef_hist", "pick0", "refine1", "pick1", "refine2",
-    "pick2", "count", "scan", "write", "quant", "decomp"
+    "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan",
+    "crefine1", "pick1", "crefine2", "pick2", "ccount", "cscan", "cwrite",
+    "fb_plan", "fb_refine1", "fb_pick1", "fb_refine2", "fb_pick2", "fb_count",
+    "fb_scan", "fb_write", "quant", "decomp"
 };
 static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
 
-/* Device-resident tables of one (bucket layout, ratio, bits) combination. */
+/* Device-resident tables.  Layout part: fixed by the bucket offsets.  Call part: fixed by
+ * (ratio, bits).  State part: rewritten by every compress call. */
 struct Tables {
-    const uint64_t *off;    /* B+1 bucket offsets */
-    const uint32_t *tile0;  /* B+1 prefix of tile counts */
-    const uint32_t *span0;  /* B+1 prefix of span counts */
-    uint32_t *k;            /* B   survivors per bucket */
-    uint64_t *P;            /* B+1 prefix of k */
-    uint64_t *V;            /* B+1 prefix of value bytes */
-    uint64_t *S;            /* B+1 prefix of scale counts */
-    uint64_t *C;            /* B+1 prefix of chunk counts (all widths) */
-    uint32_t *T;            /* B   threshold key, refined level by level */
-    uint32_t *need;         /* B   how many more to take at the current level */
+    const uint64_t *off;     /* B+1 bucket offsets */
+    const uint32_t *tile0;   /* B+1 prefix of tile counts */
+    const uint32_t *span0;   /* B+1 prefix of span counts */
+    const uint32_t *samp0;   /* B+1 prefix of sample workgroups */
+    const uint32_t *span_b;  /* n_spans: bucket of each span */
+    uint32_t *k;             /* B   survivors per bucket */
+    uint64_t *P;             /* B+1 prefix of k */
+    uint64_t *V;             /* B+1 prefix of value bytes */
+    uint64_t *S;             /* B+1 prefix of scale counts */
+    uint64_t *C;             /* B+1 prefix of chunk counts (all widths) */
+    uint32_t *T;             /* B   threshold key, refined level by level */
+    uint32_t *need;          /* B   how many more to take at the current level */
+    uint32_t *T0, *need0;    /* B   T and need as they stood after level 0 (for the fallback) */
+    uint32_t *L;             /* B   candidates are the elements with key >= L (NONE: no candidates) */
+    uint32_t *fast;          /* B   1: the candidates decide the bucket, 0: the dense fallback does */
+    uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
+    uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
     uint32_t B;
-    uint32_t spanT;         /* tiles per span */
+    uint32_t n_spans;
+    uint32_t spanT;          /* tiles per span */
     uint32_t chunk;
+};
+
+/* Candidate staging: subspan ss = 4 * span + wavefront owns entries [ss * cap, ss * cap + cnt[ss]) */
+struct Cand {
+    uint32_t *idx;   /* bucket-local index */
+    float *val;      /* accumulator value */
+    uint32_t *cnt;   /* entries per subspan */
+    uint32_t *G;     /* per subspan: #(key > T), later its exclusive prefix inside the bucket */
+    uint32_t *E;     /* per subspan: #(key == T), later its exclusive prefix */
+    uint32_t cap;    /* entries per subspan = spanT * 256 (a quarter of the elements it covers) */
 };
 
 typedef float f4 __attribute__((ext_vector_type(4)));   /* one aligned 16-byte access */
@@ -97,19 +134,26 @@ struct SpanGeo {
     uint64_t base;     /* aligned global element index where the first tile starts */
 };
 
-__device__ __forceinline__ SpanGeo span_geo(const Tables &t, uint32_t s)
+/* span number si of bucket b */
+__device__ __forceinline__ SpanGeo span_geo_b(const Tables &t, uint32_t b, uint32_t si)
 {
     SpanGeo g;
-    g.b = find_bucket<uint32_t>(t.span0, t.B, s);
-    const uint32_t si = s - t.span0[g.b];
-    g.lo = t.off[g.b];
-    g.hi = t.off[g.b + 1];
-    const uint32_t tiles_b = t.tile0[g.b + 1] - t.tile0[g.b];
+    g.b = b;
+    g.lo = t.off[b];
+    g.hi = t.off[b + 1];
+    const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
     const uint32_t first = si * t.spanT;
     g.ntiles = min(t.spanT, tiles_b - first);
-    g.tile_g = t.tile0[g.b] + first;
+    g.tile_g = t.tile0[b] + first;
     g.base = (g.lo & ~3ull) + (uint64_t)first * TILE;
     return g;
+}
+
+/* global span s */
+__device__ __forceinline__ SpanGeo span_geo(const Tables &t, uint32_t s)
+{
+    const uint32_t b = t.span_b[s];
+    return span_geo_b(t, b, s - t.span0[b]);
 }
 
 /* Load the quad at aligned element index gi, masking what lies outside [lo, hi).
@@ -179,6 +223,14 @@ __global__ __launch_bounds__(WG) void k_setup(Tables t, double ratio, int bits)
     }
 }
 
+/* span -> bucket map, once per bucket layout */
+__global__ __launch_bounds__(WG) void k_spanmap(const uint32_t *__restrict__ span0, uint32_t B,
+                                                uint32_t n_spans, uint32_t *__restrict__ span_b)
+{
+    const uint32_t s = blockIdx.x * WG + threadIdx.x;
+    if (s < n_spans) span_b[s] = find_bucket<uint32_t>(span0, B, s);
+}
+
 __global__ __launch_bounds__(WG) void k_clear(uint32_t *__restrict__ p, uint64_t n)
 {
     const uint64_t stride = (uint64_t)gridDim.x * WG;
@@ -189,7 +241,8 @@ __global__ __launch_bounds__(WG) void k_clear(uint32_t *__restrict__ p, uint64_t
 
 /* Add the four level digits of a quad to an LDS histogram.  When every lane of the wavefront
  * carries the same digit in all four slots (runs of zeros, saturated buckets) one lane adds
- * the whole count: same-address LDS atomics of a wavefront serialise. */
+ * the whole count: same-address LDS atomics of a wavefront serialise.  All 64 lanes must be
+ * active. */
 __device__ __forceinline__ void hist_quad_full(uint32_t *h, uint32_t d0, uint32_t d1,
                                                uint32_t d2, uint32_t d3)
 {
@@ -210,106 +263,6 @@ __device__ __forceinline__ void hist_flush(const uint32_t *h, uint32_t *__restri
     }
 }
 
-/* acc = grad + residual over a span, written over residual, plus the level-0 histogram.
- * (Sec. 4.2 Step 3: what top-k filters out is accumulated locally; the add is that.) */
-__global__ __launch_bounds__(WG) void k_ef_hist(const float *__restrict__ g, float *__restrict__ r,
-                                                Tables t, uint32_t *__restrict__ hist0)
-{
-    __shared__ uint32_t h[NB0];
-    const uint32_t tid = threadIdx.x;
-    for (int i = tid; i < NB0; i += WG) h[i] = 0;
-    const SpanGeo s = span_geo(t, blockIdx.x);
-    __syncthreads();
-    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-        const uint64_t tb = s.base + (uint64_t)ti * TILE;
-        if (tb >= s.lo && tb + TILE <= s.hi) {
-            f4 gv[4], rv[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi));
-                rv[u] = *reinterpret_cast<const f4 *>(r + gi);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-                f4 a;
-                a.x = __fadd_rn(gv[u].x, rv[u].x); a.y = __fadd_rn(gv[u].y, rv[u].y);
-                a.z = __fadd_rn(gv[u].z, rv[u].z); a.w = __fadd_rn(gv[u].w, rv[u].w);
-                *reinterpret_cast<f4 *>(r + gi) = a;
-                hist_quad_full(h, keyof(a.x) >> SH0, keyof(a.y) >> SH0, keyof(a.z) >> SH0,
-                               keyof(a.w) >> SH0);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint64_t i = gi + j;
-                    if (i >= s.lo && i < s.hi) {
-                        const float a = __fadd_rn(g[i], r[i]);
-                        r[i] = a;
-                        atomicAdd(&h[keyof(a) >> SH0], 1u);
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
-    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
-}
-
-/* Histogram of the next digit over the elements whose higher digits equal the prefix found
- * so far (LEVEL 1: 12-bit prefix in T, digit = bits 18..7; LEVEL 2: 24-bit prefix, bits 6..0). */
-template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_refine(const float *__restrict__ r, Tables t,
-                                               uint32_t *__restrict__ hist)
-{
-    constexpr int NB = LEVEL == 1 ? NB1 : NB2;
-    constexpr int PSH = LEVEL == 1 ? SH0 : SH1;          /* key >> PSH is the prefix */
-    constexpr int DSH = LEVEL == 1 ? SH1 : 0;
-    constexpr uint32_t DMASK = NB - 1;
-    __shared__ uint32_t h[NB];
-    const uint32_t tid = threadIdx.x;
-    for (int i = tid; i < NB; i += WG) h[i] = 0;
-    const SpanGeo s = span_geo(t, blockIdx.x);
-    const uint32_t prefix = t.T[s.b];
-    __syncthreads();
-    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-        const uint64_t tb = s.base + (uint64_t)ti * TILE;
-        const bool interior = tb >= s.lo && tb + TILE <= s.hi;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-            float x[4];
-            const uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-            uint32_t d[4];
-            uint32_t hit = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t key = keyof(x[j]);
-                d[j] = (key >> DSH) & DMASK;
-                if (((m >> j) & 1u) && (key >> PSH) == prefix) hit |= 1u << j;
-            }
-            if (interior) {
-                /* all lanes active here: whole-wavefront shortcut for runs of equal keys */
-                const uint32_t f = __builtin_amdgcn_readfirstlane(d[0]);
-                const bool same = hit == 0xFu && d[0] == f && d[1] == f && d[2] == f && d[3] == f;
-                if (__all(same)) {
-                    if ((tid & 63) == 0) atomicAdd(&h[f], 256u);
-                    continue;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((hit >> j) & 1u) atomicAdd(&h[d[j]], 1u);
-        }
-    }
-    __syncthreads();
-    hist_flush(h, hist + (uint64_t)s.b * NB, NB);
-}
-
 /* Inclusive scan over the 256 threads of a workgroup (tmp: 256 words of LDS). */
 __device__ __forceinline__ uint32_t block_incl_scan(uint32_t x, uint32_t *tmp)
 {
@@ -327,176 +280,569 @@ __device__ __forceinline__ uint32_t block_incl_scan(uint32_t x, uint32_t *tmp)
     return x;
 }
 
-/* Per bucket: walk one level's histogram from the top digit down to the digit that holds the
- * want-th largest key; append it to the prefix; what is still wanted inside it goes to need. */
-template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist)
+/* A histogram row seen from the top digit down: thread 0 owns the highest digits. */
+template <int NB>
+struct DigitWalk {
+    static constexpr int PER = NB >= WG ? NB / WG : 1;
+    uint32_t c[PER];
+    uint32_t sum, incl, total;
+    int top;
+
+    /* every thread of the workgroup must call this (it synchronises) */
+    __device__ __forceinline__ void load(const uint32_t *__restrict__ hb, uint32_t *tmp)
+    {
+        top = NB - 1 - (int)threadIdx.x * PER;
+        sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int d = top - i;
+            c[i] = d >= 0 ? hb[d] : 0u;
+            sum += c[i];
+        }
+        incl = block_incl_scan(sum, tmp);
+        total = tmp[WG - 1];
+        __syncthreads();
+    }
+    /* The digit holding the want-th largest entry (1 <= want <= total): exactly one thread
+     * returns true, with the digit, the number of entries in higher digits, and the number
+     * in the digit itself. */
+    __device__ __forceinline__ bool find(uint32_t want, uint32_t &digit, uint32_t &above,
+                                         uint32_t &at) const
+    {
+        const uint32_t before = incl - sum;
+        if (!(before < want && want <= incl)) return false;
+        uint32_t acc = before;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (acc + c[i] >= want) { digit = (uint32_t)(top - i); above = acc; at = c[i]; return true; }
+            acc += c[i];
+        }
+        return false;
+    }
+};
+
+/* ------------------------------------------------------------------ sample / predict */
+
+/* Level-0 histogram of a sample of acc = grad + residual: runs of 32 consecutive elements,
+ * every run of a small bucket, one run in 64 of a large one. */
+__global__ __launch_bounds__(WG) void k_sample(const float *__restrict__ g, const float *__restrict__ r,
+                                               Tables t, uint32_t *__restrict__ hist_s)
 {
-    constexpr int NB = LEVEL == 2 ? NB2 : NB0;
-    constexpr int PER = NB >= WG ? NB / WG : 1;
+    __shared__ uint32_t h[NB0];
+    const uint32_t tid = threadIdx.x;
+    for (int i = tid; i < NB0; i += WG) h[i] = 0;
+    const uint32_t b = find_bucket<uint32_t>(t.samp0, t.B, blockIdx.x);
+    const uint32_t wi = blockIdx.x - t.samp0[b];
+    const uint64_t lo = t.off[b], hi = t.off[b + 1];
+    const uint64_t a0 = lo & ~3ull;
+    const uint64_t stride = (hi - lo) < SAMPLE_ALL_BELOW ? 1 : SAMPLE_STRIDE;
+    const uint64_t run_elems = 32ull * stride;
+    const uint64_t n_runs = (hi - a0 + run_elems - 1) / run_elems;
+    __syncthreads();
+#pragma unroll 4
+    for (uint32_t i = 0; i < RUNS_PER_WG / 32; ++i) {
+        const uint64_t run = (uint64_t)wi * RUNS_PER_WG + i * 32 + (tid >> 3);
+        if (run < n_runs) {
+            const uint64_t gi = a0 + run * run_elems + (tid & 7u) * 4;
+            float x[4], y[4];
+            const uint32_t m = load_quad(g, gi, lo, hi, x);
+            load_quad(r, gi, lo, hi, y);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((m >> j) & 1u) atomicAdd(&h[keyof(__fadd_rn(x[j], y[j])) >> SH0], 1u);
+        }
+    }
+    __syncthreads();
+    hist_flush(h, hist_s + (uint64_t)b * NB0, NB0);
+}
+
+/* Per bucket: choose the candidate bound L_b from the sample histogram.  The sample count
+ * above the true k-th key is binomial with mean ks = k * m / n; asking for ks + 4 sqrt(ks) + 4
+ * sampled entries above L_b leaves the candidates short of k only a few times in 1e5 buckets,
+ * and then the dense fallback still gives the exact result. */
+__global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__restrict__ hist_s,
+                                                int force_dense)
+{
+    __shared__ uint32_t tmp[WG];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint64_t nb = t.off[b + 1] - t.off[b];
+    const uint32_t k = t.k[b];
+    if (nb == 0 || force_dense) {
+        if (tid == 0) { t.L[b] = NONE; t.fast[b] = nb == 0 ? 1u : 0u; }
+        return;
+    }
+    DigitWalk<NB0> w;
+    w.load(hist_s + (uint64_t)b * NB0, tmp);
+    const uint32_t m = w.total;
+    const bool exact = nb < SAMPLE_ALL_BELOW;
+    const double ks = (double)k * (double)m / (double)nb;
+    const double want_d = exact ? (double)k : ceil(ks + 4.0 * sqrt(ks) + 4.0);
+    const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
+    if (m == 0 || want_d > (double)m || (double)k > 0.5 * cap_b) {
+        /* not enough sample above any bound, or k too large for the staging area */
+        if (tid == 0) { t.L[b] = NONE; t.fast[b] = 0u; }
+        return;
+    }
+    uint32_t digit, above, at;
+    if (w.find((uint32_t)want_d, digit, above, at)) {
+        const double est = (double)(above + at) * (double)nb / (double)m;
+        const bool fits = est <= 0.8 * cap_b;
+        t.L[b] = fits ? (digit << SH0) : NONE;
+        t.fast[b] = fits ? 1u : 0u;
+    }
+}
+
+/* ------------------------------------------------------------------ the streaming pass */
+
+/* One row of the streaming pass: 64 lanes x 4 consecutive elements (one contiguous 1 KiB).
+ * a[] is the accumulator quad of this lane, m its validity mask, li the bucket-local index
+ * of a[0].  Stores the accumulator, counts its level-0 digits and appends candidates. */
+template <bool INTERIOR, bool EMIT>
+__device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const float (&a)[4],
+                                       uint32_t m, uint32_t li, uint32_t *h, uint32_t L,
+                                       const Cand &c, uint64_t cbase, uint32_t &wcount, uint64_t lt)
+{
+    uint32_t key[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) key[j] = keyof(a[j]);
+    if (INTERIOR) {
+        f4 v; v.x = a[0]; v.y = a[1]; v.z = a[2]; v.w = a[3];
+        *reinterpret_cast<f4 *>(r + gi) = v;
+        hist_quad_full(h, key[0] >> SH0, key[1] >> SH0, key[2] >> SH0, key[3] >> SH0);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if ((m >> j) & 1u) { r[gi + j] = a[j]; atomicAdd(&h[key[j] >> SH0], 1u); }
+    }
+    if (EMIT) {
+        bool f[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = ((m >> j) & 1u) && key[j] >= L;
+        if (__ballot(f[0] | f[1] | f[2] | f[3]) != 0ull) {
+            uint64_t bal[4];
+            uint32_t pos = wcount;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { bal[j] = __ballot(f[j]); pos += __popcll(bal[j] & lt); }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (f[j]) {
+                    if (pos < c.cap) { c.idx[cbase + pos] = li + j; c.val[cbase + pos] = a[j]; }
+                    ++pos;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wcount += __popcll(bal[j]);
+        }
+    }
+}
+
+/* acc = grad + residual over a span, written over residual (Sec. 4.2 Step 3: what top-k
+ * filters out is accumulated locally; the add is that), the exact level-0 histogram, and the
+ * candidates.  Each wavefront owns a contiguous quarter of the span and its own staging
+ * segment, so candidates come out in index order without any cross-wavefront exchange. */
+template <bool EMIT>
+__global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
+                                                Tables t, uint32_t *__restrict__ hist0, Cand c)
+{
+    __shared__ uint32_t h[NB0];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < NB0; i += WG) h[i] = 0;
+    const SpanGeo s = span_geo(t, blockIdx.x);
+    const uint32_t L = EMIT ? t.L[s.b] : NONE;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    const uint32_t ss = blockIdx.x * 4 + wave;
+    const uint64_t cbase = (uint64_t)ss * c.cap;
+    uint32_t wcount = 0;
+    __syncthreads();
+    /* this wavefront's wave-tiles: [wave * spanT, (wave + 1) * spanT) of the span's 4 * ntiles */
+    const uint32_t wt0 = wave * t.spanT;
+    const uint32_t wt1 = min(s.ntiles * 4u, wt0 + t.spanT);
+    for (uint32_t wt = wt0; wt < wt1; ++wt) {
+        const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+        if (wb >= s.lo && wb + WTILE <= s.hi) {
+            f4 gv[4], rv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi));
+                rv[u] = *reinterpret_cast<const f4 *>(r + gi);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                float a[4];
+                a[0] = __fadd_rn(gv[u].x, rv[u].x); a[1] = __fadd_rn(gv[u].y, rv[u].y);
+                a[2] = __fadd_rn(gv[u].z, rv[u].z); a[3] = __fadd_rn(gv[u].w, rv[u].w);
+                ef_row<true, EMIT>(r, gi, a, 0xFu, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                float x[4], y[4], a[4];
+                const uint32_t m = load_quad(g, gi, s.lo, s.hi, x);
+                load_quad(r, gi, s.lo, s.hi, y);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a[j] = __fadd_rn(x[j], y[j]);
+                ef_row<false, EMIT>(r, gi, a, m, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+            }
+        }
+    }
+    if (EMIT && lane == 0) {
+        c.cnt[ss] = min(wcount, c.cap);
+        if (wcount > c.cap) t.ovf[s.b] = 1u;
+    }
+    __syncthreads();
+    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
+}
+
+/* Per bucket: exact level-0 digit of the k-th largest key, and whether the candidates can
+ * decide the bucket. */
+__global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restrict__ hist0)
+{
+    __shared__ uint32_t tmp[WG];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t want = t.k[b];
+    if (want == 0) {                       /* empty bucket: nothing can match */
+        if (tid == 0) { t.T[b] = t.T0[b] = NONE; t.need[b] = t.need0[b] = 0; }
+        return;
+    }
+    DigitWalk<NB0> w;
+    w.load(hist0 + (uint64_t)b * NB0, tmp);
+    uint32_t digit, above, at;
+    if (w.find(want, digit, above, at)) {
+        t.T[b] = t.T0[b] = digit;
+        t.need[b] = t.need0[b] = want - above;
+        const uint32_t L = t.L[b];
+        if (t.fast[b] && (L == NONE || (L >> SH0) > digit || t.ovf[b])) t.fast[b] = 0u;
+    }
+}
+
+/* ------------------------------------------------------------------ candidate path */
+
+/* Next-digit histogram over the candidates that carry the prefix found so far (LEVEL 1:
+ * 12-bit prefix, digit = key bits 18..7; LEVEL 2: 24-bit prefix, digit = bits 6..0).  One
+ * wavefront per subspan; the matching entries are few, so they go straight to global atomics. */
+template <int LEVEL>
+__global__ __launch_bounds__(WG) void k_crefine(Tables t, Cand c, uint32_t *__restrict__ hist)
+{
+    constexpr int NB = LEVEL == 1 ? NB1 : NB2;
+    constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
+    constexpr int DSH = LEVEL == 1 ? SH1 : 0;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t n_ss = t.n_spans * 4;
+    for (uint32_t ss = blockIdx.x * 4 + (threadIdx.x >> 6); ss < n_ss; ss += gridDim.x * 4) {
+        const uint32_t b = t.span_b[ss >> 2];
+        if (!t.fast[b]) continue;
+        const uint32_t cnt = c.cnt[ss], prefix = t.T[b];
+        const uint64_t base = (uint64_t)ss * c.cap;
+        for (uint32_t i = lane; i < cnt; i += 64) {
+            const uint32_t key = keyof(c.val[base + i]);
+            if ((key >> PSH) == prefix) atomicAdd(&hist[(uint64_t)b * NB + ((key >> DSH) & (NB - 1))], 1u);
+        }
+    }
+}
+
+/* Per bucket, levels 1 and 2: walk the level's histogram to the digit holding the need-th
+ * entry, append it to the prefix.  mode 1: buckets on the candidate path, mode 0: fallback.
+ * A candidate histogram with fewer entries than needed means the candidates were not a
+ * superset after all; the bucket is handed to the fallback untouched. */
+template <int LEVEL>
+__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist, uint32_t mode)
+{
+    constexpr int NB = LEVEL == 2 ? NB2 : NB1;
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    const uint32_t want = LEVEL == 0 ? t.k[b] : t.need[b];
-    if (want == 0) {                       /* empty bucket: nothing can match */
-        if (tid == 0) { t.T[b] = 0xFFFFFFFFu; t.need[b] = 0; }
+    if (t.fast[b] != mode) return;
+    const uint32_t want = t.need[b];
+    if (want == 0) return;
+    DigitWalk<NB> w;
+    w.load(hist + (uint64_t)b * NB, tmp);
+    if (w.total < want) {
+        if (tid == 0) t.fast[b] = 0u;     /* only reachable on the candidate path */
         return;
     }
-    const uint32_t *hb = hist + (uint64_t)b * NB;
-    /* thread 0 owns the highest digits */
-    const int top = NB - 1 - (int)tid * PER;
-    uint32_t c[PER];
-    uint32_t sum = 0;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int d = top - i;
-        c[i] = d >= 0 ? hb[d] : 0u;
-        sum += c[i];
-    }
-    const uint32_t incl = block_incl_scan(sum, tmp);
-    const uint32_t above = incl - sum;
-    if (above < want && want <= incl) {
-        uint32_t acc = above;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            if (acc + c[i] >= want) {
-                const uint32_t d = (uint32_t)(top - i);
-                t.T[b] = LEVEL == 0 ? d : ((t.T[b] << BITS) | d);
-                t.need[b] = want - acc;
-                break;
-            }
-            acc += c[i];
-        }
+    uint32_t digit, above, at;
+    if (w.find(want, digit, above, at)) {
+        t.T[b] = (t.T[b] << BITS) | digit;
+        t.need[b] = want - above;
     }
 }
 
-/* ------------------------------------------------------------------ compaction */
-
-/* Per tile: how many keys exceed the threshold, how many equal it. */
-__global__ __launch_bounds__(WG) void k_count(const float *__restrict__ r, Tables t,
-                                              uint32_t *__restrict__ tG, uint32_t *__restrict__ tE)
+/* Per subspan: how many candidates exceed the threshold, how many equal it. */
+__global__ __launch_bounds__(WG) void k_ccount(Tables t, Cand c)
 {
-    __shared__ uint32_t cnt[MAX_SPAN_TILES][2];
-    const uint32_t tid = threadIdx.x;
-    if (tid < MAX_SPAN_TILES * 2) (&cnt[0][0])[tid] = 0;
-    const SpanGeo s = span_geo(t, blockIdx.x);
-    const uint32_t T = t.T[s.b];
-    __syncthreads();
-    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-        const uint64_t tb = s.base + (uint64_t)ti * TILE;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t n_ss = t.n_spans * 4;
+    for (uint32_t ss = blockIdx.x * 4 + (threadIdx.x >> 6); ss < n_ss; ss += gridDim.x * 4) {
+        const uint32_t b = t.span_b[ss >> 2];
+        if (!t.fast[b]) continue;
+        const uint32_t cnt = c.cnt[ss], T = t.T[b];
+        const uint64_t base = (uint64_t)ss * c.cap;
         uint32_t ng = 0, ne = 0;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-            float x[4];
-            const uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t key = keyof(x[j]);
-                const bool ok = (m >> j) & 1u;
-                ng += (ok && key > T) ? 1u : 0u;
-                ne += (ok && key == T) ? 1u : 0u;
-            }
+        for (uint32_t i = lane; i < cnt; i += 64) {
+            const uint32_t key = keyof(c.val[base + i]);
+            ng += key > T ? 1u : 0u;
+            ne += key == T ? 1u : 0u;
         }
-        /* wavefront sum by shuffles, then one LDS atomic per wavefront */
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            ng += __shfl_xor(ng, d, 64);
-            ne += __shfl_xor(ne, d, 64);
-        }
-        if ((tid & 63) == 0) { atomicAdd(&cnt[ti][0], ng); atomicAdd(&cnt[ti][1], ne); }
+        for (int d = 32; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
+        if (lane == 0) { c.G[ss] = ng; c.E[ss] = ne; }
     }
-    __syncthreads();
-    if (tid < s.ntiles) { tG[s.tile_g + tid] = cnt[tid][0]; tE[s.tile_g + tid] = cnt[tid][1]; }
 }
 
-/* Per bucket: exclusive scan, in place, of the per-tile counts. */
-__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ tG,
-                                             uint32_t *__restrict__ tE)
+/* Per bucket: exclusive scan, in place, of per-unit counts (units: the bucket's subspans on
+ * the candidate path, its tiles on the fallback path). */
+__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ G, uint32_t *__restrict__ E,
+                                             uint32_t mode)
 {
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    const uint32_t t0 = t.tile0[b], t1 = t.tile0[b + 1];
+    if (t.fast[b] != mode) return;
+    const uint32_t t0 = mode ? t.span0[b] * 4 : t.tile0[b];
+    const uint32_t t1 = mode ? t.span0[b + 1] * 4 : t.tile0[b + 1];
     uint32_t carry_g = 0, carry_e = 0;
     for (uint32_t base = t0; base < t1; base += WG) {
         const uint32_t i = base + tid;
-        const uint32_t g = i < t1 ? tG[i] : 0u, e = i < t1 ? tE[i] : 0u;
+        const uint32_t g = i < t1 ? G[i] : 0u, e = i < t1 ? E[i] : 0u;
         const uint32_t ig = block_incl_scan(g, tmp);
         const uint32_t tot_g = tmp[WG - 1];
         __syncthreads();
         const uint32_t ie = block_incl_scan(e, tmp);
         const uint32_t tot_e = tmp[WG - 1];
         __syncthreads();
-        if (i < t1) { tG[i] = carry_g + ig - g; tE[i] = carry_e + ie - e; }
+        if (i < t1) { G[i] = carry_g + ig - g; E[i] = carry_e + ie - e; }
         carry_g += tot_g;
         carry_e += tot_e;
     }
 }
 
-/* Per tile: write the survivors (key > T, or key == T and among the first e_b equal ones of
- * the bucket in index order) to their final slots, in ascending index order. */
-__global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Tables t,
-                                              const uint32_t *__restrict__ tG,
-                                              const uint32_t *__restrict__ tE,
-                                              uint32_t *__restrict__ idx_out,
-                                              float *__restrict__ v_out)
+/* Per subspan: copy the admitted candidates (key > T, or key == T and among the first e_b
+ * equal ones of the bucket in index order) to their final slots. */
+__global__ __launch_bounds__(WG) void k_cwrite(Tables t, Cand c, uint32_t *__restrict__ idx_out,
+                                               float *__restrict__ v_out)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    const uint32_t n_ss = t.n_spans * 4;
+    for (uint32_t ss = blockIdx.x * 4 + (threadIdx.x >> 6); ss < n_ss; ss += gridDim.x * 4) {
+        const uint32_t b = t.span_b[ss >> 2];
+        if (!t.fast[b]) continue;
+        const uint32_t cnt = c.cnt[ss], T = t.T[b], e_b = t.need[b];
+        const uint64_t base = (uint64_t)ss * c.cap, Pb = t.P[b];
+        uint32_t run_g = c.G[ss], run_e = c.E[ss];
+        for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {
+            const uint32_t i = i0 + lane;
+            float x = 0.0f;
+            uint32_t li = 0;
+            bool isg = false, ise = false;
+            if (i < cnt) {
+                x = c.val[base + i];
+                li = c.idx[base + i];
+                const uint32_t key = keyof(x);
+                isg = key > T;
+                ise = key == T;
+            }
+            const uint64_t bg = __ballot(isg), be = __ballot(ise);
+            const uint32_t pg = run_g + __popcll(bg & lt), pe = run_e + __popcll(be & lt);
+            if (isg || (ise && pe < e_b)) {
+                const uint64_t pos = Pb + pg + min(e_b, pe);
+                idx_out[pos] = li;
+                v_out[pos] = x;
+            }
+            run_g += __popcll(bg);
+            run_e += __popcll(be);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ dense fallback path */
+
+/* One workgroup: the list of spans that belong to fallback buckets. */
+__global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
+{
+    __shared__ uint32_t tmp[WG];
+    const uint32_t tid = threadIdx.x;
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < t.B; base += WG) {
+        const uint32_t b = base + tid;
+        const bool fb = b < t.B && !t.fast[b];
+        const uint32_t x = fb ? t.span0[b + 1] - t.span0[b] : 0u;
+        if (fb) { t.T[b] = t.T0[b]; t.need[b] = t.need0[b]; }    /* restart from level 0 */
+        const uint32_t incl = block_incl_scan(x, tmp);
+        const uint32_t tot = tmp[WG - 1];
+        __syncthreads();
+        if (b < t.B) t.fspan0[b] = carry + incl - x;
+        carry += tot;
+    }
+    if (tid == 0) t.fspan0[t.B] = carry;
+}
+
+/* Histogram of the next digit over the dense accumulator of the fallback buckets. */
+template <int LEVEL>
+__global__ __launch_bounds__(WG) void k_fb_refine(const float *__restrict__ r, Tables t,
+                                                  uint32_t *__restrict__ hist)
+{
+    constexpr int NB = LEVEL == 1 ? NB1 : NB2;
+    constexpr int PSH = LEVEL == 1 ? SH0 : SH1;          /* key >> PSH is the prefix */
+    constexpr int DSH = LEVEL == 1 ? SH1 : 0;
+    constexpr uint32_t DMASK = NB - 1;
+    __shared__ uint32_t h[NB];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t total = t.fspan0[t.B];
+    for (uint32_t fs = blockIdx.x; fs < total; fs += gridDim.x) {
+        const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
+        const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
+        const uint32_t prefix = t.T[b];
+        for (int i = tid; i < NB; i += WG) h[i] = 0;
+        __syncthreads();
+        for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
+            const uint64_t tb = s.base + (uint64_t)ti * TILE;
+            const bool interior = tb >= s.lo && tb + TILE <= s.hi;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+                float x[4];
+                const uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
+                uint32_t d[4];
+                uint32_t hit = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = keyof(x[j]);
+                    d[j] = (key >> DSH) & DMASK;
+                    if (((m >> j) & 1u) && (key >> PSH) == prefix) hit |= 1u << j;
+                }
+                if (interior) {
+                    /* all lanes active here: whole-wavefront shortcut for runs of equal keys */
+                    const uint32_t f = __builtin_amdgcn_readfirstlane(d[0]);
+                    const bool same = hit == 0xFu && d[0] == f && d[1] == f && d[2] == f && d[3] == f;
+                    if (__all(same)) {
+                        if ((tid & 63) == 0) atomicAdd(&h[f], 256u);
+                        continue;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((hit >> j) & 1u) atomicAdd(&h[d[j]], 1u);
+            }
+        }
+        __syncthreads();
+        hist_flush(h, hist + (uint64_t)b * NB, NB);
+        __syncthreads();
+    }
+}
+
+/* Per tile of a fallback bucket: how many keys exceed the threshold, how many equal it. */
+__global__ __launch_bounds__(WG) void k_fb_count(const float *__restrict__ r, Tables t,
+                                                 uint32_t *__restrict__ tG, uint32_t *__restrict__ tE)
+{
+    __shared__ uint32_t cnt[MAX_SPAN_TILES][2];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t total = t.fspan0[t.B];
+    for (uint32_t fs = blockIdx.x; fs < total; fs += gridDim.x) {
+        const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
+        const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
+        const uint32_t T = t.T[b];
+        if (tid < MAX_SPAN_TILES * 2) (&cnt[0][0])[tid] = 0;
+        __syncthreads();
+        for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
+            const uint64_t tb = s.base + (uint64_t)ti * TILE;
+            uint32_t ng = 0, ne = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+                float x[4];
+                const uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = keyof(x[j]);
+                    const bool ok = (m >> j) & 1u;
+                    ng += (ok && key > T) ? 1u : 0u;
+                    ne += (ok && key == T) ? 1u : 0u;
+                }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                ng += __shfl_xor(ng, d, 64);
+                ne += __shfl_xor(ne, d, 64);
+            }
+            if ((tid & 63) == 0) { atomicAdd(&cnt[ti][0], ng); atomicAdd(&cnt[ti][1], ne); }
+        }
+        __syncthreads();
+        if (tid < s.ntiles) { tG[s.tile_g + tid] = cnt[tid][0]; tE[s.tile_g + tid] = cnt[tid][1]; }
+        __syncthreads();
+    }
+}
+
+/* Per tile of a fallback bucket: write the survivors to their final slots, in ascending
+ * index order.  Inside a tile, thread t owns the quads (u*256 + t)*4, u = 0..3. */
+__global__ __launch_bounds__(WG) void k_fb_write(const float *__restrict__ r, Tables t,
+                                                 const uint32_t *__restrict__ tG,
+                                                 const uint32_t *__restrict__ tE,
+                                                 uint32_t *__restrict__ idx_out,
+                                                 float *__restrict__ v_out)
 {
     __shared__ uint32_t tot[16][2];      /* slot = u * 4 + wavefront */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t lt = (1ull << lane) - 1ull;
-    const SpanGeo s = span_geo(t, blockIdx.x);
-    const uint32_t T = t.T[s.b], e_b = t.need[s.b];
-    const uint64_t Pb = t.P[s.b];
-    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-        const uint64_t tb = s.base + (uint64_t)ti * TILE;
-        const uint32_t gpre = tG[s.tile_g + ti], epre = tE[s.tile_g + ti];
-        float x[4][4];
-        uint32_t fg[4], fe[4], gb[4], eb[4];
+    const uint32_t total = t.fspan0[t.B];
+    for (uint32_t fs = blockIdx.x; fs < total; fs += gridDim.x) {
+        const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
+        const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
+        const uint32_t T = t.T[b], e_b = t.need[b];
+        const uint64_t Pb = t.P[b];
+        for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
+            const uint64_t tb = s.base + (uint64_t)ti * TILE;
+            const uint32_t gpre = tG[s.tile_g + ti], epre = tE[s.tile_g + ti];
+            float x[4][4];
+            uint32_t fg[4], fe[4], gb[4], eb[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-            const uint32_t m = load_quad(r, gi, s.lo, s.hi, x[u]);
-            fg[u] = fe[u] = 0;
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+                const uint32_t m = load_quad(r, gi, s.lo, s.hi, x[u]);
+                fg[u] = fe[u] = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t key = keyof(x[u][j]);
-                if (((m >> j) & 1u) && key > T) fg[u] |= 1u << j;
-                if (((m >> j) & 1u) && key == T) fe[u] |= 1u << j;
-            }
-            uint32_t cg = 0, ce = 0, wg = 0, we = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint64_t bg = __ballot((fg[u] >> j) & 1u);
-                const uint64_t be = __ballot((fe[u] >> j) & 1u);
-                cg += __popcll(bg & lt); wg += __popcll(bg);
-                ce += __popcll(be & lt); we += __popcll(be);
-            }
-            gb[u] = cg; eb[u] = ce;
-            if (lane == 0) { tot[u * 4 + wave][0] = wg; tot[u * 4 + wave][1] = we; }
-        }
-        __syncthreads();
-        uint32_t run_g = 0, run_e = 0;
-        int sl = 0;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int mine = u * 4 + (int)wave;
-            for (; sl < mine; ++sl) { run_g += tot[sl][0]; run_e += tot[sl][1]; }
-            uint32_t pg = gpre + run_g + gb[u];
-            uint32_t pe = epre + run_e + eb[u];
-            const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool isg = (fg[u] >> j) & 1u, ise = (fe[u] >> j) & 1u;
-                if (isg || (ise && pe < e_b)) {
-                    const uint64_t pos = Pb + pg + min(e_b, pe);
-                    idx_out[pos] = (uint32_t)(gi + j - s.lo);
-                    v_out[pos] = x[u][j];
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = keyof(x[u][j]);
+                    if (((m >> j) & 1u) && key > T) fg[u] |= 1u << j;
+                    if (((m >> j) & 1u) && key == T) fe[u] |= 1u << j;
                 }
-                pg += isg ? 1u : 0u;
-                pe += ise ? 1u : 0u;
+                uint32_t cg = 0, ce = 0, wg = 0, we = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint64_t bg = __ballot((fg[u] >> j) & 1u);
+                    const uint64_t be = __ballot((fe[u] >> j) & 1u);
+                    cg += __popcll(bg & lt); wg += __popcll(bg);
+                    ce += __popcll(be & lt); we += __popcll(be);
+                }
+                gb[u] = cg; eb[u] = ce;
+                if (lane == 0) { tot[u * 4 + wave][0] = wg; tot[u * 4 + wave][1] = we; }
             }
+            __syncthreads();
+            uint32_t run_g = 0, run_e = 0;
+            int sl = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int mine = u * 4 + (int)wave;
+                for (; sl < mine; ++sl) { run_g += tot[sl][0]; run_e += tot[sl][1]; }
+                uint32_t pg = gpre + run_g + gb[u];
+                uint32_t pe = epre + run_e + eb[u];
+                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool isg = (fg[u] >> j) & 1u, ise = (fe[u] >> j) & 1u;
+                    if (isg || (ise && pe < e_b)) {
+                        const uint64_t pos = Pb + pg + min(e_b, pe);
+                        idx_out[pos] = (uint32_t)(gi + j - s.lo);
+                        v_out[pos] = x[u][j];
+                    }
+                    pg += isg ? 1u : 0u;
+                    pe += ise ? 1u : 0u;
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
@@ -626,7 +972,7 @@ __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx,
         const uint64_t tb = s.base + (uint64_t)ti * TILE;
         /* local index one past the tile's last valid element */
         const uint64_t tend_g = tb + TILE < s.hi ? tb + TILE : s.hi;
-        const uint32_t L1 = (uint32_t)(tend_g - s.lo);      /* may be 2^32 - 0? no: n_b < 2^32 */
+        const uint32_t L1 = (uint32_t)(tend_g - s.lo);
         const uint64_t shift = s.lo - tb;                   /* slot = local index + lo - tb (mod 2^64) */
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -675,24 +1021,28 @@ struct nsml_ctx {
     int last_hip;
     uint64_t ws_bytes;
     uint32_t max_tiles;
+    uint64_t max_cand;     /* staging entries */
 
     /* device workspace */
     uint64_t *d_off, *d_P, *d_V, *d_S, *d_C;
-    uint32_t *d_tile0, *d_span0, *d_k, *d_T, *d_need;
-    uint32_t *d_hist;      /* B * (NB0 + NB1 + NB2) */
-    uint32_t *d_tG, *d_tE; /* per tile */
+    uint32_t *d_tile0, *d_span0, *d_samp0, *d_span_b, *d_k, *d_T, *d_need, *d_T0, *d_need0, *d_L, *d_fast, *d_fspan0;
+    uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
+    uint32_t *d_tG, *d_tE; /* per tile (fallback path) */
+    uint32_t *d_ccnt, *d_cG, *d_cE, *d_cidx;   /* candidate staging */
+    float *d_cval;
     float *d_v;            /* survivor values in final order (not used for bits == 32) */
 
     /* host copies / caches */
     std::vector<uint64_t> h_off;
     uint32_t B;
     uint64_t n;
-    uint32_t n_tiles, n_spans, spanT;
+    uint32_t n_tiles, n_spans, n_samp, spanT;
     bool tables_valid;
     double t_ratio; int t_bits;       /* what d_k/d_P/... were computed for */
     uint64_t K, NC;                   /* totals for (layout, t_ratio, t_bits) */
     void *pinned; size_t pinned_bytes;
     int span_override;
+    int force_dense;
 
     /* profiling */
     bool prof;
@@ -727,14 +1077,42 @@ int dev_alloc(nsml_ctx *c, T **p, uint64_t count)
     return NSML_OK;
 }
 
+/* words of the per-call zeroed area: hist0, sample hist, candidate level 1/2, fallback level
+ * 1/2 histograms, overflow flags */
+uint64_t zero_words(uint64_t B) { return B * (uint64_t)(NB0 + NB0 + NB1 + NB2 + NB1 + NB2 + 1); }
+
+struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *ovf; };
+Hists hists_of(const nsml_ctx *c, uint32_t B)
+{
+    Hists h;
+    h.h0 = c->d_zero;
+    h.hs = h.h0 + (uint64_t)B * NB0;
+    h.c1 = h.hs + (uint64_t)B * NB0;
+    h.c2 = h.c1 + (uint64_t)B * NB1;
+    h.f1 = h.c2 + (uint64_t)B * NB2;
+    h.f2 = h.f1 + (uint64_t)B * NB1;
+    h.ovf = h.f2 + (uint64_t)B * NB2;
+    return h;
+}
+
 Tables tables_of(const nsml_ctx *c)
 {
     Tables t;
-    t.off = c->d_off; t.tile0 = c->d_tile0; t.span0 = c->d_span0;
+    t.off = c->d_off; t.tile0 = c->d_tile0; t.span0 = c->d_span0; t.samp0 = c->d_samp0;
+    t.span_b = c->d_span_b;
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
-    t.T = c->d_T; t.need = c->d_need;
-    t.B = c->B; t.spanT = c->spanT; t.chunk = c->chunk;
+    t.T = c->d_T; t.need = c->d_need; t.T0 = c->d_T0; t.need0 = c->d_need0; t.L = c->d_L; t.fast = c->d_fast;
+    t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
+    t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.chunk = c->chunk;
     return t;
+}
+
+Cand cand_of(const nsml_ctx *c)
+{
+    Cand k;
+    k.idx = c->d_cidx; k.val = c->d_cval; k.cnt = c->d_ccnt; k.G = c->d_cG; k.E = c->d_cE;
+    k.cap = c->spanT * 256u;
+    return k;
 }
 
 /* Profiling brackets */
@@ -794,15 +1172,24 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
         return NSML_OK;
 
     /* new layout: tiles start at the bucket start rounded down to a multiple of 4 */
-    std::vector<uint32_t> tile0((size_t)B + 1), span0((size_t)B + 1);
-    uint64_t nt = 0;
+    const size_t B1 = (size_t)B + 1;
+    std::vector<uint32_t> tile0(B1), span0(B1), samp0(B1);
+    uint64_t nt = 0, nsamp = 0;
     for (uint32_t b = 0; b < B; ++b) {
         tile0[b] = (uint32_t)nt;
+        samp0[b] = (uint32_t)nsamp;
         const uint64_t lo = off[b], hi = off[b + 1];
-        if (hi > lo) nt += (hi - (lo & ~3ull) + TILE - 1) / TILE;
+        if (hi > lo) {
+            const uint64_t len = hi - (lo & ~3ull);
+            nt += (len + TILE - 1) / TILE;
+            const uint64_t run_elems = 32ull * ((hi - lo) < SAMPLE_ALL_BELOW ? 1 : SAMPLE_STRIDE);
+            const uint64_t runs = (len + run_elems - 1) / run_elems;
+            nsamp += (runs + RUNS_PER_WG - 1) / RUNS_PER_WG;
+        }
         if (nt > c->max_tiles) return NSML_ECAP;
     }
     tile0[B] = (uint32_t)nt;
+    samp0[B] = (uint32_t)nsamp;
     const uint32_t spanT = pick_span_tiles((uint32_t)nt, c->span_override);
     uint64_t ns = 0;
     for (uint32_t b = 0; b < B; ++b) {
@@ -810,27 +1197,33 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
         ns += (tile0[b + 1] - tile0[b] + spanT - 1) / spanT;
     }
     span0[B] = (uint32_t)ns;
+    if (ns * 4ull * spanT * 256ull > c->max_cand) return NSML_ECAP;
 
     /* the stream may still be using the old tables */
     NSML_HIP(c, hipStreamSynchronize(st));
     c->tables_valid = false;
     c->B = 0;
-    const size_t need = sizeof(uint64_t) * ((size_t)B + 1) + 2 * sizeof(uint32_t) * ((size_t)B + 1);
+    const size_t need = sizeof(uint64_t) * B1 + 3 * sizeof(uint32_t) * B1;
     if (need > c->pinned_bytes) return NSML_ECAP;
     uint8_t *hp = static_cast<uint8_t *>(c->pinned);
-    memcpy(hp, off, sizeof(uint64_t) * ((size_t)B + 1));
-    uint8_t *hp_t = hp + sizeof(uint64_t) * ((size_t)B + 1);
-    memcpy(hp_t, tile0.data(), sizeof(uint32_t) * ((size_t)B + 1));
-    uint8_t *hp_s = hp_t + sizeof(uint32_t) * ((size_t)B + 1);
-    memcpy(hp_s, span0.data(), sizeof(uint32_t) * ((size_t)B + 1));
-    NSML_HIP(c, hipMemcpyAsync(c->d_off, hp, sizeof(uint64_t) * ((size_t)B + 1), hipMemcpyHostToDevice, st));
-    NSML_HIP(c, hipMemcpyAsync(c->d_tile0, hp_t, sizeof(uint32_t) * ((size_t)B + 1), hipMemcpyHostToDevice, st));
-    NSML_HIP(c, hipMemcpyAsync(c->d_span0, hp_s, sizeof(uint32_t) * ((size_t)B + 1), hipMemcpyHostToDevice, st));
+    uint8_t *hp_t = hp + sizeof(uint64_t) * B1;
+    uint8_t *hp_s = hp_t + sizeof(uint32_t) * B1;
+    uint8_t *hp_m = hp_s + sizeof(uint32_t) * B1;
+    memcpy(hp, off, sizeof(uint64_t) * B1);
+    memcpy(hp_t, tile0.data(), sizeof(uint32_t) * B1);
+    memcpy(hp_s, span0.data(), sizeof(uint32_t) * B1);
+    memcpy(hp_m, samp0.data(), sizeof(uint32_t) * B1);
+    NSML_HIP(c, hipMemcpyAsync(c->d_off, hp, sizeof(uint64_t) * B1, hipMemcpyHostToDevice, st));
+    NSML_HIP(c, hipMemcpyAsync(c->d_tile0, hp_t, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
+    NSML_HIP(c, hipMemcpyAsync(c->d_span0, hp_s, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
+    NSML_HIP(c, hipMemcpyAsync(c->d_samp0, hp_m, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
+    LAUNCH(c, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)c->d_span0, B,
+           (uint32_t)ns, c->d_span_b);
     NSML_HIP(c, hipStreamSynchronize(st));
 
     c->h_off.assign(off, off + B + 1);
     c->B = B; c->n = n;
-    c->n_tiles = (uint32_t)nt; c->n_spans = (uint32_t)ns; c->spanT = spanT;
+    c->n_tiles = (uint32_t)nt; c->n_spans = (uint32_t)ns; c->n_samp = (uint32_t)nsamp; c->spanT = spanT;
     return NSML_OK;
 }
 
@@ -840,14 +1233,10 @@ int ensure_tables(nsml_ctx *c, double ratio, int bits, hipStream_t st)
     if (!(ratio > 0.0 && ratio <= 1.0)) return NSML_EINVAL;
     if (bits != 4 && bits != 8 && bits != 16 && bits != 32) return NSML_EINVAL;
     if (c->tables_valid && c->t_ratio == ratio && c->t_bits == bits) return NSML_OK;
-    uint64_t K = 0;
-    int rc = nsml_payload_layout(c->h_off.data(), c->B, ratio, bits, c->chunk, nullptr, &K, nullptr, nullptr);
-    if (rc) return rc;
-    /* chunk count over all buckets (for every width) */
-    uint64_t nc = 0;
+    uint64_t K = 0, nc = 0;
     {
         std::vector<uint64_t> kb(c->B);
-        rc = nsml_payload_layout(c->h_off.data(), c->B, ratio, bits, c->chunk, kb.data(), nullptr, nullptr, nullptr);
+        int rc = nsml_payload_layout(c->h_off.data(), c->B, ratio, bits, c->chunk, kb.data(), &K, nullptr, nullptr);
         if (rc) return rc;
         for (uint32_t b = 0; b < c->B; ++b) nc += (kb[b] + c->chunk - 1) / c->chunk;
     }
@@ -873,10 +1262,14 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->last_hip = 0; c->ws_bytes = 0; c->B = 0; c->n = 0; c->tables_valid = false;
     c->prof = false; c->pinned = nullptr; c->pinned_bytes = 0;
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
-    c->d_tile0 = c->d_span0 = c->d_k = c->d_T = c->d_need = c->d_hist = c->d_tG = c->d_tE = nullptr;
-    c->d_v = nullptr;
+    c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
+    c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = c->d_T0 = c->d_need0 = nullptr;
+    c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
+    c->d_cval = nullptr; c->d_v = nullptr;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
+    const char *fd = getenv("NSML_FORCE_DENSE");
+    c->force_dense = (fd && atoi(fd) != 0) ? 1 : 0;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
@@ -889,20 +1282,28 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
 
     /* every bucket can add one partial tile at each end */
     const uint64_t mt = max_n / TILE + 2ull * max_buckets + 2;
-    if (mt >= 0xFFFFFFFFull) { delete c; return NSML_ECAP; }
+    if (mt >= 0x3FFFFFFFull) { delete c; return NSML_ECAP; }
     c->max_tiles = (uint32_t)mt;
+    /* staging: a quarter of the elements every span covers; a span is at most 16 tiles and
+     * every bucket can leave one span partly filled */
+    c->max_cand = (mt + (uint64_t)MAX_SPAN_TILES * max_buckets) * (TILE / 4);
     const uint64_t B1 = (uint64_t)max_buckets + 1;
     int rc = NSML_OK;
     auto A = [&](int r) { if (rc == NSML_OK) rc = r; };
     A(dev_alloc(c, &c->d_off, B1)); A(dev_alloc(c, &c->d_P, B1)); A(dev_alloc(c, &c->d_V, B1));
     A(dev_alloc(c, &c->d_S, B1)); A(dev_alloc(c, &c->d_C, B1));
-    A(dev_alloc(c, &c->d_tile0, B1)); A(dev_alloc(c, &c->d_span0, B1));
+    A(dev_alloc(c, &c->d_tile0, B1)); A(dev_alloc(c, &c->d_span0, B1)); A(dev_alloc(c, &c->d_samp0, B1));
     A(dev_alloc(c, &c->d_k, B1)); A(dev_alloc(c, &c->d_T, B1)); A(dev_alloc(c, &c->d_need, B1));
-    A(dev_alloc(c, &c->d_hist, (uint64_t)max_buckets * (NB0 + NB1 + NB2)));
+    A(dev_alloc(c, &c->d_T0, B1)); A(dev_alloc(c, &c->d_need0, B1));
+    A(dev_alloc(c, &c->d_L, B1)); A(dev_alloc(c, &c->d_fast, B1)); A(dev_alloc(c, &c->d_fspan0, B1));
+    A(dev_alloc(c, &c->d_span_b, mt));
+    A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
     A(dev_alloc(c, &c->d_tG, mt)); A(dev_alloc(c, &c->d_tE, mt));
+    A(dev_alloc(c, &c->d_ccnt, 4 * mt)); A(dev_alloc(c, &c->d_cG, 4 * mt)); A(dev_alloc(c, &c->d_cE, 4 * mt));
+    A(dev_alloc(c, &c->d_cidx, c->max_cand)); A(dev_alloc(c, &c->d_cval, c->max_cand));
     A(dev_alloc(c, &c->d_v, max_n));
     if (rc == NSML_OK) {
-        c->pinned_bytes = B1 * 16;
+        c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
         if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
     }
@@ -916,8 +1317,10 @@ int nsml_destroy(nsml_ctx *c)
     if (!c) return NSML_EINVAL;
     DeviceGuard guard(c->device);
     (void)hipDeviceSynchronize();
-    void *ptrs[] = {c->d_off, c->d_P, c->d_V, c->d_S, c->d_C, c->d_tile0, c->d_span0, c->d_k,
-                    c->d_T, c->d_need, c->d_hist, c->d_tG, c->d_tE, c->d_v};
+    void *ptrs[] = {c->d_off, c->d_P, c->d_V, c->d_S, c->d_C, c->d_tile0, c->d_span0, c->d_samp0,
+                    c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_T0, c->d_need0, c->d_L, c->d_fast, c->d_fspan0,
+                    c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
+                    c->d_cval, c->d_v};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -947,23 +1350,42 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
     if (rc) return rc;
 
     const Tables t = tables_of(c);
-    uint32_t *h0 = c->d_hist;
-    uint32_t *h1 = h0 + (uint64_t)B * NB0;
-    uint32_t *h2 = h1 + (uint64_t)B * NB1;
-    const uint64_t hist_words = (uint64_t)B * (NB0 + NB1 + NB2);
-    const uint32_t clear_grid = (uint32_t)((hist_words + WG * 8 - 1) / (WG * 8));
+    const Cand cd = cand_of(c);
+    const Hists h = hists_of(c, B);
+    const uint64_t zw = zero_words(B);
+    const uint32_t clear_grid = (uint32_t)((zw + WG * 8 - 1) / (WG * 8));
     float *vdst = bits == 32 ? static_cast<float *>(val) : c->d_v;
+    const uint32_t n_ss = c->n_spans * 4;
+    const uint32_t cgrid = (n_ss + 3) / 4 < SIDE_GRID ? (n_ss + 3) / 4 : SIDE_GRID;
+    const uint32_t fgrid = c->n_spans < SIDE_GRID ? c->n_spans : SIDE_GRID;
 
-    LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_hist, hist_words);
-    LAUNCH(c, KID_EF_HIST, st, k_ef_hist, c->n_spans, grad, residual, t, h0);
-    LAUNCH(c, KID_PICK0, st, k_pick<0>, B, t, (const uint32_t *)h0);
-    LAUNCH(c, KID_REFINE1, st, k_refine<1>, c->n_spans, (const float *)residual, t, h1);
-    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h1);
-    LAUNCH(c, KID_REFINE2, st, k_refine<2>, c->n_spans, (const float *)residual, t, h2);
-    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h2);
-    LAUNCH(c, KID_COUNT, st, k_count, c->n_spans, (const float *)residual, t, c->d_tG, c->d_tE);
-    LAUNCH(c, KID_SCAN, st, k_scan, B, t, c->d_tG, c->d_tE);
-    LAUNCH(c, KID_WRITE, st, k_write, c->n_spans, (const float *)residual, t,
+    LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
+    if (!c->force_dense)
+        LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
+    LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
+    if (!c->force_dense)
+        LAUNCH(c, KID_EF_EMIT, st, k_ef_emit<true>, c->n_spans, grad, residual, t, h.h0, cd);
+    else
+        LAUNCH(c, KID_EF_EMIT, st, k_ef_emit<false>, c->n_spans, grad, residual, t, h.h0, cd);
+    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0);
+    if (!c->force_dense) {
+        LAUNCH(c, KID_CREFINE1, st, k_crefine<1>, cgrid, t, cd, h.c1);
+        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, 1u);
+        LAUNCH(c, KID_CREFINE2, st, k_crefine<2>, cgrid, t, cd, h.c2);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, 1u);
+        LAUNCH(c, KID_CCOUNT, st, k_ccount, cgrid, t, cd);
+        LAUNCH(c, KID_CSCAN, st, k_scan, B, t, cd.G, cd.E, 1u);
+        LAUNCH(c, KID_CWRITE, st, k_cwrite, cgrid, t, cd, idx, vdst);
+    }
+    /* buckets the candidates could not decide: the same steps over the dense accumulator */
+    LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
+    LAUNCH(c, KID_FB_REFINE1, st, k_fb_refine<1>, fgrid, (const float *)residual, t, h.f1);
+    LAUNCH(c, KID_FB_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.f1, 0u);
+    LAUNCH(c, KID_FB_REFINE2, st, k_fb_refine<2>, fgrid, (const float *)residual, t, h.f2);
+    LAUNCH(c, KID_FB_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.f2, 0u);
+    LAUNCH(c, KID_FB_COUNT, st, k_fb_count, fgrid, (const float *)residual, t, c->d_tG, c->d_tE);
+    LAUNCH(c, KID_FB_SCAN, st, k_scan, B, t, c->d_tG, c->d_tE, 0u);
+    LAUNCH(c, KID_FB_WRITE, st, k_fb_write, fgrid, (const float *)residual, t,
            (const uint32_t *)c->d_tG, (const uint32_t *)c->d_tE, idx, vdst);
     const uint32_t qgrid = (uint32_t)c->NC;
     switch (bits) {
@@ -1023,6 +1445,22 @@ int nsml_profile_read(nsml_ctx *c, uint32_t *launches, double *total_ms)
     }
     c->recs.clear();
     return rc;
+}
+
+int nsml_path_stats(nsml_ctx *c, uint32_t *fast_buckets, uint32_t *fallback_buckets)
+{
+    if (!c || !fast_buckets || !fallback_buckets) return NSML_EINVAL;
+    *fast_buckets = *fallback_buckets = 0;
+    if (c->B == 0) return NSML_OK;
+    DeviceGuard guard(c->device);
+    NSML_HIP(c, hipDeviceSynchronize());
+    std::vector<uint32_t> f(c->B);
+    NSML_HIP(c, hipMemcpy(f.data(), c->d_fast, sizeof(uint32_t) * c->B, hipMemcpyDeviceToHost));
+    for (uint32_t b = 0; b < c->B; ++b) {
+        if (c->h_off[b + 1] == c->h_off[b]) continue;
+        if (f[b]) *fast_buckets += 1; else *fallback_buckets += 1;
+    }
+    return NSML_OK;
 }
 
 const char *nsml_kernel_name(int id) { return (id >= 0 && id < KID_N) ? kKernelNames[id] : nullptr; }

@@ -120,6 +120,7 @@ def test_cfg3_bert_full(ratio, bits):
     idx, val, sc = ctx.compress(g, r, off, ratio, bits)
     dense = ctx.decompress(idx, val, sc, n, off, ratio, bits)
     torch.cuda.synchronize()
+    say("cfg3", ratio, bits, "buckets (one pass, dense passes):", ctx.path_stats())
     sb = SampledBuckets(off, [0, 1, 2, 5, 17, 100, 198])
     sb.check(g, r, idx, val, sc, dense, ratio, bits)
     _properties(g, torch.zeros_like(g), r, idx, val, sc, dense, off, ratio, bits)
@@ -145,6 +146,9 @@ def test_cfg4_llama7b_full_sampled():
         ctx.compress(g, r, off, 0.001, 4, idx, val, sc)
         ctx.decompress(idx, val, sc, n, off, 0.001, 4, dense)
         torch.cuda.synchronize()
+        fast, fb = ctx.path_stats()
+        say("cfg4 step", step, "buckets decided in one pass:", fast, "by dense passes:", fb)
+        assert fast >= 250
         say("cfg4 step", step, "oracle")
         sb.check(g, r, idx, val, sc, dense, 0.001, 4)
     say("cfg4 properties")

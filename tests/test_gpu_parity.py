@@ -13,18 +13,28 @@ from gpu_util import DEV, Case, say
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["auto", "dense"])
+def path(request, monkeypatch):
+    """Every case runs twice: with the single-pass candidate path enabled (buckets fall back
+    to the dense passes on their own when they must) and with every bucket forced through the
+    dense passes.  The library reads the switch when a context is created."""
+    monkeypatch.setenv("NSML_FORCE_DENSE", "1" if request.param == "dense" else "0")
+    return request.param
+
+
 def _rand(n, seed, sigma=1e-3):
     g = torch.Generator(device=DEV)
     g.manual_seed(seed)
     return torch.randn(n, generator=g, device=DEV) * sigma
 
 
-def test_cfg1_single_vector():
+def test_cfg1_single_vector(path):
     """Configuration 1: 1,048,576 x N(0, 1e-3), ratio 0.01 (k = 10,486), int8, chunk 2048."""
     g, off = W.cfg1(DEV)
     c = Case(g, off)
     K, vb, ns = c.step(0.01, 8)
     assert (K, vb, ns) == (10486, 10486, 6)
+    assert c.ctx.path_stats() == ((1, 0) if path == "auto" else (0, 1))
 
 
 @pytest.mark.parametrize("bits", [4, 8, 16, 32])
