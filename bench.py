@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB copy kernel (k_calib_copy): the yardstick for "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one worker's pipeline on ONE GPU; a run with "
@@ -148,6 +151,13 @@ def main():
         ctx.compress(g, residual, off, ratio, bits, idx, val, sc)
         ctx.decompress(idx, val, sc, n, off, ratio, bits, dense)
 
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        nsml.calibration_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -178,12 +188,13 @@ def main():
     achieved = EF_HIST_BYTES_PER_ELEM * n / (ef_ms * 1e-3) / 1e9
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_ef_emit_{args.workload}.json")
+    # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, calibrated on a
+    # plain copy); the figure is kept in the committed profile summary of this workload
+    tpath = os.path.join(ROOT, "profiles", f"ef_emit_{args.workload}.txt")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+        import re
+        m = re.search(r"hbm_bytes_per_launch:\s*([0-9.eE+]+)", open(tpath).read())
+        traffic = float(m.group(1)) if m else None
 
     value = 4.0 * n / (ms_per_step * 1e-3) / 1e9
     floor_bytes = 16.0 * n + 2.0 * payload

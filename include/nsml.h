@@ -188,6 +188,10 @@ int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
  * decided from the single streaming pass (fast) and how many needed the extra dense passes
  * (fallback).  Both give identical results.  Synchronises the device. */
 int nsml_path_stats(nsml_ctx *ctx, uint32_t *fast_buckets, uint32_t *fallback_buckets);
+/* Measurement aid: a plain device-to-device copy kernel ("k_calib_copy") of `bytes` bytes
+ * (a multiple of 16, both pointers 16-byte aligned, dev) on `stream`, on the current device.
+ * A profiler's HBM byte counters are scaled by what they report for this copy of known size. */
+int nsml_calibration_copy(const void *src, void *dst, uint64_t bytes, void *stream);
 /* Name of kernel id (NULL beyond the last). */
 const char *nsml_kernel_name(int id);
 

@@ -64,6 +64,8 @@ _lib.nsml_profile_enable.argtypes = [_vp, _i32]
 _lib.nsml_profile_read.argtypes = [_vp, _vp, _vp]
 _lib.nsml_path_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
 _lib.nsml_path_stats.restype = _i32
+_lib.nsml_calibration_copy.argtypes = [_vp, _vp, _u64, _vp]
+_lib.nsml_calibration_copy.restype = _i32
 _lib.nsml_kernel_name.argtypes = [_i32]
 _lib.nsml_kernel_name.restype = C.c_char_p
 for _f in ("nsml_ctl_default_params", "nsml_ctl_init", "nsml_choose_ratio", "nsml_payload_layout",
@@ -230,6 +232,14 @@ class Context:
             if name is not None and n[i]:
                 out[name.decode()] = (int(n[i]), float(ms[i]))
         return out
+
+
+def calibration_copy(src: torch.Tensor, dst: torch.Tensor):
+    """Plain copy kernel of known size (src -> dst, same byte size, a multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(_lib.nsml_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(src.device)),
+           "nsml_calibration_copy")
 
 
 def compress(ctx: Context, grad, residual, bucket_off, ratio, bits, idx=None, val=None, scales=None):

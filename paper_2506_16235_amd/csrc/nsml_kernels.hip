@@ -237,6 +237,13 @@ __global__ __launch_bounds__(WG) void k_clear(uint32_t *__restrict__ p, uint64_t
     for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
+/* Plain 16-byte copy, the yardstick for the profiler's HBM byte counters. */
+__global__ __launch_bounds__(WG) void k_calib_copy(const f4 *__restrict__ src, f4 *__restrict__ dst, uint64_t n16)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * WG;
+    for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 /* ------------------------------------------------------------------ histograms */
 
 /* Add the four level digits of a quad to an LDS histogram.  When every lane of the wavefront
@@ -1461,6 +1468,18 @@ int nsml_path_stats(nsml_ctx *c, uint32_t *fast_buckets, uint32_t *fallback_buck
         if (f[b]) *fast_buckets += 1; else *fallback_buckets += 1;
     }
     return NSML_OK;
+}
+
+int nsml_calibration_copy(const void *src, void *dst, uint64_t bytes, void *stream)
+{
+    if (!src || !dst || bytes == 0 || bytes % 16 != 0 || !aligned(src, 16) || !aligned(dst, 16))
+        return NSML_EINVAL;
+    const uint64_t n16 = bytes / 16;
+    const uint64_t want = (n16 + WG - 1) / WG;
+    const uint32_t grid = (uint32_t)(want < 65536 ? want : 65536);
+    hipLaunchKernelGGL(k_calib_copy, dim3(grid), dim3(WG), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const f4 *>(src), static_cast<f4 *>(dst), n16);
+    return hipGetLastError() == hipSuccess ? NSML_OK : NSML_EHIP;
 }
 
 const char *nsml_kernel_name(int id) { return (id >= 0 && id < KID_N) ? kKernelNames[id] : nullptr; }
