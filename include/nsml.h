@@ -44,6 +44,8 @@ extern "C" {
 #define NSML_EHIP     (-3)  /* a HIP call failed; see nsml_last_hip_error */
 #define NSML_ENOTIMPL (-4)
 #define NSML_ENOMEM   (-5)  /* host allocation failed */
+#define NSML_EINTERNAL (-6) /* a device-side consistency check of the selection failed (a bug in
+                               the library): reported by nsml_path_stats */
 
 const char *nsml_strerror(int code);
 
@@ -186,7 +188,8 @@ int nsml_profile_enable(nsml_ctx *ctx, int on);
 int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
 /* Diagnostics for the last nsml_compress of the context: how many non-empty buckets were
  * decided from the single streaming pass (fast) and how many needed the extra dense passes
- * (fallback).  Both give identical results.  Synchronises the device. */
+ * (fallback).  Both give identical results.  Synchronises the device.  NSML_EINTERNAL if the
+ * call tripped a device-side consistency check (its outputs are then not valid). */
 int nsml_path_stats(nsml_ctx *ctx, uint32_t *fast_buckets, uint32_t *fallback_buckets);
 /* Measurement aid: a plain device-to-device copy kernel ("k_calib_copy") of `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned, dev) on `stream`, on the current device.

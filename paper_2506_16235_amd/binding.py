@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libnsml.so")
 
-OK, EINVAL, ECAP, EHIP, ENOTIMPL, ENOMEM = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ECAP, EHIP, ENOTIMPL, ENOMEM, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 MAX_KERNELS = 32
 CTL_MAX_WIN = 128
 

@@ -17,6 +17,7 @@ const char *nsml_strerror(int code)
     case NSML_EHIP:     return "a HIP call failed";
     case NSML_ENOTIMPL: return "not implemented";
     case NSML_ENOMEM:   return "out of host memory";
+    case NSML_EINTERNAL: return "internal consistency check failed";
     default:            return "unknown error";
     }
 }

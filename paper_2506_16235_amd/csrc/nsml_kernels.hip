@@ -61,16 +61,14 @@ constexpr uint32_t RUNS_PER_WG = 512;          /* sample runs (32 elements each)
 constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
 
 enum KernelId {
-    KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN,
-    KID_CREFINE1, KID_PICK1, KID_CREFINE2, KID_PICK2, KID_CCOUNT, KID_CSCAN, KID_CWRITE,
-    KID_FB_PLAN, KID_FB_REFINE1, KID_FB_PICK1, KID_FB_REFINE2, KID_FB_PICK2, KID_FB_COUNT,
-    KID_FB_SCAN, KID_FB_WRITE, KID_QUANT, KID_DECOMP, KID_N
+    KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
+    KID_REFINE1, KID_PICK1, KID_REFINE2, KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE,
+    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_N
 };
 const char *const kKernelNames[KID_N] = {
-    "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan",
-    "crefine1", "pick1", "crefine2", "pick2", "ccount", "cscan", "cwrite",
-    "fb_plan", "fb_refine1", "fb_pick1", "fb_refine2", "fb_pick2", "fb_count",
-    "fb_scan", "fb_write", "quant", "decomp"
+    "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan", "fb_plan",
+    "refine1", "pick1", "refine2", "pick2", "count", "scan", "write",
+    "quant", "tilestart", "decomp"
 };
 static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
 
@@ -89,7 +87,6 @@ struct Tables {
     uint64_t *C;             /* B+1 prefix of chunk counts (all widths) */
     uint32_t *T;             /* B   threshold key, refined level by level */
     uint32_t *need;          /* B   how many more to take at the current level */
-    uint32_t *T0, *need0;    /* B   T and need as they stood after level 0 (for the fallback) */
     uint32_t *L;             /* B   candidates are the elements with key >= L (NONE: no candidates) */
     uint32_t *fast;          /* B   1: the candidates decide the bucket, 0: the dense fallback does */
     uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
@@ -404,7 +401,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
 /* One row of the streaming pass: 64 lanes x 4 consecutive elements (one contiguous 1 KiB).
  * a[] is the accumulator quad of this lane, m its validity mask, li the bucket-local index
  * of a[0].  Stores the accumulator, counts its level-0 digits and appends candidates. */
-template <bool INTERIOR, bool EMIT>
+template <bool INTERIOR, bool EMIT, int NT>
 __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const float (&a)[4],
                                        uint32_t m, uint32_t li, uint32_t *h, uint32_t L,
                                        const Cand &c, uint64_t cbase, uint32_t &wcount, uint64_t lt)
@@ -414,7 +411,8 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
     for (int j = 0; j < 4; ++j) key[j] = keyof(a[j]);
     if (INTERIOR) {
         f4 v; v.x = a[0]; v.y = a[1]; v.z = a[2]; v.w = a[3];
-        *reinterpret_cast<f4 *>(r + gi) = v;
+        if (NT & 4) __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(r + gi));
+        else *reinterpret_cast<f4 *>(r + gi) = v;
         hist_quad_full(h, key[0] >> SH0, key[1] >> SH0, key[2] >> SH0, key[3] >> SH0);
     } else {
 #pragma unroll
@@ -447,7 +445,7 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
  * filters out is accumulated locally; the add is that), the exact level-0 histogram, and the
  * candidates.  Each wavefront owns a contiguous quarter of the span and its own staging
  * segment, so candidates come out in index order without any cross-wavefront exchange. */
-template <bool EMIT>
+template <bool EMIT, int NT>
 __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
                                                 Tables t, uint32_t *__restrict__ hist0, Cand c)
 {
@@ -471,8 +469,10 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
-                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi));
-                rv[u] = *reinterpret_cast<const f4 *>(r + gi);
+                gv[u] = (NT & 1) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi))
+                                 : *reinterpret_cast<const f4 *>(g + gi);
+                rv[u] = (NT & 2) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r + gi))
+                                 : *reinterpret_cast<const f4 *>(r + gi);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
                 float a[4];
                 a[0] = __fadd_rn(gv[u].x, rv[u].x); a[1] = __fadd_rn(gv[u].y, rv[u].y);
                 a[2] = __fadd_rn(gv[u].z, rv[u].z); a[3] = __fadd_rn(gv[u].w, rv[u].w);
-                ef_row<true, EMIT>(r, gi, a, 0xFu, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+                ef_row<true, EMIT, NT>(r, gi, a, 0xFu, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         } else {
 #pragma unroll
@@ -491,7 +491,7 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
                 load_quad(r, gi, s.lo, s.hi, y);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) a[j] = __fadd_rn(x[j], y[j]);
-                ef_row<false, EMIT>(r, gi, a, m, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+                ef_row<false, EMIT, NT>(r, gi, a, m, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         }
     }
@@ -511,18 +511,39 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restric
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const uint32_t want = t.k[b];
     if (want == 0) {                       /* empty bucket: nothing can match */
-        if (tid == 0) { t.T[b] = t.T0[b] = NONE; t.need[b] = t.need0[b] = 0; }
+        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; }
         return;
     }
     DigitWalk<NB0> w;
     w.load(hist0 + (uint64_t)b * NB0, tmp);
     uint32_t digit, above, at;
     if (w.find(want, digit, above, at)) {
-        t.T[b] = t.T0[b] = digit;
-        t.need[b] = t.need0[b] = want - above;
+        t.T[b] = digit;
+        t.need[b] = want - above;
         const uint32_t L = t.L[b];
         if (t.fast[b] && (L == NONE || (L >> SH0) > digit || t.ovf[b])) t.fast[b] = 0u;
     }
+}
+
+/* One workgroup: the list of spans that belong to fallback buckets.  (Kept as its own small
+ * launch: doing it in the last workgroup of k_plan needs a device-scope fence in every
+ * workgroup, which on this multi-die GPU writes back each L2 and costs more than a launch.) */
+__global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
+{
+    __shared__ uint32_t tmp[WG];
+    const uint32_t tid = threadIdx.x;
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < t.B; base += WG) {
+        const uint32_t bb = base + tid;
+        const bool fb = bb < t.B && !t.fast[bb];
+        const uint32_t x = fb ? t.span0[bb + 1] - t.span0[bb] : 0u;
+        const uint32_t incl = block_incl_scan(x, tmp);
+        const uint32_t tot = tmp[WG - 1];
+        __syncthreads();
+        if (bb < t.B) t.fspan0[bb] = carry + incl - x;
+        carry += tot;
+    }
+    if (tid == 0) t.fspan0[t.B] = carry;
 }
 
 /* ------------------------------------------------------------------ candidate path */
@@ -531,14 +552,15 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restric
  * 12-bit prefix, digit = key bits 18..7; LEVEL 2: 24-bit prefix, digit = bits 6..0).  One
  * wavefront per subspan; the matching entries are few, so they go straight to global atomics. */
 template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_crefine(Tables t, Cand c, uint32_t *__restrict__ hist)
+__device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uint32_t *__restrict__ hist,
+                                             uint32_t bid, uint32_t nblk)
 {
     constexpr int NB = LEVEL == 1 ? NB1 : NB2;
     constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
     constexpr int DSH = LEVEL == 1 ? SH1 : 0;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t n_ss = t.n_spans * 4;
-    for (uint32_t ss = blockIdx.x * 4 + (threadIdx.x >> 6); ss < n_ss; ss += gridDim.x * 4) {
+    for (uint32_t ss = bid * 4 + (threadIdx.x >> 6); ss < n_ss; ss += nblk * 4) {
         const uint32_t b = t.span_b[ss >> 2];
         if (!t.fast[b]) continue;
         const uint32_t cnt = c.cnt[ss], prefix = t.T[b];
@@ -550,24 +572,24 @@ __global__ __launch_bounds__(WG) void k_crefine(Tables t, Cand c, uint32_t *__re
     }
 }
 
-/* Per bucket, levels 1 and 2: walk the level's histogram to the digit holding the need-th
- * entry, append it to the prefix.  mode 1: buckets on the candidate path, mode 0: fallback.
- * A candidate histogram with fewer entries than needed means the candidates were not a
- * superset after all; the bucket is handed to the fallback untouched. */
+/* Per bucket, levels 1 and 2: walk the level's histogram (the candidates' one or the dense
+ * fallback's, whichever path the bucket is on) to the digit holding the need-th entry and
+ * append it to the prefix. */
 template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist, uint32_t mode)
+__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
+                                             const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err)
 {
     constexpr int NB = LEVEL == 2 ? NB2 : NB1;
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    if (t.fast[b] != mode) return;
     const uint32_t want = t.need[b];
     if (want == 0) return;
+    const uint32_t *hist = t.fast[b] ? hist_c : hist_f;
     DigitWalk<NB> w;
     w.load(hist + (uint64_t)b * NB, tmp);
-    if (w.total < want) {
-        if (tid == 0) t.fast[b] = 0u;     /* only reachable on the candidate path */
+    if (w.total < want) {                  /* cannot happen: the level above counted them */
+        if (tid == 0) err[0] = 1u;
         return;
     }
     uint32_t digit, above, at;
@@ -578,11 +600,11 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
 }
 
 /* Per subspan: how many candidates exceed the threshold, how many equal it. */
-__global__ __launch_bounds__(WG) void k_ccount(Tables t, Cand c)
+__device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint32_t bid, uint32_t nblk)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t n_ss = t.n_spans * 4;
-    for (uint32_t ss = blockIdx.x * 4 + (threadIdx.x >> 6); ss < n_ss; ss += gridDim.x * 4) {
+    for (uint32_t ss = bid * 4 + (threadIdx.x >> 6); ss < n_ss; ss += nblk * 4) {
         const uint32_t b = t.span_b[ss >> 2];
         if (!t.fast[b]) continue;
         const uint32_t cnt = c.cnt[ss], T = t.T[b];
@@ -601,12 +623,13 @@ __global__ __launch_bounds__(WG) void k_ccount(Tables t, Cand c)
 
 /* Per bucket: exclusive scan, in place, of per-unit counts (units: the bucket's subspans on
  * the candidate path, its tiles on the fallback path). */
-__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ G, uint32_t *__restrict__ E,
-                                             uint32_t mode)
+__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
+                                             uint32_t *__restrict__ tG, uint32_t *__restrict__ tE)
 {
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    if (t.fast[b] != mode) return;
+    const uint32_t mode = t.fast[b];
+    uint32_t *G = mode ? cG : tG, *E = mode ? cE : tE;
     const uint32_t t0 = mode ? t.span0[b] * 4 : t.tile0[b];
     const uint32_t t1 = mode ? t.span0[b + 1] * 4 : t.tile0[b + 1];
     uint32_t carry_g = 0, carry_e = 0;
@@ -627,13 +650,13 @@ __global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ G,
 
 /* Per subspan: copy the admitted candidates (key > T, or key == T and among the first e_b
  * equal ones of the bucket in index order) to their final slots. */
-__global__ __launch_bounds__(WG) void k_cwrite(Tables t, Cand c, uint32_t *__restrict__ idx_out,
-                                               float *__restrict__ v_out)
+__device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint32_t *__restrict__ idx_out,
+                                            float *__restrict__ v_out, uint32_t bid, uint32_t nblk)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t n_ss = t.n_spans * 4;
-    for (uint32_t ss = blockIdx.x * 4 + (threadIdx.x >> 6); ss < n_ss; ss += gridDim.x * 4) {
+    for (uint32_t ss = bid * 4 + (threadIdx.x >> 6); ss < n_ss; ss += nblk * 4) {
         const uint32_t b = t.span_b[ss >> 2];
         if (!t.fast[b]) continue;
         const uint32_t cnt = c.cnt[ss], T = t.T[b], e_b = t.need[b];
@@ -666,39 +689,19 @@ __global__ __launch_bounds__(WG) void k_cwrite(Tables t, Cand c, uint32_t *__res
 
 /* ------------------------------------------------------------------ dense fallback path */
 
-/* One workgroup: the list of spans that belong to fallback buckets. */
-__global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
-{
-    __shared__ uint32_t tmp[WG];
-    const uint32_t tid = threadIdx.x;
-    uint32_t carry = 0;
-    for (uint32_t base = 0; base < t.B; base += WG) {
-        const uint32_t b = base + tid;
-        const bool fb = b < t.B && !t.fast[b];
-        const uint32_t x = fb ? t.span0[b + 1] - t.span0[b] : 0u;
-        if (fb) { t.T[b] = t.T0[b]; t.need[b] = t.need0[b]; }    /* restart from level 0 */
-        const uint32_t incl = block_incl_scan(x, tmp);
-        const uint32_t tot = tmp[WG - 1];
-        __syncthreads();
-        if (b < t.B) t.fspan0[b] = carry + incl - x;
-        carry += tot;
-    }
-    if (tid == 0) t.fspan0[t.B] = carry;
-}
-
 /* Histogram of the next digit over the dense accumulator of the fallback buckets. */
 template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_fb_refine(const float *__restrict__ r, Tables t,
-                                                  uint32_t *__restrict__ hist)
+__device__ __forceinline__ void fb_refine_body(const float *__restrict__ r, const Tables &t,
+                                               uint32_t *__restrict__ hist, uint32_t *h,
+                                               uint32_t bid, uint32_t nblk)
 {
     constexpr int NB = LEVEL == 1 ? NB1 : NB2;
     constexpr int PSH = LEVEL == 1 ? SH0 : SH1;          /* key >> PSH is the prefix */
     constexpr int DSH = LEVEL == 1 ? SH1 : 0;
     constexpr uint32_t DMASK = NB - 1;
-    __shared__ uint32_t h[NB];
     const uint32_t tid = threadIdx.x;
     const uint32_t total = t.fspan0[t.B];
-    for (uint32_t fs = blockIdx.x; fs < total; fs += gridDim.x) {
+    for (uint32_t fs = bid; fs < total; fs += nblk) {
         const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
         const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
         const uint32_t prefix = t.T[b];
@@ -741,13 +744,13 @@ __global__ __launch_bounds__(WG) void k_fb_refine(const float *__restrict__ r, T
 }
 
 /* Per tile of a fallback bucket: how many keys exceed the threshold, how many equal it. */
-__global__ __launch_bounds__(WG) void k_fb_count(const float *__restrict__ r, Tables t,
-                                                 uint32_t *__restrict__ tG, uint32_t *__restrict__ tE)
+__device__ __forceinline__ void fb_count_body(const float *__restrict__ r, const Tables &t,
+                                              uint32_t *__restrict__ tG, uint32_t *__restrict__ tE,
+                                              uint32_t (*cnt)[2], uint32_t bid, uint32_t nblk)
 {
-    __shared__ uint32_t cnt[MAX_SPAN_TILES][2];
     const uint32_t tid = threadIdx.x;
     const uint32_t total = t.fspan0[t.B];
-    for (uint32_t fs = blockIdx.x; fs < total; fs += gridDim.x) {
+    for (uint32_t fs = bid; fs < total; fs += nblk) {
         const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
         const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
         const uint32_t T = t.T[b];
@@ -784,17 +787,17 @@ __global__ __launch_bounds__(WG) void k_fb_count(const float *__restrict__ r, Ta
 
 /* Per tile of a fallback bucket: write the survivors to their final slots, in ascending
  * index order.  Inside a tile, thread t owns the quads (u*256 + t)*4, u = 0..3. */
-__global__ __launch_bounds__(WG) void k_fb_write(const float *__restrict__ r, Tables t,
-                                                 const uint32_t *__restrict__ tG,
-                                                 const uint32_t *__restrict__ tE,
-                                                 uint32_t *__restrict__ idx_out,
-                                                 float *__restrict__ v_out)
+__device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const Tables &t,
+                                              const uint32_t *__restrict__ tG,
+                                              const uint32_t *__restrict__ tE,
+                                              uint32_t *__restrict__ idx_out,
+                                              float *__restrict__ v_out, uint32_t (*tot)[2],
+                                              uint32_t bid, uint32_t nblk)
 {
-    __shared__ uint32_t tot[16][2];      /* slot = u * 4 + wavefront */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t total = t.fspan0[t.B];
-    for (uint32_t fs = blockIdx.x; fs < total; fs += gridDim.x) {
+    for (uint32_t fs = bid; fs < total; fs += nblk) {
         const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
         const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
         const uint32_t T = t.T[b], e_b = t.need[b];
@@ -851,6 +854,40 @@ __global__ __launch_bounds__(WG) void k_fb_write(const float *__restrict__ r, Ta
             __syncthreads();
         }
     }
+}
+
+/* ------------------------------------------------------------------ merged stages */
+
+/* Each selection stage is one launch: the first cgrid workgroups walk the candidate segments,
+ * the others walk the dense spans of the fallback buckets (usually none: they read the empty
+ * list and leave). */
+template <int LEVEL>
+__global__ __launch_bounds__(WG) void k_refine(const float *__restrict__ r, Tables t, Cand c,
+                                               uint32_t *__restrict__ hist_c, uint32_t *__restrict__ hist_f,
+                                               uint32_t cgrid)
+{
+    __shared__ uint32_t h[LEVEL == 1 ? NB1 : NB2];
+    if (blockIdx.x < cgrid) crefine_body<LEVEL>(t, c, hist_c, blockIdx.x, cgrid);
+    else fb_refine_body<LEVEL>(r, t, hist_f, h, blockIdx.x - cgrid, gridDim.x - cgrid);
+}
+
+__global__ __launch_bounds__(WG) void k_count(const float *__restrict__ r, Tables t, Cand c,
+                                              uint32_t *__restrict__ tG, uint32_t *__restrict__ tE,
+                                              uint32_t cgrid)
+{
+    __shared__ uint32_t cnt[MAX_SPAN_TILES][2];
+    if (blockIdx.x < cgrid) ccount_body(t, c, blockIdx.x, cgrid);
+    else fb_count_body(r, t, tG, tE, cnt, blockIdx.x - cgrid, gridDim.x - cgrid);
+}
+
+__global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Tables t, Cand c,
+                                              const uint32_t *__restrict__ tG, const uint32_t *__restrict__ tE,
+                                              uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
+                                              uint32_t cgrid)
+{
+    __shared__ uint32_t tot[16][2];      /* slot = u * 4 + wavefront */
+    if (blockIdx.x < cgrid) cwrite_body(t, c, idx_out, v_out, blockIdx.x, cgrid);
+    else fb_write_body(r, t, tG, tE, idx_out, v_out, tot, blockIdx.x - cgrid, gridDim.x - cgrid);
 }
 
 /* ------------------------------------------------------------------ value coding */
@@ -937,69 +974,91 @@ __device__ __forceinline__ float decode(const uint8_t *__restrict__ vb, const fl
     return __fmul_rn((float)q, sc[j / chunk]);
 }
 
+/* Where each tile's survivors start in its bucket's ascending index list: ts[tile0[b] + b + i]
+ * = number of survivors of bucket b with an index below tile i (i = 0..tiles_b).  One thread
+ * per survivor writes the entries of the tiles that begin between its predecessor and itself;
+ * the last survivor of a bucket also closes the bucket's remaining tiles. */
+__global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ idx, Tables t,
+                                                  uint64_t K, uint32_t *__restrict__ ts)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * WG;
+    for (uint64_t j = (uint64_t)blockIdx.x * WG + threadIdx.x; j < K; j += stride) {
+        const uint32_t b = find_bucket<uint64_t>(t.P, t.B, j);
+        const uint64_t lo = t.off[b];
+        const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
+        const uint32_t kb = t.k[b];
+        const uint32_t jj = (uint32_t)(j - t.P[b]);
+        uint32_t *tsb = ts + t.tile0[b] + b;
+        const uint32_t head = (uint32_t)(lo & 3ull);
+        /* tile of a local index; indices beyond the bucket (invalid payload) count as the last tile */
+        uint32_t tcur = (uint32_t)(((uint64_t)idx[j] + head) / TILE);
+        tcur = min(tcur, tiles_b - 1);
+        uint32_t tfrom = 0;                         /* first tile this thread fills */
+        if (jj > 0) {
+            uint32_t tprev = (uint32_t)(((uint64_t)idx[j - 1] + head) / TILE);
+            tprev = min(tprev, tiles_b - 1);
+            tfrom = tprev + 1;
+        }
+        for (uint32_t tt = tfrom; tt <= tcur; ++tt) tsb[tt] = jj;
+        if (jj == kb - 1)
+            for (uint32_t tt = tcur + 1; tt <= tiles_b; ++tt) tsb[tt] = kb;
+    }
+}
+
 /* Dense output for a span of tiles: each tile is assembled in LDS (zeros, then the decoded
- * survivors that fall inside it) and written out once with aligned 16-byte stores, so no
- * output line is touched twice and no atomics are needed.  The survivors of a span are a
- * contiguous run of the bucket's ascending index list: its start is found by a 256-ary
- * search, after that a running cursor follows the tiles. */
+ * survivors that fall inside it, found through the tile-start table) and written out once with
+ * aligned 16-byte stores, so no output line is touched twice and no atomics are needed.  The
+ * loads of the next tile's survivors are issued before the current tile is written out. */
 template <int BITS>
 __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx, const void *__restrict__ val,
                                                const float *__restrict__ scales, Tables t,
-                                               float *__restrict__ dense)
+                                               const uint32_t *__restrict__ ts, float *__restrict__ dense)
 {
     __shared__ float tile[TILE];
+    __shared__ uint32_t sts[MAX_SPAN_TILES + 1];
     const uint32_t tid = threadIdx.x;
     const SpanGeo s = span_geo(t, blockIdx.x);
     const uint32_t kb = t.k[s.b];
     const uint32_t *ib = idx + t.P[s.b];
     const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[s.b];
     const float *sb = BITS <= 8 ? scales + t.S[s.b] : nullptr;
+    const uint32_t nb = (uint32_t)(s.hi - s.lo);
+    const uint32_t first = s.tile_g - t.tile0[s.b];
+    if (tid <= s.ntiles) sts[tid] = min(ts[t.tile0[s.b] + s.b + first + tid], kb);
+    __syncthreads();
 
-    /* first survivor whose local index is >= the first local index of the span */
-    const uint64_t first_g = s.base > s.lo ? s.base : s.lo;
-    const uint32_t L0 = (uint32_t)(first_g - s.lo);
-    uint32_t a = 0, bnd = kb;                      /* answer in [a, bnd] */
-    while (bnd - a > WG) {
-        const uint32_t step = (bnd - a + WG - 1) / WG;
-        const uint64_t p = (uint64_t)a + (uint64_t)tid * step;
-        const int below = (p < bnd) && (ib[p] < L0);
-        const uint32_t c = __syncthreads_count(below);   /* flags are a prefix: idx ascending */
-        const uint64_t na = c ? (uint64_t)a + (uint64_t)(c - 1) * step + 1 : a;
-        const uint64_t nb = min((uint64_t)bnd, (uint64_t)a + (uint64_t)c * step);
-        a = (uint32_t)na; bnd = (uint32_t)nb;
-    }
-    {
-        const uint32_t p = a + tid;
-        const int below = (p < bnd) && (ib[p] < L0);
-        a += __syncthreads_count(below);
-    }
-    uint32_t cur = a;
-
+    /* survivor number j0 + tid of a tile, if it exists: local index and decoded value */
+    uint32_t p_li = NONE;
+    float p_x = 0.0f;
+    auto fetch = [&](uint32_t ti) {
+        p_li = NONE;
+        if (ti < s.ntiles) {
+            const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
+            const uint64_t j = (uint64_t)j0 + tid;
+            if (j < j1) { p_li = ib[j]; p_x = decode<BITS>(vb, sb, j, t.chunk); }
+        }
+    };
+    fetch(0);
     for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
         const uint64_t tb = s.base + (uint64_t)ti * TILE;
-        /* local index one past the tile's last valid element */
-        const uint64_t tend_g = tb + TILE < s.hi ? tb + TILE : s.hi;
-        const uint32_t L1 = (uint32_t)(tend_g - s.lo);
         const uint64_t shift = s.lo - tb;                   /* slot = local index + lo - tb (mod 2^64) */
 #pragma unroll
         for (int u = 0; u < 4; ++u)
             *reinterpret_cast<f4 *>(&tile[(u * WG + tid) * 4]) = f4{0.f, 0.f, 0.f, 0.f};
         __syncthreads();
-        for (;;) {
-            const uint64_t j = (uint64_t)cur + tid;
-            int in = 0;
-            if (j < kb) {
-                const uint32_t li = ib[j];
-                if (li < L1) {
-                    const uint64_t slot = (uint64_t)li + shift;
-                    if (slot < TILE) { tile[slot] = decode<BITS>(vb, sb, j, t.chunk); }
-                    in = 1;
-                }
-            }
-            const uint32_t c = __syncthreads_count(in);
-            cur += c;
-            if (c < WG) break;
+        if (p_li < nb) {
+            const uint64_t slot = (uint64_t)p_li + shift;
+            if (slot < TILE) tile[slot] = p_x;
         }
+        /* more than 256 survivors in the tile (ratio above 6 %) */
+        const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
+        for (uint64_t j = (uint64_t)j0 + WG + tid; j < j1; j += WG) {
+            const uint32_t li = ib[j];
+            const uint64_t slot = (uint64_t)li + shift;
+            if (li < nb && slot < TILE) tile[slot] = decode<BITS>(vb, sb, j, t.chunk);
+        }
+        fetch(ti + 1);
+        __syncthreads();
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t sl = (u * WG + tid) * 4;
@@ -1012,7 +1071,6 @@ __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx,
                     if (gi + j >= s.lo && gi + j < s.hi) dense[gi + j] = tile[sl + j];
             }
         }
-        __syncthreads();
     }
 }
 
@@ -1032,12 +1090,13 @@ struct nsml_ctx {
 
     /* device workspace */
     uint64_t *d_off, *d_P, *d_V, *d_S, *d_C;
-    uint32_t *d_tile0, *d_span0, *d_samp0, *d_span_b, *d_k, *d_T, *d_need, *d_T0, *d_need0, *d_L, *d_fast, *d_fspan0;
+    uint32_t *d_tile0, *d_span0, *d_samp0, *d_span_b, *d_k, *d_T, *d_need, *d_L, *d_fast, *d_fspan0;
     uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
     uint32_t *d_tG, *d_tE; /* per tile (fallback path) */
     uint32_t *d_ccnt, *d_cG, *d_cE, *d_cidx;   /* candidate staging */
     float *d_cval;
     float *d_v;            /* survivor values in final order (not used for bits == 32) */
+    uint32_t *d_ts;        /* decompress: where each tile's survivors start */
 
     /* host copies / caches */
     std::vector<uint64_t> h_off;
@@ -1050,6 +1109,7 @@ struct nsml_ctx {
     void *pinned; size_t pinned_bytes;
     int span_override;
     int force_dense;
+    int nt_mode;
 
     /* profiling */
     bool prof;
@@ -1086,9 +1146,9 @@ int dev_alloc(nsml_ctx *c, T **p, uint64_t count)
 
 /* words of the per-call zeroed area: hist0, sample hist, candidate level 1/2, fallback level
  * 1/2 histograms, overflow flags */
-uint64_t zero_words(uint64_t B) { return B * (uint64_t)(NB0 + NB0 + NB1 + NB2 + NB1 + NB2 + 1); }
+uint64_t zero_words(uint64_t B) { return B * (uint64_t)(NB0 + NB0 + NB1 + NB2 + NB1 + NB2 + 1) + 16; }
 
-struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *ovf; };
+struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *ovf, *ticket, *err; };
 Hists hists_of(const nsml_ctx *c, uint32_t B)
 {
     Hists h;
@@ -1099,6 +1159,8 @@ Hists hists_of(const nsml_ctx *c, uint32_t B)
     h.f1 = h.c2 + (uint64_t)B * NB2;
     h.f2 = h.f1 + (uint64_t)B * NB1;
     h.ovf = h.f2 + (uint64_t)B * NB2;
+    h.ticket = h.ovf + B;
+    h.err = h.ticket + 1;
     return h;
 }
 
@@ -1108,7 +1170,7 @@ Tables tables_of(const nsml_ctx *c)
     t.off = c->d_off; t.tile0 = c->d_tile0; t.span0 = c->d_span0; t.samp0 = c->d_samp0;
     t.span_b = c->d_span_b;
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
-    t.T = c->d_T; t.need = c->d_need; t.T0 = c->d_T0; t.need0 = c->d_need0; t.L = c->d_L; t.fast = c->d_fast;
+    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.fast = c->d_fast;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.chunk = c->chunk;
     return t;
@@ -1154,6 +1216,9 @@ int prof_end(nsml_ctx *c, int kid, hipStream_t st)
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+/* Tiles per span (one span = one workgroup of the streaming kernels, four candidate
+ * segments).  Small spans stream a few per cent faster, large spans mean fewer segments for
+ * the candidate kernels to walk; measured on 25 M .. 6.7 G elements the totals favour this. */
 uint32_t pick_span_tiles(uint32_t n_tiles, int override_)
 {
     if (override_ >= 1 && override_ <= MAX_SPAN_TILES) return (uint32_t)override_;
@@ -1270,13 +1335,15 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->prof = false; c->pinned = nullptr; c->pinned_bytes = 0;
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
-    c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = c->d_T0 = c->d_need0 = nullptr;
+    c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
-    c->d_cval = nullptr; c->d_v = nullptr;
+    c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
     const char *fd = getenv("NSML_FORCE_DENSE");
     c->force_dense = (fd && atoi(fd) != 0) ? 1 : 0;
+    const char *ntm = getenv("NSML_NT");
+    c->nt_mode = ntm ? atoi(ntm) : 7;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
@@ -1301,7 +1368,6 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_S, B1)); A(dev_alloc(c, &c->d_C, B1));
     A(dev_alloc(c, &c->d_tile0, B1)); A(dev_alloc(c, &c->d_span0, B1)); A(dev_alloc(c, &c->d_samp0, B1));
     A(dev_alloc(c, &c->d_k, B1)); A(dev_alloc(c, &c->d_T, B1)); A(dev_alloc(c, &c->d_need, B1));
-    A(dev_alloc(c, &c->d_T0, B1)); A(dev_alloc(c, &c->d_need0, B1));
     A(dev_alloc(c, &c->d_L, B1)); A(dev_alloc(c, &c->d_fast, B1)); A(dev_alloc(c, &c->d_fspan0, B1));
     A(dev_alloc(c, &c->d_span_b, mt));
     A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
@@ -1309,6 +1375,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_ccnt, 4 * mt)); A(dev_alloc(c, &c->d_cG, 4 * mt)); A(dev_alloc(c, &c->d_cE, 4 * mt));
     A(dev_alloc(c, &c->d_cidx, c->max_cand)); A(dev_alloc(c, &c->d_cval, c->max_cand));
     A(dev_alloc(c, &c->d_v, max_n));
+    A(dev_alloc(c, &c->d_ts, mt + B1 + 1));
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
@@ -1325,9 +1392,9 @@ int nsml_destroy(nsml_ctx *c)
     DeviceGuard guard(c->device);
     (void)hipDeviceSynchronize();
     void *ptrs[] = {c->d_off, c->d_P, c->d_V, c->d_S, c->d_C, c->d_tile0, c->d_span0, c->d_samp0,
-                    c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_T0, c->d_need0, c->d_L, c->d_fast, c->d_fspan0,
+                    c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
-                    c->d_cval, c->d_v};
+                    c->d_cval, c->d_v, c->d_ts};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -1370,30 +1437,30 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
     if (!c->force_dense)
         LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
     LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
-    if (!c->force_dense)
-        LAUNCH(c, KID_EF_EMIT, st, k_ef_emit<true>, c->n_spans, grad, residual, t, h.h0, cd);
-    else
-        LAUNCH(c, KID_EF_EMIT, st, k_ef_emit<false>, c->n_spans, grad, residual, t, h.h0, cd);
-    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0);
-    if (!c->force_dense) {
-        LAUNCH(c, KID_CREFINE1, st, k_crefine<1>, cgrid, t, cd, h.c1);
-        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, 1u);
-        LAUNCH(c, KID_CREFINE2, st, k_crefine<2>, cgrid, t, cd, h.c2);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, 1u);
-        LAUNCH(c, KID_CCOUNT, st, k_ccount, cgrid, t, cd);
-        LAUNCH(c, KID_CSCAN, st, k_scan, B, t, cd.G, cd.E, 1u);
-        LAUNCH(c, KID_CWRITE, st, k_cwrite, cgrid, t, cd, idx, vdst);
+    if (c->force_dense) {
+        LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7>), c->n_spans, grad, residual, t, h.h0, cd);
+    } else {
+        switch (c->nt_mode) {
+        case 1:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 1>), c->n_spans, grad, residual, t, h.h0, cd); break;
+        case 3:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 3>), c->n_spans, grad, residual, t, h.h0, cd); break;
+        case 5:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 5>), c->n_spans, grad, residual, t, h.h0, cd); break;
+        default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7>), c->n_spans, grad, residual, t, h.h0, cd); break;
+        }
     }
-    /* buckets the candidates could not decide: the same steps over the dense accumulator */
+    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0);
     LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
-    LAUNCH(c, KID_FB_REFINE1, st, k_fb_refine<1>, fgrid, (const float *)residual, t, h.f1);
-    LAUNCH(c, KID_FB_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.f1, 0u);
-    LAUNCH(c, KID_FB_REFINE2, st, k_fb_refine<2>, fgrid, (const float *)residual, t, h.f2);
-    LAUNCH(c, KID_FB_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.f2, 0u);
-    LAUNCH(c, KID_FB_COUNT, st, k_fb_count, fgrid, (const float *)residual, t, c->d_tG, c->d_tE);
-    LAUNCH(c, KID_FB_SCAN, st, k_scan, B, t, c->d_tG, c->d_tE, 0u);
-    LAUNCH(c, KID_FB_WRITE, st, k_fb_write, fgrid, (const float *)residual, t,
-           (const uint32_t *)c->d_tG, (const uint32_t *)c->d_tE, idx, vdst);
+    /* every stage serves both kinds of bucket: candidate segments first, then the dense
+     * spans of the buckets the candidates could not decide */
+    const uint32_t cg = c->force_dense ? 0u : cgrid;
+    const float *acc = residual;
+    LAUNCH(c, KID_REFINE1, st, k_refine<1>, cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
+    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err);
+    LAUNCH(c, KID_REFINE2, st, k_refine<2>, cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
+    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err);
+    LAUNCH(c, KID_COUNT, st, k_count, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
+    LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE);
+    LAUNCH(c, KID_WRITE, st, k_write, cg + fgrid, acc, t, cd, (const uint32_t *)c->d_tG,
+           (const uint32_t *)c->d_tE, idx, vdst, cg);
     const uint32_t qgrid = (uint32_t)c->NC;
     switch (bits) {
     case 32: LAUNCH(c, KID_QUANT, st, k_quant<32>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
@@ -1420,11 +1487,14 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     rc = ensure_tables(c, ratio, bits, st);
     if (rc) return rc;
     const Tables t = tables_of(c);
+    const uint64_t want = (c->K + WG - 1) / WG;
+    LAUNCH(c, KID_TILESTART, st, k_tilestart, (uint32_t)(want < 16384 ? want : 16384), idx, t, c->K, c->d_ts);
+    const uint32_t *ts = c->d_ts;
     switch (bits) {
-    case 32: LAUNCH(c, KID_DECOMP, st, k_decomp<32>, c->n_spans, idx, val, scales, t, dense_out); break;
-    case 16: LAUNCH(c, KID_DECOMP, st, k_decomp<16>, c->n_spans, idx, val, scales, t, dense_out); break;
-    case 8:  LAUNCH(c, KID_DECOMP, st, k_decomp<8>,  c->n_spans, idx, val, scales, t, dense_out); break;
-    default: LAUNCH(c, KID_DECOMP, st, k_decomp<4>,  c->n_spans, idx, val, scales, t, dense_out); break;
+    case 32: LAUNCH(c, KID_DECOMP, st, k_decomp<32>, c->n_spans, idx, val, scales, t, ts, dense_out); break;
+    case 16: LAUNCH(c, KID_DECOMP, st, k_decomp<16>, c->n_spans, idx, val, scales, t, ts, dense_out); break;
+    case 8:  LAUNCH(c, KID_DECOMP, st, k_decomp<8>,  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+    default: LAUNCH(c, KID_DECOMP, st, k_decomp<4>,  c->n_spans, idx, val, scales, t, ts, dense_out); break;
     }
     return NSML_OK;
 }
@@ -1467,7 +1537,9 @@ int nsml_path_stats(nsml_ctx *c, uint32_t *fast_buckets, uint32_t *fallback_buck
         if (c->h_off[b + 1] == c->h_off[b]) continue;
         if (f[b]) *fast_buckets += 1; else *fallback_buckets += 1;
     }
-    return NSML_OK;
+    uint32_t err = 0;
+    NSML_HIP(c, hipMemcpy(&err, hists_of(c, c->B).err, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    return err ? NSML_EINTERNAL : NSML_OK;
 }
 
 int nsml_calibration_copy(const void *src, void *dst, uint64_t bytes, void *stream)

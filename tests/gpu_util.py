@@ -76,6 +76,7 @@ class Case:
         idx, val, sc = ctx.compress(self.g, self.r, off, ratio, bits)
         dense = ctx.decompress(idx, val, sc, self.n, off, ratio, bits)
         torch.cuda.synchronize()
+        ctx.path_stats()                      # raises if a device-side consistency check tripped
         w_idx, w_val, w_sc = oracle.compress(self.g_host, self.r_host, off, ratio, bits, chunk, nthreads=threads)
         k_b, K, vb, ns = oracle.layout(off, ratio, bits, chunk)
         got = (idx.cpu().numpy().view(np.uint32)[:K], val.cpu().numpy()[:vb], sc.cpu().numpy()[:ns])
