@@ -175,6 +175,23 @@ int nsml_decompress(nsml_ctx *ctx, const uint32_t *idx, const void *val, const f
                     uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
                     float *dense_out, void *stream);
 
+/* Receiver side of an all-gather of payloads (the communication pattern the paper reports for
+ * sparsified gradients, Sec. 5.3): add one payload into a dense gradient that is being
+ * accumulated.  dense_inout[bucket_off[b] + idx[j]] += decoded value j; no other element is
+ * read or written.  Same arguments as nsml_decompress.  Calling it once per peer on a zeroed
+ * buffer sums the peers' sparse gradients. */
+int nsml_decompress_accumulate(nsml_ctx *ctx, const uint32_t *idx, const void *val,
+                               const float *scales, uint64_t n, const uint64_t *bucket_off,
+                               uint32_t B, double ratio, int bits, float *dense_inout, void *stream);
+
+/* L2 norm of the gradient handed to the last nsml_compress of the context: a by-product of its
+ * streaming pass (no extra memory traffic), for the density test of Algorithm 2 Step 1
+ * (pass it as last_l2norm to nsml_choose_ratio).  total: norm over the whole gradient;
+ * per_bucket: host array of B norms, or NULL.  The sums are accumulated in double over a fixed
+ * reduction tree (binary32 products inside groups of four), so the value does not depend on
+ * scheduling.  Synchronises the device.  NSML_EINVAL before the first compress. */
+int nsml_last_l2norm(nsml_ctx *ctx, double *total, double *per_bucket);
+
 /* ------------------------------------------------------------------ measurement */
 
 #define NSML_MAX_KERNELS 32

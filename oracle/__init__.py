@@ -61,6 +61,10 @@ def lib() -> C.CDLL:
             L.orc_compress.argtypes = [vp, vp, u64, vp, u32, dbl, i32, u32, vp, vp, vp, i32]
             L.orc_decompress.restype = i32
             L.orc_decompress.argtypes = [vp, vp, vp, u64, vp, u32, dbl, i32, u32, vp, i32]
+            L.orc_decompress_accumulate.restype = i32
+            L.orc_decompress_accumulate.argtypes = [vp, vp, vp, u64, vp, u32, dbl, i32, u32, vp]
+            L.orc_l2norm.restype = dbl
+            L.orc_l2norm.argtypes = [vp, vp, u32, vp]
             L.orc_f32_to_f16.restype = C.c_uint16
             L.orc_f32_to_f16.argtypes = [C.c_float]
             L.orc_f16_to_f32.restype = C.c_float
@@ -124,6 +128,30 @@ def decompress(idx, val, scales, n: int, bucket_off, ratio: float, bits: int, ch
     if rc != 0:
         raise ValueError("orc_decompress rc=%d" % rc)
     return dense
+
+
+def decompress_accumulate(idx, val, scales, dense, bucket_off, ratio: float, bits: int,
+                          chunk: int = 2048):
+    """dense[off_b + idx[j]] += decoded value j, in place (dense: contiguous float32)."""
+    off = np.ascontiguousarray(bucket_off, dtype=np.uint64)
+    idx = np.ascontiguousarray(idx, dtype=np.uint32)
+    val = np.ascontiguousarray(val).view(np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    assert dense.dtype == np.float32 and dense.flags.c_contiguous
+    rc = lib().orc_decompress_accumulate(_p(idx), _p(val), _p(scales), dense.size, _p(off),
+                                         len(off) - 1, float(ratio), int(bits), int(chunk), _p(dense))
+    if rc != 0:
+        raise ValueError("orc_decompress_accumulate rc=%d" % rc)
+    return dense
+
+
+def l2norm(grad, bucket_off):
+    """-> (norm of the whole gradient, per-bucket norms), accumulated in double."""
+    g = np.ascontiguousarray(grad, dtype=np.float32)
+    off = np.ascontiguousarray(bucket_off, dtype=np.uint64)
+    per = np.zeros(len(off) - 1, dtype=np.float64)
+    tot = lib().orc_l2norm(_p(g), _p(off), len(off) - 1, _p(per))
+    return float(tot), per
 
 
 def compress_bucket(grad, residual, ratio: float, bits: int, chunk: int = 2048):

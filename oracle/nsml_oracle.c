@@ -338,6 +338,47 @@ int orc_decompress(const uint32_t *idx, const void *val, const float *scales, ui
     return err;
 }
 
+/* Receiver side of an all-gather of sparse payloads (Sec. 5.3 reports AllGather as the pattern
+ * for TopK): dense[idx[j]] += decoded value j, one binary32 add per survivor; everything else
+ * in dense is left alone. */
+int orc_decompress_accumulate(const uint32_t *idx, const void *val, const float *scales, uint64_t n,
+                              const uint64_t *off, uint32_t B, double ratio, int bits,
+                              uint32_t chunk, float *dense)
+{
+    if (!off || B == 0 || off[0] != 0 || off[B] != n || !dense) return ORC_EINVAL;
+    float *tmp = (float *)malloc((size_t)(n ? n : 1) * sizeof(float));
+    if (!tmp) return ORC_ENOMEM;
+    /* decode into a scratch dense vector with the plain decompressor, then add where a survivor sits */
+    int rc = orc_decompress(idx, val, scales, n, off, B, ratio, bits, chunk, tmp, 1);
+    if (rc == ORC_OK) {
+        uint64_t p = 0;
+        for (uint32_t b = 0; b < B; ++b) {
+            uint64_t k = orc_k(ratio, off[b + 1] - off[b]);
+            for (uint64_t j = 0; j < k; ++j, ++p) {
+                uint64_t i = off[b] + idx[p];
+                volatile float sum = dense[i] + tmp[i];
+                dense[i] = sum;
+            }
+        }
+    }
+    free(tmp);
+    return rc;
+}
+
+/* Algorithm 2 Step 1: calculate_L2_norm(grads), in double, in index order.  per_bucket (B
+ * entries) may be NULL.  Returns the norm of the whole gradient. */
+double orc_l2norm(const float *g, const uint64_t *off, uint32_t B, double *per_bucket)
+{
+    double total = 0.0;
+    for (uint32_t b = 0; b < B; ++b) {
+        double s = 0.0;
+        for (uint64_t i = off[b]; i < off[b + 1]; ++i) s += (double)g[i] * (double)g[i];
+        if (per_bucket) per_bucket[b] = sqrt(s);
+        total += s;
+    }
+    return sqrt(total);
+}
+
 /* Exposed so tests can pin the conversions against numpy's binary16. */
 uint16_t orc_f32_to_f16(float x) { return f32_to_f16(x); }
 float orc_f16_to_f32(uint16_t h) { return f16_to_f32(h); }

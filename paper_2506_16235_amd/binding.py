@@ -64,6 +64,10 @@ _lib.nsml_profile_enable.argtypes = [_vp, _i32]
 _lib.nsml_profile_read.argtypes = [_vp, _vp, _vp]
 _lib.nsml_path_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
 _lib.nsml_path_stats.restype = _i32
+_lib.nsml_decompress_accumulate.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp]
+_lib.nsml_decompress_accumulate.restype = _i32
+_lib.nsml_last_l2norm.argtypes = [_vp, C.POINTER(_dbl), _vp]
+_lib.nsml_last_l2norm.restype = _i32
 _lib.nsml_calibration_copy.argtypes = [_vp, _vp, _u64, _vp]
 _lib.nsml_calibration_copy.restype = _i32
 _lib.nsml_kernel_name.argtypes = [_i32]
@@ -212,6 +216,25 @@ class Context:
         _check(rc, "nsml_decompress", self._h)
         return out
 
+    def decompress_accumulate(self, idx, val, scales, bucket_off, ratio: float, bits: int,
+                              dense: torch.Tensor) -> torch.Tensor:
+        """dense[bucket_off[b] + idx[j]] += decoded value j, in place."""
+        off = _off(bucket_off)
+        assert dense.dtype == torch.float32 and dense.is_contiguous()
+        rc = _lib.nsml_decompress_accumulate(self._h, _ptr(idx), _ptr(val), _ptr(scales),
+                                             dense.numel(), off.ctypes.data, len(off) - 1,
+                                             float(ratio), int(bits), _ptr(dense), _stream(self.device))
+        _check(rc, "nsml_decompress_accumulate", self._h)
+        return dense
+
+    def last_l2norm(self, n_buckets: int = 0):
+        """-> (norm of the last compressed gradient, per-bucket norms or None).  Synchronises."""
+        tot = _dbl()
+        per = np.zeros(n_buckets, dtype=np.float64) if n_buckets else None
+        _check(_lib.nsml_last_l2norm(self._h, C.byref(tot), per.ctypes.data if n_buckets else None),
+               "nsml_last_l2norm", self._h)
+        return tot.value, per
+
     def path_stats(self):
         """-> (fast buckets, fallback buckets) of the last compress call (synchronises)."""
         a, b = _u32(), _u32()
@@ -232,6 +255,10 @@ class Context:
             if name is not None and n[i]:
                 out[name.decode()] = (int(n[i]), float(ms[i]))
         return out
+
+
+def decompress_accumulate(ctx: Context, idx, val, scales, bucket_off, ratio, bits, dense):
+    return ctx.decompress_accumulate(idx, val, scales, bucket_off, ratio, bits, dense)
 
 
 def calibration_copy(src: torch.Tensor, dst: torch.Tensor):

@@ -57,18 +57,18 @@ constexpr int MAX_SPAN_TILES = 16;
 constexpr uint32_t NONE = 0xFFFFFFFFu;
 constexpr uint32_t SAMPLE_ALL_BELOW = 262144;  /* buckets smaller than this are sampled in full */
 constexpr uint32_t SAMPLE_STRIDE = 64;         /* larger ones: 32 elements out of every 2048 */
-constexpr uint32_t RUNS_PER_WG = 512;          /* sample runs (32 elements each) per workgroup */
+constexpr uint32_t RUNS_PER_WG = 128;          /* sample runs (32 elements each) per workgroup */
 constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
 
 enum KernelId {
     KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
     KID_REFINE1, KID_PICK1, KID_REFINE2, KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE,
-    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_N
+    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_N
 };
 const char *const kKernelNames[KID_N] = {
     "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan", "fb_plan",
     "refine1", "pick1", "refine2", "pick2", "count", "scan", "write",
-    "quant", "tilestart", "decomp"
+    "quant", "tilestart", "decomp", "decomp_acc"
 };
 static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
 
@@ -267,20 +267,27 @@ __device__ __forceinline__ void hist_flush(const uint32_t *h, uint32_t *__restri
     }
 }
 
-/* Inclusive scan over the 256 threads of a workgroup (tmp: 256 words of LDS). */
+/* Inclusive scan over the 256 threads of a workgroup: shuffles inside each wavefront, one
+ * exchange of the four wavefront totals through LDS.  tmp needs WG words; on return
+ * tmp[WG - 1] holds the grand total (callers read it, then synchronise before reusing tmp). */
 __device__ __forceinline__ uint32_t block_incl_scan(uint32_t x, uint32_t *tmp)
 {
-    const uint32_t tid = threadIdx.x;
-    tmp[tid] = x;
-    __syncthreads();
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-    for (int d = 1; d < WG; d <<= 1) {
-        const uint32_t y = tid >= (uint32_t)d ? tmp[tid - d] : 0u;
-        __syncthreads();
-        x += y;
-        tmp[tid] = x;
-        __syncthreads();
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, 64);
+        if (lane >= (uint32_t)d) x += y;
     }
+    if (lane == 63) tmp[wave] = x;
+    __syncthreads();
+    uint32_t add = 0;
+#pragma unroll
+    for (int w = 0; w < WG / 64; ++w) add += (uint32_t)w < wave ? tmp[w] : 0u;
+    const uint32_t total = tmp[0] + tmp[1] + tmp[2] + tmp[3];
+    __syncthreads();
+    x += add;
+    if (tid == WG - 1) tmp[WG - 1] = total;
+    __syncthreads();
     return x;
 }
 
@@ -447,9 +454,12 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
  * segment, so candidates come out in index order without any cross-wavefront exchange. */
 template <bool EMIT, int NT>
 __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
-                                                Tables t, uint32_t *__restrict__ hist0, Cand c)
+                                                Tables t, uint32_t *__restrict__ hist0, Cand c,
+                                                double *__restrict__ span_sq)
 {
     __shared__ uint32_t h[NB0];
+    __shared__ double sq_w[WG / 64];
+    double sq = 0.0;                     /* sum of grad^2 over this thread's elements */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < NB0; i += WG) h[i] = 0;
     const SpanGeo s = span_geo(t, blockIdx.x);
@@ -480,6 +490,8 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
                 float a[4];
                 a[0] = __fadd_rn(gv[u].x, rv[u].x); a[1] = __fadd_rn(gv[u].y, rv[u].y);
                 a[2] = __fadd_rn(gv[u].z, rv[u].z); a[3] = __fadd_rn(gv[u].w, rv[u].w);
+                sq += (double)(__fmaf_rn(gv[u].x, gv[u].x, __fmul_rn(gv[u].y, gv[u].y)) +
+                               __fmaf_rn(gv[u].z, gv[u].z, __fmul_rn(gv[u].w, gv[u].w)));
                 ef_row<true, EMIT, NT>(r, gi, a, 0xFu, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         } else {
@@ -490,7 +502,7 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
                 const uint32_t m = load_quad(g, gi, s.lo, s.hi, x);
                 load_quad(r, gi, s.lo, s.hi, y);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) a[j] = __fadd_rn(x[j], y[j]);
+                for (int j = 0; j < 4; ++j) { a[j] = __fadd_rn(x[j], y[j]); sq += (double)__fmul_rn(x[j], x[j]); }
                 ef_row<false, EMIT, NT>(r, gi, a, m, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         }
@@ -499,16 +511,33 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
         c.cnt[ss] = min(wcount, c.cap);
         if (wcount > c.cap) t.ovf[s.b] = 1u;
     }
+    /* the span's share of |grad|^2 (by-product for the density test of Algorithm 2 Step 1):
+     * fixed reduction tree, so the sum does not depend on scheduling */
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, 64);
+    if (lane == 0) sq_w[wave] = sq;
     __syncthreads();
+    if (tid == 0) span_sq[blockIdx.x] = (sq_w[0] + sq_w[1]) + (sq_w[2] + sq_w[3]);
     hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
 }
 
 /* Per bucket: exact level-0 digit of the k-th largest key, and whether the candidates can
  * decide the bucket. */
-__global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restrict__ hist0)
+__global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restrict__ hist0,
+                                             const double *__restrict__ span_sq, double *__restrict__ l2sq)
 {
     __shared__ uint32_t tmp[WG];
+    __shared__ double red[WG / 64];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    {   /* |grad|^2 of the bucket: strided partial sums, then a fixed tree */
+        double acc = 0.0;
+        for (uint32_t s = t.span0[b] + tid; s < t.span0[b + 1]; s += WG) acc += span_sq[s];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+        if ((tid & 63) == 0) red[tid >> 6] = acc;
+        __syncthreads();
+        if (tid == 0) l2sq[b] = (red[0] + red[1]) + (red[2] + red[3]);
+    }
     const uint32_t want = t.k[b];
     if (want == 0) {                       /* empty bucket: nothing can match */
         if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; }
@@ -981,9 +1010,16 @@ __device__ __forceinline__ float decode(const uint8_t *__restrict__ vb, const fl
 __global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ idx, Tables t,
                                                   uint64_t K, uint32_t *__restrict__ ts)
 {
+    constexpr uint32_t LDS_B = 2047;
+    __shared__ uint64_t sP[LDS_B + 1];
+    const bool in_lds = t.B <= LDS_B;
+    if (in_lds) {
+        for (uint32_t i = threadIdx.x; i <= t.B; i += WG) sP[i] = t.P[i];
+        __syncthreads();
+    }
     const uint64_t stride = (uint64_t)gridDim.x * WG;
     for (uint64_t j = (uint64_t)blockIdx.x * WG + threadIdx.x; j < K; j += stride) {
-        const uint32_t b = find_bucket<uint64_t>(t.P, t.B, j);
+        const uint32_t b = in_lds ? find_bucket<uint64_t>(sP, t.B, j) : find_bucket<uint64_t>(t.P, t.B, j);
         const uint64_t lo = t.off[b];
         const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
         const uint32_t kb = t.k[b];
@@ -1074,6 +1110,35 @@ __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx,
     }
 }
 
+/* Receiver side of an all-gather of payloads: add one worker's decoded survivors into a dense
+ * gradient that is being accumulated (nothing else is touched).  One thread per survivor;
+ * the indices of a payload are distinct, so plain read-modify-write needs no atomics. */
+template <int BITS>
+__global__ __launch_bounds__(WG) void k_decomp_acc(const uint32_t *__restrict__ idx, const void *__restrict__ val,
+                                                   const float *__restrict__ scales, Tables t, uint64_t K,
+                                                   float *__restrict__ dense)
+{
+    constexpr uint32_t LDS_B = 2047;
+    __shared__ uint64_t sP[LDS_B + 1];
+    const bool in_lds = t.B <= LDS_B;
+    if (in_lds) {
+        for (uint32_t i = threadIdx.x; i <= t.B; i += WG) sP[i] = t.P[i];
+        __syncthreads();
+    }
+    const uint64_t stride = (uint64_t)gridDim.x * WG;
+    for (uint64_t j = (uint64_t)blockIdx.x * WG + threadIdx.x; j < K; j += stride) {
+        const uint32_t b = in_lds ? find_bucket<uint64_t>(sP, t.B, j) : find_bucket<uint64_t>(t.P, t.B, j);
+        const uint64_t lo = t.off[b], nb = t.off[b + 1] - lo;
+        const uint64_t jj = j - t.P[b];
+        const uint32_t li = idx[j];
+        if (li >= nb) continue;                       /* invalid payload: never leave the bucket */
+        const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[b];
+        const float *sb = BITS <= 8 ? scales + t.S[b] : nullptr;
+        const float x = decode<BITS>(vb, sb, jj, t.chunk);
+        dense[lo + li] = __fadd_rn(dense[lo + li], x);
+    }
+}
+
 }  // namespace
 
 /* ====================================================================== host side */
@@ -1097,6 +1162,9 @@ struct nsml_ctx {
     float *d_cval;
     float *d_v;            /* survivor values in final order (not used for bits == 32) */
     uint32_t *d_ts;        /* decompress: where each tile's survivors start */
+    double *d_span_sq;     /* per span: sum of grad^2 */
+    double *d_l2sq;        /* per bucket: sum of grad^2 of the last compress call */
+    bool have_l2;
 
     /* host copies / caches */
     std::vector<uint64_t> h_off;
@@ -1337,7 +1405,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
-    c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr;
+    c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
     const char *fd = getenv("NSML_FORCE_DENSE");
@@ -1376,6 +1444,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_cidx, c->max_cand)); A(dev_alloc(c, &c->d_cval, c->max_cand));
     A(dev_alloc(c, &c->d_v, max_n));
     A(dev_alloc(c, &c->d_ts, mt + B1 + 1));
+    A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
@@ -1394,7 +1463,7 @@ int nsml_destroy(nsml_ctx *c)
     void *ptrs[] = {c->d_off, c->d_P, c->d_V, c->d_S, c->d_C, c->d_tile0, c->d_span0, c->d_samp0,
                     c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
-                    c->d_cval, c->d_v, c->d_ts};
+                    c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -1438,16 +1507,16 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
         LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
     LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
     if (c->force_dense) {
-        LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7>), c->n_spans, grad, residual, t, h.h0, cd);
+        LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
     } else {
         switch (c->nt_mode) {
-        case 1:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 1>), c->n_spans, grad, residual, t, h.h0, cd); break;
-        case 3:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 3>), c->n_spans, grad, residual, t, h.h0, cd); break;
-        case 5:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 5>), c->n_spans, grad, residual, t, h.h0, cd); break;
-        default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7>), c->n_spans, grad, residual, t, h.h0, cd); break;
+        case 1:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 1>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        case 3:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 3>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        case 5:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 5>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
         }
     }
-    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0);
+    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const double *)c->d_span_sq, c->d_l2sq);
     LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
     /* every stage serves both kinds of bucket: candidate segments first, then the dense
      * spans of the buckets the candidates could not decide */
@@ -1468,6 +1537,7 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
     case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
     default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
     }
+    c->have_l2 = true;
     return NSML_OK;
 }
 
@@ -1496,6 +1566,52 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     case 8:  LAUNCH(c, KID_DECOMP, st, k_decomp<8>,  c->n_spans, idx, val, scales, t, ts, dense_out); break;
     default: LAUNCH(c, KID_DECOMP, st, k_decomp<4>,  c->n_spans, idx, val, scales, t, ts, dense_out); break;
     }
+    return NSML_OK;
+}
+
+int nsml_decompress_accumulate(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,
+                               uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio,
+                               int bits, float *dense_inout, void *stream)
+{
+    if (!c || !idx || !val || !dense_inout) return NSML_EINVAL;
+    if ((bits == 8 || bits == 4) && !scales) return NSML_EINVAL;
+    if (!aligned(dense_inout, 16) || !aligned(idx, 4) || !aligned(val, 4) || !aligned(scales, 4))
+        return NSML_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    DeviceGuard guard(c->device);
+    if (!guard.ok) { c->last_hip = (int)hipErrorInvalidDevice; return NSML_EHIP; }
+    int rc = ensure_layout(c, n, bucket_off, B, st);
+    if (rc) return rc;
+    rc = ensure_tables(c, ratio, bits, st);
+    if (rc) return rc;
+    const Tables t = tables_of(c);
+    const uint64_t want = (c->K + WG - 1) / WG;
+    const uint32_t grid = (uint32_t)(want < 32768 ? want : 32768);
+    switch (bits) {
+    case 32: LAUNCH(c, KID_DECOMP_ACC, st, k_decomp_acc<32>, grid, idx, val, scales, t, c->K, dense_inout); break;
+    case 16: LAUNCH(c, KID_DECOMP_ACC, st, k_decomp_acc<16>, grid, idx, val, scales, t, c->K, dense_inout); break;
+    case 8:  LAUNCH(c, KID_DECOMP_ACC, st, k_decomp_acc<8>,  grid, idx, val, scales, t, c->K, dense_inout); break;
+    default: LAUNCH(c, KID_DECOMP_ACC, st, k_decomp_acc<4>,  grid, idx, val, scales, t, c->K, dense_inout); break;
+    }
+    return NSML_OK;
+}
+
+int nsml_last_l2norm(nsml_ctx *c, double *total, double *per_bucket)
+{
+    if (!c || !total) return NSML_EINVAL;
+    *total = 0.0;
+    if (!c->have_l2 || c->B == 0) return NSML_EINVAL;
+    DeviceGuard guard(c->device);
+    NSML_HIP(c, hipDeviceSynchronize());
+    std::vector<double> sq(c->B);
+    NSML_HIP(c, hipMemcpy(sq.data(), c->d_l2sq, sizeof(double) * c->B, hipMemcpyDeviceToHost));
+    double sum = 0.0;
+    for (uint32_t b = 0; b < c->B; ++b) {
+        const double v = c->h_off[b + 1] > c->h_off[b] ? sq[b] : 0.0;
+        sum += v;
+        if (per_bucket) per_bucket[b] = sqrt(v);
+    }
+    *total = sqrt(sum);
     return NSML_OK;
 }
 

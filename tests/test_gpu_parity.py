@@ -196,3 +196,44 @@ def test_gpu_argument_errors():
     with pytest.raises(nsml.NsmlError) as e:
         ctx.compress(g[1:], r[1:], W.offsets_of([9_999]), 0.5, 8)          # misaligned
     assert e.value.code == nsml.EINVAL
+
+
+def test_l2norm_byproduct():
+    """The streaming pass also returns |grad|_2 (density test of Algorithm 2 Step 1): within
+    1e-6 relative of the oracle's double-precision norm, per bucket and in total, and the same
+    bits on a second run."""
+    sizes = [1, 64, 4097, 0, 300_003, 7, 1_000_001]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    g = _rand(n, 77, sigma=3e-3)
+    ctx = nsml.Context(n, len(sizes), 64)
+    got = []
+    for _ in range(2):
+        r = _rand(n, 78)
+        ctx.compress(g, r, off, 0.01, 8)
+        got.append(ctx.last_l2norm(len(sizes)))
+    want_tot, want_per = oracle.l2norm(g.cpu().numpy(), off)
+    tot, per = got[0]
+    assert abs(tot - want_tot) <= 1e-6 * want_tot
+    assert np.all(np.abs(per - want_per) <= 1e-6 * np.maximum(want_per, 1e-30))
+    assert per[3] == 0.0
+    assert got[0][0] == got[1][0] and np.array_equal(got[0][1], got[1][1])
+
+
+@pytest.mark.parametrize("bits", [4, 8, 16, 32])
+def test_decompress_accumulate(bits):
+    """Three workers' payloads summed into one dense buffer, bit-exact against the oracle."""
+    sizes = [5, 70_000, 0, 33_333, 100_001]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    ctx = nsml.Context(n, len(sizes), 64)
+    dense = torch.full((n,), 0.125, device=DEV)
+    want = np.full(n, 0.125, dtype=np.float32)
+    for w in range(3):
+        g = _rand(n, 300 + w, sigma=1e-2)
+        r = torch.zeros(n, device=DEV)
+        idx, val, sc = ctx.compress(g, r, off, 0.03, bits)
+        ctx.decompress_accumulate(idx, val, sc, off, 0.03, bits, dense)
+        w_idx, w_val, w_sc = oracle.compress(g.cpu().numpy(), np.zeros(n, np.float32), off, 0.03, bits, 64)
+        oracle.decompress_accumulate(w_idx, w_val, w_sc, want, off, 0.03, bits, 64)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
