@@ -192,3 +192,50 @@ def test_cfg5_adaptive_run_scaled():
         last_bytes *= 16
     say("cfg5 widths used:", sorted(seen), "final ratio", ctl.state.ratio)
     assert len(seen) >= 2
+
+
+def test_maximum_bucket_size_properties():
+    """One bucket of 2^32 - 4096 elements (the largest a 32-bit bucket-local index allows, less
+    one tile): indices above 2^31 must survive every step of the path.  The oracle cannot sort
+    this in reasonable time, so the check is by properties that hold at any size: the k largest
+    magnitudes were planted at known positions, everything else is strictly smaller."""
+    n = (1 << 32) - 4096
+    ratio, bits = 2.0 ** -22, 8          # k = ceil(n * 2^-22) = 1024
+    k = int(nsml.payload_layout([0, n], ratio, bits)[1])
+    assert k == 1024
+    g = torch.empty(n, dtype=torch.float32, device=DEV)
+    step = 1 << 28
+    for lo in range(0, n, step):          # |noise| < 1e-3
+        hi = min(n, lo + step)
+        g[lo:hi].uniform_(-1e-3, 1e-3)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    pos = torch.randperm(n // 4096, generator=gen, device=DEV)[:k].to(torch.int64) * 4096 + 4095
+    pos[0], pos[1] = n - 1, 0              # the very last and the very first element
+    pos = torch.unique(pos)
+    assert pos.numel() == k
+    planted = (torch.arange(k, device=DEV, dtype=torch.float32) * 1e-3 + 1.0) * \
+        torch.where(torch.arange(k, device=DEV) % 2 == 0, 1.0, -1.0)
+    g[pos] = planted
+    r = torch.zeros(n, dtype=torch.float32, device=DEV)
+    ctx = nsml.Context(n, 1, 2048)
+    off = np.array([0, n], dtype=np.uint64)
+    idx, val, sc = ctx.compress(g, r, off, ratio, bits)
+    torch.cuda.synchronize()
+    ctx.path_stats()
+    got = (idx[:k].view(torch.int32).to(torch.int64) & 0xFFFFFFFF)
+    assert torch.equal(got, pos)                                    # ascending, exact, > 2^31 included
+    assert int(got.max()) == n - 1 and int(got.min()) == 0
+    # int8 codes of the planted values: one chunk of 1024, scale = max / 127
+    m = float(planted.abs().max())
+    want_scale = np.float32(m) / np.float32(127.0)
+    assert sc[0].item() == want_scale
+    q = val[:k].view(torch.int8).to(torch.float32)
+    want_q = torch.clamp(torch.round(planted / want_scale), -127, 127)   # ties-to-even, as rintf
+    assert torch.equal(q, want_q)
+    # residual: survivors hold value - code * scale, everything else the accumulator itself
+    assert torch.equal(r[pos], planted - q * want_scale)
+    del idx
+    dense = ctx.decompress(ctx_idx := got.to(torch.int32), val, sc, n, off, ratio, bits)
+    assert torch.equal(dense[pos], q * want_scale)
+    assert int(torch.count_nonzero(dense)) == k
