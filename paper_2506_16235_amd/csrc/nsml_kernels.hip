@@ -577,26 +577,58 @@ __global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
 
 /* ------------------------------------------------------------------ candidate path */
 
+/* The candidate kernels walk the staging segments.  A segment usually holds a few dozen
+ * entries, so a wavefront takes four segments at a time, 16 lanes each: the table look-ups of
+ * four segments are in flight together and the lanes stay busy. */
+/* GROUP = lanes per segment: 16 when segments are short (low ratios), 64 otherwise. */
+struct Seg {
+    uint32_t ss, b, cnt, sub, gl;
+    uint64_t base;
+    bool active;
+};
+
+/* segment handled by this lane's group in round `it` of a grid-stride walk */
+template <uint32_t GROUP>
+__device__ __forceinline__ Seg seg_of(const Tables &t, const Cand &c, uint32_t bid, uint32_t nblk, uint32_t it)
+{
+    Seg g;
+    const uint32_t lane = threadIdx.x & 63;
+    g.sub = lane / GROUP;
+    g.gl = lane % GROUP;
+    const uint32_t wave_g = bid * 4 + (threadIdx.x >> 6);
+    g.ss = (it * nblk * 4 + wave_g) * (64 / GROUP) + g.sub;
+    g.active = g.ss < t.n_spans * 4;
+    g.b = g.active ? t.span_b[g.ss >> 2] : 0u;
+    g.active = g.active && t.fast[g.b];
+    g.cnt = g.active ? c.cnt[g.ss] : 0u;
+    g.base = (uint64_t)g.ss * c.cap;
+    return g;
+}
+
+template <uint32_t GROUP>
+__device__ __forceinline__ uint32_t seg_rounds(const Tables &t, uint32_t nblk)
+{
+    const uint32_t per_round = nblk * 4 * (64 / GROUP);
+    return (t.n_spans * 4 + per_round - 1) / per_round;
+}
+
 /* Next-digit histogram over the candidates that carry the prefix found so far (LEVEL 1:
- * 12-bit prefix, digit = key bits 18..7; LEVEL 2: 24-bit prefix, digit = bits 6..0).  One
- * wavefront per subspan; the matching entries are few, so they go straight to global atomics. */
-template <int LEVEL>
+ * 12-bit prefix, digit = key bits 18..7; LEVEL 2: 24-bit prefix, digit = bits 6..0).  The
+ * matching entries are few, so they go straight to global atomics. */
+template <int LEVEL, uint32_t GROUP>
 __device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uint32_t *__restrict__ hist,
                                              uint32_t bid, uint32_t nblk)
 {
     constexpr int NB = LEVEL == 1 ? NB1 : NB2;
     constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
     constexpr int DSH = LEVEL == 1 ? SH1 : 0;
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t n_ss = t.n_spans * 4;
-    for (uint32_t ss = bid * 4 + (threadIdx.x >> 6); ss < n_ss; ss += nblk * 4) {
-        const uint32_t b = t.span_b[ss >> 2];
-        if (!t.fast[b]) continue;
-        const uint32_t cnt = c.cnt[ss], prefix = t.T[b];
-        const uint64_t base = (uint64_t)ss * c.cap;
-        for (uint32_t i = lane; i < cnt; i += 64) {
-            const uint32_t key = keyof(c.val[base + i]);
-            if ((key >> PSH) == prefix) atomicAdd(&hist[(uint64_t)b * NB + ((key >> DSH) & (NB - 1))], 1u);
+    const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
+    for (uint32_t it = 0; it < rounds; ++it) {
+        const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
+        const uint32_t prefix = g.active ? t.T[g.b] : 0u;
+        for (uint32_t i = g.gl; i < g.cnt; i += GROUP) {
+            const uint32_t key = keyof(c.val[g.base + i]);
+            if ((key >> PSH) == prefix) atomicAdd(&hist[(uint64_t)g.b * NB + ((key >> DSH) & (NB - 1))], 1u);
         }
     }
 }
@@ -628,25 +660,23 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
     }
 }
 
-/* Per subspan: how many candidates exceed the threshold, how many equal it. */
+/* Per segment: how many candidates exceed the threshold, how many equal it. */
+template <uint32_t GROUP>
 __device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint32_t bid, uint32_t nblk)
 {
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t n_ss = t.n_spans * 4;
-    for (uint32_t ss = bid * 4 + (threadIdx.x >> 6); ss < n_ss; ss += nblk * 4) {
-        const uint32_t b = t.span_b[ss >> 2];
-        if (!t.fast[b]) continue;
-        const uint32_t cnt = c.cnt[ss], T = t.T[b];
-        const uint64_t base = (uint64_t)ss * c.cap;
+    const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
+    for (uint32_t it = 0; it < rounds; ++it) {
+        const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
+        const uint32_t T = g.active ? t.T[g.b] : 0u;
         uint32_t ng = 0, ne = 0;
-        for (uint32_t i = lane; i < cnt; i += 64) {
-            const uint32_t key = keyof(c.val[base + i]);
+        for (uint32_t i = g.gl; i < g.cnt; i += GROUP) {
+            const uint32_t key = keyof(c.val[g.base + i]);
             ng += key > T ? 1u : 0u;
             ne += key == T ? 1u : 0u;
         }
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
-        if (lane == 0) { c.G[ss] = ng; c.E[ss] = ne; }
+        for (int d = GROUP / 2; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
+        if (g.active && g.gl == 0) { c.G[g.ss] = ng; c.E[g.ss] = ne; }
     }
 }
 
@@ -677,34 +707,40 @@ __global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG
     }
 }
 
-/* Per subspan: copy the admitted candidates (key > T, or key == T and among the first e_b
+/* Per segment: copy the admitted candidates (key > T, or key == T and among the first e_b
  * equal ones of the bucket in index order) to their final slots. */
+template <uint32_t GROUP>
 __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint32_t *__restrict__ idx_out,
                                             float *__restrict__ v_out, uint32_t bid, uint32_t nblk)
 {
-    const uint32_t lane = threadIdx.x & 63;
-    const uint64_t lt = (1ull << lane) - 1ull;
-    const uint32_t n_ss = t.n_spans * 4;
-    for (uint32_t ss = bid * 4 + (threadIdx.x >> 6); ss < n_ss; ss += nblk * 4) {
-        const uint32_t b = t.span_b[ss >> 2];
-        if (!t.fast[b]) continue;
-        const uint32_t cnt = c.cnt[ss], T = t.T[b], e_b = t.need[b];
-        const uint64_t base = (uint64_t)ss * c.cap, Pb = t.P[b];
-        uint32_t run_g = c.G[ss], run_e = c.E[ss];
-        for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {
-            const uint32_t i = i0 + lane;
+    const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
+    for (uint32_t it = 0; it < rounds; ++it) {
+        const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
+        const uint32_t T = g.active ? t.T[g.b] : 0u, e_b = g.active ? t.need[g.b] : 0u;
+        const uint64_t Pb = g.active ? t.P[g.b] : 0ull;
+        uint32_t run_g = g.active ? c.G[g.ss] : 0u, run_e = g.active ? c.E[g.ss] : 0u;
+        const uint32_t shift = g.sub * GROUP;
+        const uint64_t below = (1ull << g.gl) - 1ull;
+        const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << GROUP) - 1ull);
+        /* the four groups of the wavefront advance together: ballots need every lane */
+        uint32_t maxcnt = g.cnt;
+#pragma unroll
+        for (int d = 32; d >= (int)GROUP; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
+        for (uint32_t i0 = 0; i0 < maxcnt; i0 += GROUP) {
+            const uint32_t i = i0 + g.gl;
             float x = 0.0f;
             uint32_t li = 0;
             bool isg = false, ise = false;
-            if (i < cnt) {
-                x = c.val[base + i];
-                li = c.idx[base + i];
+            if (i < g.cnt) {
+                x = c.val[g.base + i];
+                li = c.idx[g.base + i];
                 const uint32_t key = keyof(x);
                 isg = key > T;
                 ise = key == T;
             }
-            const uint64_t bg = __ballot(isg), be = __ballot(ise);
-            const uint32_t pg = run_g + __popcll(bg & lt), pe = run_e + __popcll(be & lt);
+            const uint64_t bg = (__ballot(isg) >> shift) & gmask;
+            const uint64_t be = (__ballot(ise) >> shift) & gmask;
+            const uint32_t pg = run_g + __popcll(bg & below), pe = run_e + __popcll(be & below);
             if (isg || (ise && pe < e_b)) {
                 const uint64_t pos = Pb + pg + min(e_b, pe);
                 idx_out[pos] = li;
@@ -890,32 +926,34 @@ __device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const
 /* Each selection stage is one launch: the first cgrid workgroups walk the candidate segments,
  * the others walk the dense spans of the fallback buckets (usually none: they read the empty
  * list and leave). */
-template <int LEVEL>
+template <int LEVEL, uint32_t GROUP>
 __global__ __launch_bounds__(WG) void k_refine(const float *__restrict__ r, Tables t, Cand c,
                                                uint32_t *__restrict__ hist_c, uint32_t *__restrict__ hist_f,
                                                uint32_t cgrid)
 {
     __shared__ uint32_t h[LEVEL == 1 ? NB1 : NB2];
-    if (blockIdx.x < cgrid) crefine_body<LEVEL>(t, c, hist_c, blockIdx.x, cgrid);
+    if (blockIdx.x < cgrid) crefine_body<LEVEL, GROUP>(t, c, hist_c, blockIdx.x, cgrid);
     else fb_refine_body<LEVEL>(r, t, hist_f, h, blockIdx.x - cgrid, gridDim.x - cgrid);
 }
 
+template <uint32_t GROUP>
 __global__ __launch_bounds__(WG) void k_count(const float *__restrict__ r, Tables t, Cand c,
                                               uint32_t *__restrict__ tG, uint32_t *__restrict__ tE,
                                               uint32_t cgrid)
 {
     __shared__ uint32_t cnt[MAX_SPAN_TILES][2];
-    if (blockIdx.x < cgrid) ccount_body(t, c, blockIdx.x, cgrid);
+    if (blockIdx.x < cgrid) ccount_body<GROUP>(t, c, blockIdx.x, cgrid);
     else fb_count_body(r, t, tG, tE, cnt, blockIdx.x - cgrid, gridDim.x - cgrid);
 }
 
+template <uint32_t GROUP>
 __global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Tables t, Cand c,
                                               const uint32_t *__restrict__ tG, const uint32_t *__restrict__ tE,
                                               uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
                                               uint32_t cgrid)
 {
     __shared__ uint32_t tot[16][2];      /* slot = u * 4 + wavefront */
-    if (blockIdx.x < cgrid) cwrite_body(t, c, idx_out, v_out, blockIdx.x, cgrid);
+    if (blockIdx.x < cgrid) cwrite_body<GROUP>(t, c, idx_out, v_out, blockIdx.x, cgrid);
     else fb_write_body(r, t, tG, tE, idx_out, v_out, tot, blockIdx.x - cgrid, gridDim.x - cgrid);
 }
 
@@ -1522,14 +1560,34 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
      * spans of the buckets the candidates could not decide */
     const uint32_t cg = c->force_dense ? 0u : cgrid;
     const float *acc = residual;
-    LAUNCH(c, KID_REFINE1, st, k_refine<1>, cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
+    /* lanes per candidate segment: a segment is expected to hold about 1.5 * ratio of the
+     * elements it covers */
+    const bool narrow = 1.5 * ratio * (double)(c->spanT * WTILE) < 48.0;
+    if (narrow) {
+        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 16>), cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
+    } else {
+        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
+    }
     LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err);
-    LAUNCH(c, KID_REFINE2, st, k_refine<2>, cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
+    if (narrow) {
+        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 16>), cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
+    } else {
+        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
+    }
     LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err);
-    LAUNCH(c, KID_COUNT, st, k_count, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
+    if (narrow) {
+        LAUNCH(c, KID_COUNT, st, k_count<16>, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
+    } else {
+        LAUNCH(c, KID_COUNT, st, k_count<64>, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
+    }
     LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE);
-    LAUNCH(c, KID_WRITE, st, k_write, cg + fgrid, acc, t, cd, (const uint32_t *)c->d_tG,
-           (const uint32_t *)c->d_tE, idx, vdst, cg);
+    if (narrow) {
+        LAUNCH(c, KID_WRITE, st, k_write<16>, cg + fgrid, acc, t, cd, (const uint32_t *)c->d_tG,
+               (const uint32_t *)c->d_tE, idx, vdst, cg);
+    } else {
+        LAUNCH(c, KID_WRITE, st, k_write<64>, cg + fgrid, acc, t, cd, (const uint32_t *)c->d_tG,
+               (const uint32_t *)c->d_tE, idx, vdst, cg);
+    }
     const uint32_t qgrid = (uint32_t)c->NC;
     switch (bits) {
     case 32: LAUNCH(c, KID_QUANT, st, k_quant<32>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
