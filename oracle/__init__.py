@@ -61,6 +61,12 @@ def lib() -> C.CDLL:
             L.orc_compress.argtypes = [vp, vp, u64, vp, u32, dbl, i32, u32, vp, vp, vp, i32]
             L.orc_decompress.restype = i32
             L.orc_decompress.argtypes = [vp, vp, vp, u64, vp, u32, dbl, i32, u32, vp, i32]
+            L.orc_pruned_count.restype = u64
+            L.orc_pruned_count.argtypes = [dbl, u64]
+            L.orc_keep_mask.restype = i32
+            L.orc_keep_mask.argtypes = [vp, u64, dbl, vp]
+            L.orc_compress_pruned.restype = i32
+            L.orc_compress_pruned.argtypes = [vp, vp, vp, u64, vp, u32, dbl, i32, u32, vp, vp, vp, i32]
             L.orc_decompress_accumulate.restype = i32
             L.orc_decompress_accumulate.argtypes = [vp, vp, vp, u64, vp, u32, dbl, i32, u32, vp]
             L.orc_l2norm.restype = dbl
@@ -128,6 +134,42 @@ def decompress(idx, val, scales, n: int, bucket_off, ratio: float, bits: int, ch
     if rc != 0:
         raise ValueError("orc_decompress rc=%d" % rc)
     return dense
+
+
+def pruned_count(ratio: float, n: int) -> int:
+    return int(lib().orc_pruned_count(float(ratio), int(n)))
+
+
+def keep_mask(weights, ratio: float):
+    """One bucket: boolean array, True for the parameters the pruning step keeps."""
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    m = np.zeros(w.size, dtype=np.uint8)
+    rc = lib().orc_keep_mask(_p(w), w.size, float(ratio), _p(m))
+    if rc != 0:
+        raise ValueError("orc_keep_mask rc=%d" % rc)
+    return m.astype(bool)
+
+
+def compress_pruned(grad, residual, weights, bucket_off, ratio: float, bits: int,
+                    chunk: int = 2048, nthreads: int = 1):
+    """As compress, with Algorithm 2 Step 2: only parameters kept by weight-magnitude pruning
+    can be selected.  ``residual`` is updated in place."""
+    g = np.ascontiguousarray(grad, dtype=np.float32)
+    w = np.ascontiguousarray(weights, dtype=np.float32)
+    if not (isinstance(residual, np.ndarray) and residual.dtype == np.float32
+            and residual.flags.c_contiguous and residual.shape == g.shape and w.shape == g.shape):
+        raise ValueError("residual / weights must be contiguous float32 arrays shaped like grad")
+    off = np.ascontiguousarray(bucket_off, dtype=np.uint64)
+    B = len(off) - 1
+    _, K, vb, ns = layout(off, ratio, bits, chunk)
+    idx = np.zeros(K, dtype=np.uint32)
+    val = np.zeros(vb, dtype=np.uint8)
+    scales = np.zeros(ns, dtype=np.float32)
+    rc = lib().orc_compress_pruned(_p(g), _p(residual), _p(w), g.size, _p(off), B, float(ratio),
+                                   int(bits), int(chunk), _p(idx), _p(val), _p(scales), int(nthreads))
+    if rc != 0:
+        raise ValueError("orc_compress_pruned rc=%d" % rc)
+    return idx, val, scales
 
 
 def decompress_accumulate(idx, val, scales, dense, bucket_off, ratio: float, bits: int,

@@ -242,6 +242,110 @@ int64_t orc_compress_bucket(const float *g, float *r, uint64_t n, double ratio, 
     return (int64_t)k;
 }
 
+/* ------------------------------------------------- with model pruning */
+
+/* Algorithm 2 Step 2: pruning_rate = 0.5 * (1 - ratio); the parameters with the smallest
+ * |weight| are pruned and their gradients take no part in the sparsification that follows.
+ * Reading taken here: floor(rate * n) parameters of the bucket are pruned; the kept set is the
+ * n - floor(rate * n) largest |weight| with the same tie rule as the gradient selection (equal
+ * magnitudes: lower index kept first); pruned parameters are not removed for good -- their
+ * accumulated gradient stays in the residual and they may come back in a later step. */
+uint64_t orc_pruned_count(double ratio, uint64_t n)
+{
+    double np = floor(0.5 * (1.0 - ratio) * (double)n);
+    if (np < 0.0) np = 0.0;
+    return (uint64_t)np;
+}
+
+/* eligible[i] = 1 for the kept parameters of one bucket */
+int orc_keep_mask(const float *w, uint64_t n, double ratio, uint8_t *eligible)
+{
+    if (n == 0) return ORC_OK;
+    if (!w || !eligible || n > 0xFFFFFFFFull) return ORC_EINVAL;
+    uint64_t m = n - orc_pruned_count(ratio, n);
+    keyed *order = (keyed *)malloc(n * sizeof(keyed));
+    if (!order) return ORC_ENOMEM;
+    for (uint64_t i = 0; i < n; ++i) { order[i].key = mag_key(w[i]); order[i].idx = (uint32_t)i; }
+    qsort(order, n, sizeof(keyed), by_key_desc_then_idx_asc);
+    memset(eligible, 0, n);
+    for (uint64_t j = 0; j < m; ++j) eligible[order[j].idx] = 1;
+    free(order);
+    return ORC_OK;
+}
+
+/* As orc_compress_bucket, but only the parameters kept by the pruning step can be selected. */
+int64_t orc_compress_bucket_pruned(const float *g, float *r, const float *w, uint64_t n,
+                                   double ratio, int bits, uint32_t chunk, uint32_t *idx,
+                                   void *val, float *scales)
+{
+    if (n == 0) return 0;
+    if (!g || !r || !w || !idx || !val || n > 0xFFFFFFFFull || chunk == 0) return ORC_EINVAL;
+    if (!(ratio > 0.0 && ratio <= 1.0)) return ORC_EINVAL;
+    uint8_t *eligible = (uint8_t *)malloc(n);
+    if (!eligible) return ORC_ENOMEM;
+    int rc = orc_keep_mask(w, n, ratio, eligible);
+    if (rc != ORC_OK) { free(eligible); return rc; }
+
+    /* accumulate, then select among the kept parameters only */
+    for (uint64_t i = 0; i < n; ++i) { volatile float acc = g[i] + r[i]; r[i] = acc; }
+    uint64_t k = orc_k(ratio, n), m = 0;
+    keyed *order = (keyed *)malloc(n * sizeof(keyed));
+    if (!order) { free(eligible); return ORC_ENOMEM; }
+    for (uint64_t i = 0; i < n; ++i)
+        if (eligible[i]) { order[m].key = mag_key(r[i]); order[m].idx = (uint32_t)i; ++m; }
+    free(eligible);
+    if (m < k) { free(order); return ORC_EINVAL; }      /* cannot happen: kept >= (1 + ratio) n / 2 >= k */
+    qsort(order, m, sizeof(keyed), by_key_desc_then_idx_asc);
+    for (uint64_t j = 0; j < k; ++j) idx[j] = order[j].idx;
+    free(order);
+    qsort(idx, k, sizeof(uint32_t), by_u32_asc);
+
+    /* from here on nothing differs from the unpruned path: code the gathered values and leave
+     * the coding error in the residual.  Done by handing the survivors to the plain routine on
+     * a compact copy: a bucket that consists of exactly the survivors, at ratio 1. */
+    float *gv = (float *)malloc(k * sizeof(float)), *rv = (float *)calloc(k, sizeof(float));
+    uint32_t *tmp_idx = (uint32_t *)malloc(k * sizeof(uint32_t));
+    if (!gv || !rv || !tmp_idx) { free(gv); free(rv); free(tmp_idx); return ORC_ENOMEM; }
+    for (uint64_t j = 0; j < k; ++j) gv[j] = r[idx[j]];
+    int64_t kk = orc_compress_bucket(gv, rv, k, 1.0, bits, chunk, tmp_idx, val, scales);
+    if (kk == (int64_t)k)
+        for (uint64_t j = 0; j < k; ++j) r[idx[j]] = rv[j];
+    free(gv); free(rv); free(tmp_idx);
+    return kk == (int64_t)k ? (int64_t)k : ORC_EINVAL;
+}
+
+int orc_compress_pruned(const float *g, float *r, const float *w, uint64_t n, const uint64_t *off,
+                        uint32_t B, double ratio, int bits, uint32_t chunk, uint32_t *idx,
+                        void *val, float *scales, int nthreads)
+{
+    if (!off || B == 0 || off[0] != 0 || off[B] != n) return ORC_EINVAL;
+    uint64_t *P = (uint64_t *)malloc(3 * (size_t)(B + 1) * sizeof(uint64_t));
+    if (!P) return ORC_ENOMEM;
+    uint64_t *V = P + (B + 1), *S = V + (B + 1);
+    P[0] = V[0] = S[0] = 0;
+    for (uint32_t b = 0; b < B; ++b) {
+        if (off[b + 1] < off[b]) { free(P); return ORC_EINVAL; }
+        uint64_t k = orc_k(ratio, off[b + 1] - off[b]);
+        P[b + 1] = P[b] + k;
+        V[b + 1] = V[b] + val_bytes_of(k, bits);
+        S[b + 1] = S[b] + ((bits == 8 || bits == 4) ? (k + chunk - 1) / chunk : 0);
+    }
+    int err = ORC_OK;
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int64_t b = 0; b < (int64_t)B; ++b) {
+        int64_t rc = orc_compress_bucket_pruned(g + off[b], r + off[b], w + off[b], off[b + 1] - off[b],
+                                                ratio, bits, chunk, idx + P[b], (uint8_t *)val + V[b],
+                                                scales ? scales + S[b] : NULL);
+        if (rc < 0) {
+#pragma omp critical
+            err = (int)rc;
+        }
+    }
+    free(P);
+    return err;
+}
+
 /* Inverse: dense[i] = +0 everywhere, dense[idx[j]] = decoded value j. */
 int orc_decompress_bucket(const uint32_t *idx, const void *val, const float *scales, uint64_t k,
                           uint64_t n, int bits, uint32_t chunk, float *dense)
