@@ -135,8 +135,8 @@ typedef struct nsml_ctx nsml_ctx;
 
 /* Allocate a context and its device workspace on GPU `device` for gradients of up to max_n
  * elements in up to max_buckets buckets, quantized in chunks of `chunk` survivors (2048 in
- * the benchmark configurations; a positive multiple of 8).  Workspace: about 6 bytes per
- * element of max_n (survivor values, candidate staging) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
+ * the benchmark configurations; a positive multiple of 8).  Workspace: about 6.2 bytes per
+ * element of max_n (survivor values, candidate staging, pruning bitmap) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
  * available (there is no CPU fallback). */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 int nsml_destroy(nsml_ctx *ctx);
@@ -164,6 +164,19 @@ uint64_t nsml_workspace_bytes(const nsml_ctx *ctx);
 int nsml_compress(nsml_ctx *ctx, const float *grad, float *residual, uint64_t n,
                   const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
                   uint32_t *idx, void *val, float *scales, void *stream);
+
+/* As nsml_compress, preceded by the model-pruning step of Algorithm 2 Step 2.
+ *   weights   dev, const, float[n]: the parameters the gradient belongs to, same bucketing.
+ * Per bucket, floor(0.5 * (1 - ratio) * n_b) parameters with the smallest |weight| are pruned
+ * for this step (equal magnitudes: the higher index is pruned first, so the kept set is the
+ * top n_b - floor(...) by |weight| under the tie rule of the gradient selection); the k_b
+ * survivors are chosen among the kept parameters only.  Pruning is not permanent: a pruned
+ * parameter's accumulated gradient is written to the residual like any other unsent element
+ * and competes again in later steps.  Outputs, payload layout and errors as nsml_compress.
+ * Costs about five extra reads of `weights` per call. */
+int nsml_compress_pruned(nsml_ctx *ctx, const float *grad, float *residual, const float *weights,
+                         uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio,
+                         int bits, uint32_t *idx, void *val, float *scales, void *stream);
 
 /* Decompress a payload produced with the same (bucket_off, B, ratio, bits, chunk):
  *   dense_out  dev, out, float[n], fully overwritten: +0 everywhere except

@@ -59,6 +59,8 @@ _lib.nsml_last_hip_error.argtypes = [_vp]
 _lib.nsml_workspace_bytes.argtypes = [_vp]
 _lib.nsml_workspace_bytes.restype = _u64
 _lib.nsml_compress.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp, _vp, _vp]
+_lib.nsml_compress_pruned.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp, _vp, _vp]
+_lib.nsml_compress_pruned.restype = _i32
 _lib.nsml_decompress.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp]
 _lib.nsml_profile_enable.argtypes = [_vp, _i32]
 _lib.nsml_profile_read.argtypes = [_vp, _vp, _vp]
@@ -205,6 +207,22 @@ class Context:
         _check(rc, "nsml_compress", self._h)
         return idx, val, scales
 
+    def compress_pruned(self, grad: torch.Tensor, residual: torch.Tensor, weights: torch.Tensor,
+                        bucket_off, ratio: float, bits: int, idx: torch.Tensor = None,
+                        val: torch.Tensor = None, scales: torch.Tensor = None):
+        """nsml_compress_pruned: as compress, after weight-magnitude pruning of the candidates."""
+        off = _off(bucket_off)
+        if idx is None:
+            idx, val, scales = self.alloc_payload(off, ratio, bits)
+        assert grad.dtype == residual.dtype == weights.dtype == torch.float32
+        assert grad.is_contiguous() and residual.is_contiguous() and weights.is_contiguous()
+        assert weights.numel() == grad.numel()
+        rc = _lib.nsml_compress_pruned(self._h, _ptr(grad), _ptr(residual), _ptr(weights), grad.numel(),
+                                       off.ctypes.data, len(off) - 1, float(ratio), int(bits),
+                                       _ptr(idx), _ptr(val), _ptr(scales), _stream(self.device))
+        _check(rc, "nsml_compress_pruned", self._h)
+        return idx, val, scales
+
     def decompress(self, idx: torch.Tensor, val: torch.Tensor, scales: torch.Tensor, n: int,
                    bucket_off, ratio: float, bits: int, out: torch.Tensor = None) -> torch.Tensor:
         off = _off(bucket_off)
@@ -271,6 +289,11 @@ def calibration_copy(src: torch.Tensor, dst: torch.Tensor):
 
 def compress(ctx: Context, grad, residual, bucket_off, ratio, bits, idx=None, val=None, scales=None):
     return ctx.compress(grad, residual, bucket_off, ratio, bits, idx, val, scales)
+
+
+def compress_pruned(ctx: Context, grad, residual, weights, bucket_off, ratio, bits,
+                    idx=None, val=None, scales=None):
+    return ctx.compress_pruned(grad, residual, weights, bucket_off, ratio, bits, idx, val, scales)
 
 
 def decompress(ctx: Context, idx, val, scales, n, bucket_off, ratio, bits, out=None):

@@ -63,12 +63,12 @@ constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that
 enum KernelId {
     KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
     KID_REFINE1, KID_PICK1, KID_REFINE2, KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE,
-    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_N
+    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_WHIST, KID_WPLAN, KID_WMASK, KID_N
 };
 const char *const kKernelNames[KID_N] = {
     "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan", "fb_plan",
     "refine1", "pick1", "refine2", "pick2", "count", "scan", "write",
-    "quant", "tilestart", "decomp", "decomp_acc"
+    "quant", "tilestart", "decomp", "decomp_acc", "whist", "wplan", "wmask"
 };
 static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
 
@@ -91,6 +91,8 @@ struct Tables {
     uint32_t *fast;          /* B   1: the candidates decide the bucket, 0: the dense fallback does */
     uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
+    uint32_t *kw;            /* B   parameters the pruning step keeps (only with weights) */
+    const uint32_t *pmask;   /* pruning bitmap, 128 words per tile, bit = pruned; NULL: no pruning */
     uint32_t B;
     uint32_t n_spans;
     uint32_t spanT;          /* tiles per span */
@@ -153,6 +155,12 @@ __device__ __forceinline__ SpanGeo span_geo(const Tables &t, uint32_t s)
     return span_geo_b(t, b, s - t.span0[b]);
 }
 
+/* The four pruning bits of quad `quad` (0..1023) of tile `tile_abs`. */
+__device__ __forceinline__ uint32_t pruned_bits(const uint32_t *__restrict__ pm, uint32_t tile_abs, uint32_t quad)
+{
+    return (pm[(uint64_t)tile_abs * (TILE / 32) + (quad >> 3)] >> ((quad & 7u) * 4u)) & 0xFu;
+}
+
 /* Load the quad at aligned element index gi, masking what lies outside [lo, hi).
  * Returns the 4-bit validity mask. */
 __device__ __forceinline__ uint32_t load_quad(const float *__restrict__ p, uint64_t gi,
@@ -211,6 +219,11 @@ __global__ __launch_bounds__(WG) void k_setup(Tables t, double ratio, int bits)
         const uint64_t k = survivors_dev(ratio, t.off[b + 1] - t.off[b]);
         const uint64_t ch = (k + t.chunk - 1) / t.chunk;
         t.k[b] = (uint32_t)k;
+        {   /* Algorithm 2 Step 2: floor(0.5 * (1 - ratio) * n_b) parameters are pruned */
+            const uint64_t nb = t.off[b + 1] - t.off[b];
+            const double np = floor(0.5 * (1.0 - ratio) * (double)nb);
+            t.kw[b] = (uint32_t)(nb - (uint64_t)(np < 0.0 ? 0.0 : np));
+        }
         t.P[b] = pk; t.V[b] = pv; t.S[b] = ps; t.C[b] = pc;
         pk += k;
         pv += bits == 32 ? 4 * k : bits == 16 ? 2 * k : bits == 8 ? k : (k + 1) / 2;
@@ -356,8 +369,12 @@ __global__ __launch_bounds__(WG) void k_sample(const float *__restrict__ g, cons
         if (run < n_runs) {
             const uint64_t gi = a0 + run * run_elems + (tid & 7u) * 4;
             float x[4], y[4];
-            const uint32_t m = load_quad(g, gi, lo, hi, x);
+            uint32_t m = load_quad(g, gi, lo, hi, x);
             load_quad(r, gi, lo, hi, y);
+            if (t.pmask) {
+                const uint64_t rel = gi - a0;
+                m &= ~pruned_bits(t.pmask, t.tile0[b] + (uint32_t)(rel / TILE), (uint32_t)(rel % TILE) / 4);
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 if ((m >> j) & 1u) atomicAdd(&h[keyof(__fadd_rn(x[j], y[j])) >> SH0], 1u);
@@ -386,7 +403,10 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
     w.load(hist_s + (uint64_t)b * NB0, tmp);
     const uint32_t m = w.total;
     const bool exact = nb < SAMPLE_ALL_BELOW;
-    const double ks = (double)k * (double)m / (double)nb;
+    /* the sample was drawn from the parameters that can be selected: all of them, or the
+     * ones the pruning step kept */
+    const double pop = t.pmask ? (double)t.kw[b] : (double)nb;
+    const double ks = (double)k * (double)m / pop;
     const double want_d = exact ? (double)k : ceil(ks + 4.0 * sqrt(ks) + 4.0);
     const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
     if (m == 0 || want_d > (double)m || (double)k > 0.5 * cap_b) {
@@ -396,7 +416,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
     }
     uint32_t digit, above, at;
     if (w.find((uint32_t)want_d, digit, above, at)) {
-        const double est = (double)(above + at) * (double)nb / (double)m;
+        const double est = (double)(above + at) * pop / (double)m;
         const bool fits = est <= 0.8 * cap_b;
         t.L[b] = fits ? (digit << SH0) : NONE;
         t.fast[b] = fits ? 1u : 0u;
@@ -408,9 +428,9 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
 /* One row of the streaming pass: 64 lanes x 4 consecutive elements (one contiguous 1 KiB).
  * a[] is the accumulator quad of this lane, m its validity mask, li the bucket-local index
  * of a[0].  Stores the accumulator, counts its level-0 digits and appends candidates. */
-template <bool INTERIOR, bool EMIT, int NT>
+template <bool INTERIOR, bool EMIT, int NT, bool PRUNE>
 __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const float (&a)[4],
-                                       uint32_t m, uint32_t li, uint32_t *h, uint32_t L,
+                                       uint32_t m, uint32_t cm, uint32_t li, uint32_t *h, uint32_t L,
                                        const Cand &c, uint64_t cbase, uint32_t &wcount, uint64_t lt)
 {
     uint32_t key[4];
@@ -420,16 +440,24 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
         f4 v; v.x = a[0]; v.y = a[1]; v.z = a[2]; v.w = a[3];
         if (NT & 4) __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(r + gi));
         else *reinterpret_cast<f4 *>(r + gi) = v;
-        hist_quad_full(h, key[0] >> SH0, key[1] >> SH0, key[2] >> SH0, key[3] >> SH0);
+        if (!PRUNE || __all(cm == 0xFu)) {
+            hist_quad_full(h, key[0] >> SH0, key[1] >> SH0, key[2] >> SH0, key[3] >> SH0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((cm >> j) & 1u) atomicAdd(&h[key[j] >> SH0], 1u);
+        }
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if ((m >> j) & 1u) { r[gi + j] = a[j]; atomicAdd(&h[key[j] >> SH0], 1u); }
+        for (int j = 0; j < 4; ++j) {
+            if ((m >> j) & 1u) r[gi + j] = a[j];               /* the accumulator is always stored */
+            if ((cm >> j) & 1u) atomicAdd(&h[key[j] >> SH0], 1u);
+        }
     }
     if (EMIT) {
         bool f[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) f[j] = ((m >> j) & 1u) && key[j] >= L;
+        for (int j = 0; j < 4; ++j) f[j] = ((cm >> j) & 1u) && key[j] >= L;
         if (__ballot(f[0] | f[1] | f[2] | f[3]) != 0ull) {
             uint64_t bal[4];
             uint32_t pos = wcount;
@@ -452,7 +480,7 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
  * filters out is accumulated locally; the add is that), the exact level-0 histogram, and the
  * candidates.  Each wavefront owns a contiguous quarter of the span and its own staging
  * segment, so candidates come out in index order without any cross-wavefront exchange. */
-template <bool EMIT, int NT>
+template <bool EMIT, int NT, bool PRUNE>
 __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
                                                 Tables t, uint32_t *__restrict__ hist0, Cand c,
                                                 double *__restrict__ span_sq)
@@ -492,7 +520,9 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
                 a[2] = __fadd_rn(gv[u].z, rv[u].z); a[3] = __fadd_rn(gv[u].w, rv[u].w);
                 sq += (double)(__fmaf_rn(gv[u].x, gv[u].x, __fmul_rn(gv[u].y, gv[u].y)) +
                                __fmaf_rn(gv[u].z, gv[u].z, __fmul_rn(gv[u].w, gv[u].w)));
-                ef_row<true, EMIT, NT>(r, gi, a, 0xFu, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+                uint32_t cm = 0xFu;
+                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
+                ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         } else {
 #pragma unroll
@@ -503,7 +533,9 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
                 load_quad(r, gi, s.lo, s.hi, y);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) { a[j] = __fadd_rn(x[j], y[j]); sq += (double)__fmul_rn(x[j], x[j]); }
-                ef_row<false, EMIT, NT>(r, gi, a, m, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+                uint32_t cm = m;
+                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
+                ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         }
     }
@@ -721,7 +753,7 @@ __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint
         uint32_t run_g = g.active ? c.G[g.ss] : 0u, run_e = g.active ? c.E[g.ss] : 0u;
         const uint32_t shift = g.sub * GROUP;
         const uint64_t below = (1ull << g.gl) - 1ull;
-        const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << GROUP) - 1ull);
+        const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << (GROUP % 64)) - 1ull);
         /* the four groups of the wavefront advance together: ballots need every lane */
         uint32_t maxcnt = g.cnt;
 #pragma unroll
@@ -779,7 +811,8 @@ __device__ __forceinline__ void fb_refine_body(const float *__restrict__ r, cons
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
                 float x[4];
-                const uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
+                uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
+                if (t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
                 uint32_t d[4];
                 uint32_t hit = 0;
 #pragma unroll
@@ -828,7 +861,8 @@ __device__ __forceinline__ void fb_count_body(const float *__restrict__ r, const
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
                 float x[4];
-                const uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
+                uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
+                if (t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t key = keyof(x[j]);
@@ -852,11 +886,13 @@ __device__ __forceinline__ void fb_count_body(const float *__restrict__ r, const
 
 /* Per tile of a fallback bucket: write the survivors to their final slots, in ascending
  * index order.  Inside a tile, thread t owns the quads (u*256 + t)*4, u = 0..3. */
+template <bool MASKOUT>
 __device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const Tables &t,
                                               const uint32_t *__restrict__ tG,
                                               const uint32_t *__restrict__ tE,
                                               uint32_t *__restrict__ idx_out,
                                               float *__restrict__ v_out, uint32_t (*tot)[2],
+                                              uint32_t *bitmap, uint32_t *__restrict__ mask_out,
                                               uint32_t bid, uint32_t nblk)
 {
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -871,12 +907,17 @@ __device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const
             const uint64_t tb = s.base + (uint64_t)ti * TILE;
             const uint32_t gpre = tG[s.tile_g + ti], epre = tE[s.tile_g + ti];
             float x[4][4];
-            uint32_t fg[4], fe[4], gb[4], eb[4];
+            uint32_t fg[4], fe[4], gb[4], eb[4], vm[4] = {0, 0, 0, 0};
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-                const uint32_t m = load_quad(r, gi, s.lo, s.hi, x[u]);
+                uint32_t m = load_quad(r, gi, s.lo, s.hi, x[u]);
+                if (!MASKOUT && t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
                 fg[u] = fe[u] = 0;
+                if (MASKOUT) {
+                    vm[u] = m;
+                    if (u == 0 && tid < TILE / 32) bitmap[tid] = 0u;
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t key = keyof(x[u][j]);
@@ -904,19 +945,31 @@ __device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const
                 uint32_t pg = gpre + run_g + gb[u];
                 uint32_t pe = epre + run_e + eb[u];
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+                uint32_t kept = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const bool isg = (fg[u] >> j) & 1u, ise = (fe[u] >> j) & 1u;
                     if (isg || (ise && pe < e_b)) {
-                        const uint64_t pos = Pb + pg + min(e_b, pe);
-                        idx_out[pos] = (uint32_t)(gi + j - s.lo);
-                        v_out[pos] = x[u][j];
+                        if (MASKOUT) {
+                            kept |= 1u << j;
+                        } else {
+                            const uint64_t pos = Pb + pg + min(e_b, pe);
+                            idx_out[pos] = (uint32_t)(gi + j - s.lo);
+                            v_out[pos] = x[u][j];
+                        }
                     }
                     pg += isg ? 1u : 0u;
                     pe += ise ? 1u : 0u;
                 }
+                if (MASKOUT) {
+                    /* pruned = inside the bucket and not kept; 8 quads share a bitmap word */
+                    const uint32_t q = u * WG + tid;
+                    const uint32_t bits = vm[u] & ~kept;
+                    if (bits) atomicOr(&bitmap[q >> 3], bits << ((q & 7u) * 4u));
+                }
             }
             __syncthreads();
+            if (MASKOUT && tid < TILE / 32) mask_out[(uint64_t)(s.tile_g + ti) * (TILE / 32) + tid] = bitmap[tid];
         }
     }
 }
@@ -954,7 +1007,68 @@ __global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Table
 {
     __shared__ uint32_t tot[16][2];      /* slot = u * 4 + wavefront */
     if (blockIdx.x < cgrid) cwrite_body<GROUP>(t, c, idx_out, v_out, blockIdx.x, cgrid);
-    else fb_write_body(r, t, tG, tE, idx_out, v_out, tot, blockIdx.x - cgrid, gridDim.x - cgrid);
+    else fb_write_body<false>(r, t, tG, tE, idx_out, v_out, tot, nullptr, nullptr, blockIdx.x - cgrid,
+                              gridDim.x - cgrid);
+}
+
+/* ------------------------------------------------------------------ model pruning (optional) */
+
+/* Algorithm 2 Step 2 on the GPU: the kept parameters of a bucket are its n_b - floor(0.5 (1 -
+ * ratio) n_b) largest |weight| (ties: lower index kept), found with the same dense radix
+ * select as a fallback bucket; the result is a bitmap (1 = pruned) that the gradient kernels
+ * consult so that pruned parameters are neither counted nor emitted.  Their accumulated
+ * gradient is still written to the residual: pruning is not permanent. */
+__global__ __launch_bounds__(WG) void k_whist(const float *__restrict__ w, Tables t, uint32_t *__restrict__ hist0)
+{
+    __shared__ uint32_t h[NB0];
+    const uint32_t tid = threadIdx.x;
+    for (int i = tid; i < NB0; i += WG) h[i] = 0;
+    const SpanGeo s = span_geo(t, blockIdx.x);
+    __syncthreads();
+    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
+        const uint64_t tb = s.base + (uint64_t)ti * TILE;
+        const bool interior = tb >= s.lo && tb + TILE <= s.hi;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+            float x[4];
+            const uint32_t m = load_quad(w, gi, s.lo, s.hi, x);
+            if (interior) {
+                hist_quad_full(h, keyof(x[0]) >> SH0, keyof(x[1]) >> SH0, keyof(x[2]) >> SH0, keyof(x[3]) >> SH0);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if ((m >> j) & 1u) atomicAdd(&h[keyof(x[j]) >> SH0], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
+}
+
+/* Per bucket: level-0 digit of the kw-th largest |weight|. */
+__global__ __launch_bounds__(WG) void k_wplan(Tables t, const uint32_t *__restrict__ hist0)
+{
+    __shared__ uint32_t tmp[WG];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t want = t.k[b];
+    if (want == 0) {
+        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; }
+        return;
+    }
+    DigitWalk<NB0> w;
+    w.load(hist0 + (uint64_t)b * NB0, tmp);
+    uint32_t digit, above, at;
+    if (w.find(want, digit, above, at)) { t.T[b] = digit; t.need[b] = want - above; }
+}
+
+__global__ __launch_bounds__(WG) void k_wmask(const float *__restrict__ w, Tables t,
+                                              const uint32_t *__restrict__ tG, const uint32_t *__restrict__ tE,
+                                              uint32_t *__restrict__ mask_out)
+{
+    __shared__ uint32_t tot[16][2];
+    __shared__ uint32_t bitmap[TILE / 32];
+    fb_write_body<true>(w, t, tG, tE, nullptr, nullptr, tot, bitmap, mask_out, blockIdx.x, gridDim.x);
 }
 
 /* ------------------------------------------------------------------ value coding */
@@ -1200,6 +1314,8 @@ struct nsml_ctx {
     float *d_cval;
     float *d_v;            /* survivor values in final order (not used for bits == 32) */
     uint32_t *d_ts;        /* decompress: where each tile's survivors start */
+    uint32_t *d_pmask;     /* pruning bitmap, 128 words per tile */
+    uint32_t *d_kw, *d_Tw, *d_needw, *d_nofast;   /* pruning stage: kept counts, threshold, all-zero flags */
     double *d_span_sq;     /* per span: sum of grad^2 */
     double *d_l2sq;        /* per bucket: sum of grad^2 of the last compress call */
     bool have_l2;
@@ -1278,6 +1394,7 @@ Tables tables_of(const nsml_ctx *c)
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
     t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.fast = c->d_fast;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
+    t.kw = c->d_kw; t.pmask = nullptr;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.chunk = c->chunk;
     return t;
 }
@@ -1444,6 +1561,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
+    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_nofast = nullptr;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
     const char *fd = getenv("NSML_FORCE_DENSE");
@@ -1483,6 +1601,10 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_v, max_n));
     A(dev_alloc(c, &c->d_ts, mt + B1 + 1));
     A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
+    A(dev_alloc(c, &c->d_pmask, mt * (TILE / 32)));
+    A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
+    A(dev_alloc(c, &c->d_nofast, B1));
+    if (rc == NSML_OK && hipMemset(c->d_nofast, 0, B1 * sizeof(uint32_t)) != hipSuccess) rc = NSML_EHIP;
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
@@ -1501,7 +1623,8 @@ int nsml_destroy(nsml_ctx *c)
     void *ptrs[] = {c->d_off, c->d_P, c->d_V, c->d_S, c->d_C, c->d_tile0, c->d_span0, c->d_samp0,
                     c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
-                    c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq};
+                    c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
+                    c->d_Tw, c->d_needw, c->d_nofast};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -1513,14 +1636,15 @@ int nsml_destroy(nsml_ctx *c)
 int nsml_last_hip_error(const nsml_ctx *c) { return c ? c->last_hip : 0; }
 uint64_t nsml_workspace_bytes(const nsml_ctx *c) { return c ? c->ws_bytes : 0; }
 
-int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
-                  const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
-                  uint32_t *idx, void *val, float *scales, void *stream)
+/* Shared body of nsml_compress and nsml_compress_pruned (weights == NULL: no pruning). */
+static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const float *weights,
+                         uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                         uint32_t *idx, void *val, float *scales, void *stream)
 {
     if (!c || !grad || !residual || !idx || !val) return NSML_EINVAL;
     if ((bits == 8 || bits == 4) && !scales) return NSML_EINVAL;
     if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(idx, 4) || !aligned(val, 4) ||
-        !aligned(scales, 4))
+        !aligned(scales, 4) || !aligned(weights, 16))
         return NSML_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     DeviceGuard guard(c->device);
@@ -1530,7 +1654,7 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
     rc = ensure_tables(c, ratio, bits, st);
     if (rc) return rc;
 
-    const Tables t = tables_of(c);
+    Tables t = tables_of(c);
     const Cand cd = cand_of(c);
     const Hists h = hists_of(c, B);
     const uint64_t zw = zero_words(B);
@@ -1540,18 +1664,41 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
     const uint32_t cgrid = (n_ss + 3) / 4 < SIDE_GRID ? (n_ss + 3) / 4 : SIDE_GRID;
     const uint32_t fgrid = c->n_spans < SIDE_GRID ? c->n_spans : SIDE_GRID;
 
+    if (weights) {
+        /* Algorithm 2 Step 2: bitmap of the pruned parameters.  Every bucket takes the dense
+         * select (the kept set is more than half of the bucket), on its own set of tables. */
+        Tables tw = t;
+        tw.k = c->d_kw; tw.T = c->d_Tw; tw.need = c->d_needw; tw.fast = c->d_nofast;
+        tw.fspan0 = c->d_span0;
+        LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
+        LAUNCH(c, KID_WHIST, st, k_whist, c->n_spans, weights, tw, h.h0);
+        LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0);
+        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, weights, tw, cd, h.c1, h.f1, 0u);
+        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err);
+        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, weights, tw, cd, h.c2, h.f2, 0u);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err);
+        LAUNCH(c, KID_COUNT, st, k_count<64>, fgrid, weights, tw, cd, c->d_tG, c->d_tE, 0u);
+        LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cd.G, cd.E, c->d_tG, c->d_tE);
+        LAUNCH(c, KID_WMASK, st, k_wmask, fgrid, weights, tw, (const uint32_t *)c->d_tG,
+               (const uint32_t *)c->d_tE, c->d_pmask);
+        t.pmask = c->d_pmask;
+    }
+
     LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
     if (!c->force_dense)
         LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
     LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
     if (c->force_dense) {
-        LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
+        if (weights) LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, true>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
+        else LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
+    } else if (weights) {
+        LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, true>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
     } else {
         switch (c->nt_mode) {
-        case 1:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 1>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
-        case 3:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 3>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
-        case 5:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 5>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
-        default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        case 1:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 1, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        case 3:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 3, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        case 5:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 5, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
         }
     }
     LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const double *)c->d_span_sq, c->d_l2sq);
@@ -1597,6 +1744,21 @@ int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
     }
     c->have_l2 = true;
     return NSML_OK;
+}
+
+int nsml_compress(nsml_ctx *c, const float *grad, float *residual, uint64_t n,
+                  const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                  uint32_t *idx, void *val, float *scales, void *stream)
+{
+    return compress_impl(c, grad, residual, nullptr, n, bucket_off, B, ratio, bits, idx, val, scales, stream);
+}
+
+int nsml_compress_pruned(nsml_ctx *c, const float *grad, float *residual, const float *weights,
+                         uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                         uint32_t *idx, void *val, float *scales, void *stream)
+{
+    if (!weights) return NSML_EINVAL;
+    return compress_impl(c, grad, residual, weights, n, bucket_off, B, ratio, bits, idx, val, scales, stream);
 }
 
 int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,

@@ -1,0 +1,68 @@
+"""GPU parity for the pruned variant (Algorithm 2 Step 2 + Step 3) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_16235_amd import binding as nsml
+from paper_2506_16235_amd import workloads as W
+from gpu_util import DEV, compare_payload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True, params=["auto", "dense"])
+def path(request, monkeypatch):
+    monkeypatch.setenv("NSML_FORCE_DENSE", "1" if request.param == "dense" else "0")
+    return request.param
+
+
+def _rand(n, seed, sigma=1e-3):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return torch.randn(n, generator=g, device=DEV) * sigma
+
+
+def _run(sizes, ratio, bits, chunk, steps=2, ties=False, seed=0):
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    ctx = nsml.Context(n, len(sizes), chunk)
+    r = torch.zeros(n, device=DEV)
+    r_h = np.zeros(n, dtype=np.float32)
+    for step in range(steps):
+        g = _rand(n, seed + 10 * step)
+        w = _rand(n, seed + 10 * step + 1, sigma=0.05)
+        if ties:
+            w = (w * 40).round() / 40            # many equal |w|, zeros included
+            g = (g * 2e3).round() / 2e3
+        idx, val, sc = ctx.compress_pruned(g, r, w, off, ratio, bits)
+        dense = ctx.decompress(idx, val, sc, n, off, ratio, bits)
+        torch.cuda.synchronize()
+        ctx.path_stats()
+        w_idx, w_val, w_sc = oracle.compress_pruned(g.cpu().numpy(), r_h, w.cpu().numpy(), off, ratio,
+                                                    bits, chunk, nthreads=8)
+        k_b, K, vb, ns = oracle.layout(off, ratio, bits, chunk)
+        got = (idx.cpu().numpy().view(np.uint32)[:K], val.cpu().numpy()[:vb], sc.cpu().numpy()[:ns])
+        compare_payload(off, ratio, bits, chunk, got, (w_idx, w_val, w_sc))
+        assert np.array_equal(r.cpu().numpy().view(np.uint32), r_h.view(np.uint32))
+        w_dense = oracle.decompress(w_idx, w_val, w_sc, n, off, ratio, bits, chunk)
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), w_dense.view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", [4, 8, 16, 32])
+def test_ragged_buckets(bits):
+    _run([1, 64, 2048, 0, 4095, 4097, 3, 17889, 8192, 12289, 1, 50001, 7, 131072 + 5], 0.05, bits, 64)
+
+
+@pytest.mark.parametrize("ratio", [0.001, 0.01, 0.3, 1.0])
+def test_ratios(ratio):
+    _run([300_000, 17, 200_003], ratio, 8, 256)
+
+
+def test_many_equal_weights_and_gradients():
+    _run([100_000, 150_001, 49_999], 0.02, 4, 128, ties=True)
+    _run([100_000, 150_001, 49_999], 0.4, 32, 128, ties=True, seed=5)
+
+
+def test_large_single_bucket():
+    _run([5_000_000], 0.01, 8, 2048, steps=2)
