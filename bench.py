@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prune", action="store_true",
+                    help="time nsml_compress_pruned (weight-magnitude pruning first) instead of nsml_compress")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB copy kernel (k_calib_copy): the yardstick for "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -144,11 +146,22 @@ def main():
         f"workspace={ctx.workspace_bytes / 2**30:.2f} GiB")
 
     step_no = [0]
+    weights = None
+    if args.prune:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(99)
+        weights = torch.empty(n, dtype=torch.float32, device=dev)
+        for lo in range(0, n, 1 << 28):
+            hi = min(n, lo + (1 << 28))
+            weights[lo:hi] = torch.randn(hi - lo, generator=gen, device=dev) * 0.02
 
     def step():
         g = grads[step_no[0] % len(grads)]
         step_no[0] += 1
-        ctx.compress(g, residual, off, ratio, bits, idx, val, sc)
+        if weights is not None:
+            ctx.compress_pruned(g, residual, weights, off, ratio, bits, idx, val, sc)
+        else:
+            ctx.compress(g, residual, off, ratio, bits, idx, val, sc)
         ctx.decompress(idx, val, sc, n, off, ratio, bits, dense)
 
     if args.calibrate_copy:
@@ -205,7 +218,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "elements": n, "buckets": B, "ratio": ratio,
                    "bits": bits, "chunk": chunk, "survivors": K, "payload_bytes": payload,
-                   "distinct_gradients": len(grads), "residual": "carried across steps"},
+                   "distinct_gradients": len(grads), "residual": "carried across steps",
+                   "weight_pruning": bool(args.prune)},
         "hbm_roofline_frac": round(floor_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "floor_bytes_per_step": floor_bytes,
         "roofline": {"kernel": "ef_emit", "bound": "hbm", "achieved": round(achieved, 1),
