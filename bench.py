@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step per distinct gradient in a HIP graph and time graph replays")
     ap.add_argument("--prune", action="store_true",
                     help="time nsml_compress_pruned (weight-magnitude pruning first) instead of nsml_compress")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -175,6 +177,28 @@ def main():
         step()
     torch.cuda.synchronize()
 
+    eager_step = step
+    if args.graph:
+        # one graph per distinct gradient buffer; the residual, payload and dense buffers are shared
+        graphs = []
+        cap_stream = torch.cuda.Stream()
+        for gi in range(len(grads)):
+            gr = torch.cuda.CUDAGraph()
+            step_no[0] = gi
+            with torch.cuda.stream(cap_stream):
+                with torch.cuda.graph(gr, stream=cap_stream):
+                    eager_step()
+            graphs.append(gr)
+        torch.cuda.synchronize()
+        step_no[0] = 0
+
+        def step():
+            graphs[step_no[0] % len(graphs)].replay()
+            step_no[0] += 1
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+
     # ---- the timed region: exactly K steps between two synchronisations
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -190,7 +214,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        eager_step()
     torch.cuda.synchronize()
     wall_prof = time.perf_counter() - t0
     prof = ctx.profile_read()
@@ -219,7 +243,7 @@ def main():
         "config": {"workload": args.workload, "elements": n, "buckets": B, "ratio": ratio,
                    "bits": bits, "chunk": chunk, "survivors": K, "payload_bytes": payload,
                    "distinct_gradients": len(grads), "residual": "carried across steps",
-                   "weight_pruning": bool(args.prune)},
+                   "weight_pruning": bool(args.prune), "hip_graph": bool(args.graph)},
         "hbm_roofline_frac": round(floor_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "floor_bytes_per_step": floor_bytes,
         "roofline": {"kernel": "ef_emit", "bound": "hbm", "achieved": round(achieved, 1),

@@ -91,6 +91,7 @@ struct Tables {
     uint32_t *fast;          /* B   1: the candidates decide the bucket, 0: the dense fallback does */
     uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
+    uint32_t *margin;        /* B   history mode: how far below the last threshold key L is placed */
     uint32_t *kw;            /* B   parameters the pruning step keeps (only with weights) */
     const uint32_t *pmask;   /* pruning bitmap, 128 words per tile, bit = pruned; NULL: no pruning */
     uint32_t B;
@@ -247,6 +248,12 @@ __global__ __launch_bounds__(WG) void k_clear(uint32_t *__restrict__ p, uint64_t
     for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
+__global__ __launch_bounds__(WG) void k_fill_u32(uint32_t *__restrict__ p, uint32_t n, uint32_t v)
+{
+    const uint32_t i = blockIdx.x * WG + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 /* Plain 16-byte copy, the yardstick for the profiler's HBM byte counters. */
 __global__ __launch_bounds__(WG) void k_calib_copy(const f4 *__restrict__ src, f4 *__restrict__ dst, uint64_t n16)
 {
@@ -396,7 +403,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
     const uint64_t nb = t.off[b + 1] - t.off[b];
     const uint32_t k = t.k[b];
     if (nb == 0 || force_dense) {
-        if (tid == 0) { t.L[b] = NONE; t.fast[b] = nb == 0 ? 1u : 0u; }
+        if (tid == 0) t.L[b] = NONE;
         return;
     }
     DigitWalk<NB0> w;
@@ -411,15 +418,13 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
     const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
     if (m == 0 || want_d > (double)m || (double)k > 0.5 * cap_b) {
         /* not enough sample above any bound, or k too large for the staging area */
-        if (tid == 0) { t.L[b] = NONE; t.fast[b] = 0u; }
+        if (tid == 0) t.L[b] = NONE;
         return;
     }
     uint32_t digit, above, at;
     if (w.find((uint32_t)want_d, digit, above, at)) {
         const double est = (double)(above + at) * pop / (double)m;
-        const bool fits = est <= 0.8 * cap_b;
-        t.L[b] = fits ? (digit << SH0) : NONE;
-        t.fast[b] = fits ? 1u : 0u;
+        t.L[b] = est <= 0.8 * cap_b ? (digit << SH0) : NONE;
     }
 }
 
@@ -553,26 +558,38 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
     hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
 }
 
+constexpr uint32_t MARGIN_INIT = 1u << 20;   /* 1/8 octave below the last threshold */
+constexpr uint32_t MARGIN_MIN = 1u << 15, MARGIN_MAX = 1u << 22;
+
 /* Per bucket: exact level-0 digit of the k-th largest key, and whether the candidates can
- * decide the bucket. */
+ * decide the bucket: they are exactly the elements with key >= L_b, so they contain the k
+ * largest iff there are at least k of them (and no staging segment overflowed).  In history
+ * mode the distance between L_b and the threshold is steered by how many candidates came. */
 __global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restrict__ hist0,
+                                             const uint32_t *__restrict__ cand_cnt, int have_cand,
                                              const double *__restrict__ span_sq, double *__restrict__ l2sq)
 {
     __shared__ uint32_t tmp[WG];
     __shared__ double red[WG / 64];
+    __shared__ uint32_t redc[WG / 64];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    {   /* |grad|^2 of the bucket: strided partial sums, then a fixed tree */
+    uint32_t n_cand = 0;
+    {   /* |grad|^2 of the bucket: strided partial sums, then a fixed tree; candidates likewise */
         double acc = 0.0;
         for (uint32_t s = t.span0[b] + tid; s < t.span0[b + 1]; s += WG) acc += span_sq[s];
+        uint32_t cc = 0;
+        if (have_cand)
+            for (uint32_t ss = t.span0[b] * 4 + tid; ss < t.span0[b + 1] * 4; ss += WG) cc += cand_cnt[ss];
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
-        if ((tid & 63) == 0) red[tid >> 6] = acc;
+        for (int d = 32; d >= 1; d >>= 1) { acc += __shfl_xor(acc, d, 64); cc += __shfl_xor(cc, d, 64); }
+        if ((tid & 63) == 0) { red[tid >> 6] = acc; redc[tid >> 6] = cc; }
         __syncthreads();
         if (tid == 0) l2sq[b] = (red[0] + red[1]) + (red[2] + red[3]);
+        n_cand = redc[0] + redc[1] + redc[2] + redc[3];
     }
     const uint32_t want = t.k[b];
     if (want == 0) {                       /* empty bucket: nothing can match */
-        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; }
+        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; t.fast[b] = 1u; }
         return;
     }
     DigitWalk<NB0> w;
@@ -582,7 +599,16 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restric
         t.T[b] = digit;
         t.need[b] = want - above;
         const uint32_t L = t.L[b];
-        if (t.fast[b] && (L == NONE || (L >> SH0) > digit || t.ovf[b])) t.fast[b] = 0u;
+        const bool valid = have_cand && L != NONE && n_cand >= want && !t.ovf[b];
+        t.fast[b] = valid ? 1u : 0u;
+        /* margin control for the next call */
+        uint32_t mg = t.margin[b];
+        if (L != NONE) {
+            if (!valid) mg = min(MARGIN_MAX, mg * 4u);
+            else if ((uint64_t)n_cand * 5u > (uint64_t)want * 8u) mg = max(MARGIN_MIN, mg - mg / 4u);   /* > 1.6 k */
+            else if ((uint64_t)n_cand * 20u < (uint64_t)want * 23u) mg = min(MARGIN_MAX, mg + mg / 4u); /* < 1.15 k */
+        }
+        t.margin[b] = mg;
     }
 }
 
@@ -670,7 +696,8 @@ __device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uin
  * append it to the prefix. */
 template <int LEVEL>
 __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
-                                             const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err)
+                                             const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
+                                             int write_next)
 {
     constexpr int NB = LEVEL == 2 ? NB2 : NB1;
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
@@ -687,8 +714,17 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
     }
     uint32_t digit, above, at;
     if (w.find(want, digit, above, at)) {
-        t.T[b] = (t.T[b] << BITS) | digit;
+        const uint32_t T = (t.T[b] << BITS) | digit;
+        t.T[b] = T;
         t.need[b] = want - above;
+        if (LEVEL == 2 && write_next) {
+            /* history mode: next call's candidate bound sits a margin below this threshold */
+            const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
+            const uint32_t mg = t.margin[b];
+            /* elements with key >= T: the k survivors plus the equal ones left out */
+            const double ge_T = (double)t.k[b] - (double)(want - above) + (double)at;
+            t.L[b] = ((double)t.k[b] > 0.5 * cap_b || ge_T > 0.8 * cap_b) ? NONE : (T > mg ? T - mg : 0u);
+        }
     }
 }
 
@@ -1332,6 +1368,9 @@ struct nsml_ctx {
     int span_override;
     int force_dense;
     int nt_mode;
+    int use_history;       /* place the candidate bound from the previous call's thresholds */
+    bool hist_ready; double hist_ratio; bool hist_pruned;
+    uint32_t *d_margin;
 
     /* profiling */
     bool prof;
@@ -1394,7 +1433,7 @@ Tables tables_of(const nsml_ctx *c)
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
     t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.fast = c->d_fast;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
-    t.kw = c->d_kw; t.pmask = nullptr;
+    t.kw = c->d_kw; t.pmask = nullptr; t.margin = c->d_margin;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.chunk = c->chunk;
     return t;
 }
@@ -1514,6 +1553,8 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
     NSML_HIP(c, hipMemcpyAsync(c->d_samp0, hp_m, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
     LAUNCH(c, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)c->d_span0, B,
            (uint32_t)ns, c->d_span_b);
+    LAUNCH(c, KID_SPANMAP, st, k_fill_u32, (B + WG - 1) / WG, c->d_margin, B, MARGIN_INIT);
+    c->hist_ready = false;
     NSML_HIP(c, hipStreamSynchronize(st));
 
     c->h_off.assign(off, off + B + 1);
@@ -1568,6 +1609,12 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->force_dense = (fd && atoi(fd) != 0) ? 1 : 0;
     const char *ntm = getenv("NSML_NT");
     c->nt_mode = ntm ? atoi(ntm) : 7;
+    const char *hs = getenv("NSML_HISTORY");
+    /* off by default: while error feedback is still building up, thresholds climb from step to
+     * step and bounds taken from the previous step let in about twice the candidates a fresh
+     * sample does; the sample costs 1 % of a step */
+    c->use_history = hs ? (atoi(hs) != 0) : 0;
+    c->hist_ready = false; c->hist_ratio = 0.0; c->hist_pruned = false; c->d_margin = nullptr;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
@@ -1603,7 +1650,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
     A(dev_alloc(c, &c->d_pmask, mt * (TILE / 32)));
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
-    A(dev_alloc(c, &c->d_nofast, B1));
+    A(dev_alloc(c, &c->d_nofast, B1)); A(dev_alloc(c, &c->d_margin, B1));
     if (rc == NSML_OK && hipMemset(c->d_nofast, 0, B1 * sizeof(uint32_t)) != hipSuccess) rc = NSML_EHIP;
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
@@ -1624,7 +1671,7 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
-                    c->d_Tw, c->d_needw, c->d_nofast};
+                    c->d_Tw, c->d_needw, c->d_nofast, c->d_margin};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -1674,9 +1721,9 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         LAUNCH(c, KID_WHIST, st, k_whist, c->n_spans, weights, tw, h.h0);
         LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0);
         LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, weights, tw, cd, h.c1, h.f1, 0u);
-        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err);
+        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
         LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, weights, tw, cd, h.c2, h.f2, 0u);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, 0);
         LAUNCH(c, KID_COUNT, st, k_count<64>, fgrid, weights, tw, cd, c->d_tG, c->d_tE, 0u);
         LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cd.G, cd.E, c->d_tG, c->d_tE);
         LAUNCH(c, KID_WMASK, st, k_wmask, fgrid, weights, tw, (const uint32_t *)c->d_tG,
@@ -1684,10 +1731,20 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         t.pmask = c->d_pmask;
     }
 
+    /* where the candidate bounds L_b come from: the thresholds of the previous call when it had
+     * the same layout, ratio and pruning (k_pick<2> left them in place), else a sample of
+     * this gradient */
+    const bool pruned = weights != nullptr;
+    const bool from_history = c->use_history && !c->force_dense && c->hist_ready &&
+                              c->hist_ratio == ratio && c->hist_pruned == pruned;
+    const int write_next = (c->use_history && !c->force_dense) ? 1 : 0;
+    c->hist_ready = false;
     LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
-    if (!c->force_dense)
-        LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
-    LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
+    if (!from_history) {
+        if (!c->force_dense)
+            LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
+        LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
+    }
     if (c->force_dense) {
         if (weights) LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, true>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
         else LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
@@ -1701,7 +1758,8 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
         }
     }
-    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const double *)c->d_span_sq, c->d_l2sq);
+    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const uint32_t *)cd.cnt,
+           c->force_dense ? 0 : 1, (const double *)c->d_span_sq, c->d_l2sq);
     LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
     /* every stage serves both kinds of bucket: candidate segments first, then the dense
      * spans of the buckets the candidates could not decide */
@@ -1715,13 +1773,13 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     } else {
         LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
     }
-    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err);
+    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
     if (narrow) {
         LAUNCH(c, KID_REFINE2, st, (k_refine<2, 16>), cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
     } else {
         LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
     }
-    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err);
+    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, write_next);
     if (narrow) {
         LAUNCH(c, KID_COUNT, st, k_count<16>, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
     } else {
@@ -1743,6 +1801,9 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
     }
     c->have_l2 = true;
+    c->hist_ready = write_next != 0;
+    c->hist_ratio = ratio;
+    c->hist_pruned = pruned;
     return NSML_OK;
 }
 

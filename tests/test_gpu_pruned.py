@@ -11,9 +11,10 @@ from gpu_util import DEV, compare_payload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["auto", "dense"])
+@pytest.fixture(autouse=True, params=["auto", "history", "dense"])
 def path(request, monkeypatch):
     monkeypatch.setenv("NSML_FORCE_DENSE", "1" if request.param == "dense" else "0")
+    monkeypatch.setenv("NSML_HISTORY", "1" if request.param == "history" else "0")
     return request.param
 
 
