@@ -1233,7 +1233,7 @@ __global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ i
  * survivors that fall inside it, found through the tile-start table) and written out once with
  * aligned 16-byte stores, so no output line is touched twice and no atomics are needed.  The
  * loads of the next tile's survivors are issued before the current tile is written out. */
-template <int BITS>
+template <int BITS, bool NTS>
 __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx, const void *__restrict__ val,
                                                const float *__restrict__ scales, Tables t,
                                                const uint32_t *__restrict__ ts, float *__restrict__ dense)
@@ -1288,7 +1288,9 @@ __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx,
             const uint32_t sl = (u * WG + tid) * 4;
             const uint64_t gi = tb + sl;
             if (gi >= s.lo && gi + 4 <= s.hi) {
-                *reinterpret_cast<f4 *>(dense + gi) = *reinterpret_cast<const f4 *>(&tile[sl]);
+                const f4 v = *reinterpret_cast<const f4 *>(&tile[sl]);
+                if (NTS) __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dense + gi));
+                else *reinterpret_cast<f4 *>(dense + gi) = v;
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -1368,6 +1370,7 @@ struct nsml_ctx {
     int span_override;
     int force_dense;
     int nt_mode;
+    int nt_dense;          /* non-temporal stores for the dense output of decompress */
     int use_history;       /* place the candidate bound from the previous call's thresholds */
     bool hist_ready; double hist_ratio; bool hist_pruned;
     uint32_t *d_margin;
@@ -1609,6 +1612,8 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->force_dense = (fd && atoi(fd) != 0) ? 1 : 0;
     const char *ntm = getenv("NSML_NT");
     c->nt_mode = ntm ? atoi(ntm) : 7;
+    const char *nd = getenv("NSML_NT_DENSE");
+    c->nt_dense = nd ? (atoi(nd) != 0) : 1;
     const char *hs = getenv("NSML_HISTORY");
     /* off by default: while error feedback is still building up, thresholds climb from step to
      * step and bounds taken from the previous step let in about twice the candidates a fresh
@@ -1841,11 +1846,20 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     const uint64_t want = (c->K + WG - 1) / WG;
     LAUNCH(c, KID_TILESTART, st, k_tilestart, (uint32_t)(want < 16384 ? want : 16384), idx, t, c->K, c->d_ts);
     const uint32_t *ts = c->d_ts;
-    switch (bits) {
-    case 32: LAUNCH(c, KID_DECOMP, st, k_decomp<32>, c->n_spans, idx, val, scales, t, ts, dense_out); break;
-    case 16: LAUNCH(c, KID_DECOMP, st, k_decomp<16>, c->n_spans, idx, val, scales, t, ts, dense_out); break;
-    case 8:  LAUNCH(c, KID_DECOMP, st, k_decomp<8>,  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-    default: LAUNCH(c, KID_DECOMP, st, k_decomp<4>,  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+    if (c->nt_dense) {
+        switch (bits) {
+        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp<32, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp<16, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp<8, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        default: LAUNCH(c, KID_DECOMP, st, (k_decomp<4, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        }
+    } else {
+        switch (bits) {
+        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp<32, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp<16, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp<8, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        default: LAUNCH(c, KID_DECOMP, st, (k_decomp<4, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        }
     }
     return NSML_OK;
 }
