@@ -641,6 +641,7 @@ __global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
 /* GROUP = lanes per segment: 16 when segments are short (low ratios), 64 otherwise. */
 struct Seg {
     uint32_t ss, b, cnt, sub, gl;
+    uint32_t T;          /* the bucket's threshold key / prefix so far */
     uint64_t base;
     bool active;
 };
@@ -655,10 +656,14 @@ __device__ __forceinline__ Seg seg_of(const Tables &t, const Cand &c, uint32_t b
     g.gl = lane % GROUP;
     const uint32_t wave_g = bid * 4 + (threadIdx.x >> 6);
     g.ss = (it * nblk * 4 + wave_g) * (64 / GROUP) + g.sub;
-    g.active = g.ss < t.n_spans * 4;
-    g.b = g.active ? t.span_b[g.ss >> 2] : 0u;
-    g.active = g.active && t.fast[g.b];
-    g.cnt = g.active ? c.cnt[g.ss] : 0u;
+    const bool in_range = g.ss < t.n_spans * 4;
+    /* independent loads first (segment -> bucket, entry count), then the bucket's state */
+    g.b = in_range ? t.span_b[g.ss >> 2] : 0u;
+    const uint32_t cnt = in_range ? c.cnt[g.ss] : 0u;
+    const uint32_t fast = t.fast[g.b];
+    g.T = t.T[g.b];
+    g.active = in_range && fast;
+    g.cnt = g.active ? cnt : 0u;
     g.base = (uint64_t)g.ss * c.cap;
     return g;
 }
@@ -683,7 +688,7 @@ __device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uin
     const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
     for (uint32_t it = 0; it < rounds; ++it) {
         const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
-        const uint32_t prefix = g.active ? t.T[g.b] : 0u;
+        const uint32_t prefix = g.T;
         for (uint32_t i = g.gl; i < g.cnt; i += GROUP) {
             const uint32_t key = keyof(c.val[g.base + i]);
             if ((key >> PSH) == prefix) atomicAdd(&hist[(uint64_t)g.b * NB + ((key >> DSH) & (NB - 1))], 1u);
@@ -735,7 +740,7 @@ __device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint
     const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
     for (uint32_t it = 0; it < rounds; ++it) {
         const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
-        const uint32_t T = g.active ? t.T[g.b] : 0u;
+        const uint32_t T = g.T;
         uint32_t ng = 0, ne = 0;
         for (uint32_t i = g.gl; i < g.cnt; i += GROUP) {
             const uint32_t key = keyof(c.val[g.base + i]);
@@ -784,9 +789,10 @@ __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint
     const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
     for (uint32_t it = 0; it < rounds; ++it) {
         const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
-        const uint32_t T = g.active ? t.T[g.b] : 0u, e_b = g.active ? t.need[g.b] : 0u;
-        const uint64_t Pb = g.active ? t.P[g.b] : 0ull;
-        uint32_t run_g = g.active ? c.G[g.ss] : 0u, run_e = g.active ? c.E[g.ss] : 0u;
+        const uint32_t T = g.T, e_b = t.need[g.b];
+        const uint64_t Pb = t.P[g.b];
+        const bool in_range = g.ss < t.n_spans * 4;
+        uint32_t run_g = in_range ? c.G[g.ss] : 0u, run_e = in_range ? c.E[g.ss] : 0u;
         const uint32_t shift = g.sub * GROUP;
         const uint64_t below = (1ull << g.gl) - 1ull;
         const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << (GROUP % 64)) - 1ull);
