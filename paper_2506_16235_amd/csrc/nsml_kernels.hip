@@ -97,17 +97,19 @@ struct Tables {
     uint32_t B;
     uint32_t n_spans;
     uint32_t spanT;          /* tiles per span */
+    uint32_t segSh;          /* log2 of the staging segments per span (= wavefronts of the streaming pass) */
     uint32_t chunk;
 };
 
-/* Candidate staging: subspan ss = 4 * span + wavefront owns entries [ss * cap, ss * cap + cnt[ss]) */
+/* Candidate staging: segment ss = (span << segSh) + wavefront owns entries [ss * cap, ss * cap + cnt[ss]) */
 struct Cand {
     uint32_t *idx;   /* bucket-local index */
     float *val;      /* accumulator value */
-    uint32_t *cnt;   /* entries per subspan */
-    uint32_t *G;     /* per subspan: #(key > T), later its exclusive prefix inside the bucket */
-    uint32_t *E;     /* per subspan: #(key == T), later its exclusive prefix */
-    uint32_t cap;    /* entries per subspan = spanT * 256 (a quarter of the elements it covers) */
+    uint32_t *cnt;   /* entries per segment */
+    uint32_t *G;     /* per segment: #(key > T), later its exclusive prefix inside the bucket */
+    uint32_t *E;     /* per segment: #(key == T), later its exclusive prefix */
+    uint32_t cap;    /* entries per segment: a quarter of the elements it covers */
+    uint32_t splitSh; /* log2 of the wavefronts that share a chunk of 64 segments in the candidate kernels */
 };
 
 typedef float f4 __attribute__((ext_vector_type(4)));   /* one aligned 16-byte access */
@@ -279,9 +281,10 @@ __device__ __forceinline__ void hist_quad_full(uint32_t *h, uint32_t d0, uint32_
     }
 }
 
-__device__ __forceinline__ void hist_flush(const uint32_t *h, uint32_t *__restrict__ dst, int nb)
+__device__ __forceinline__ void hist_flush(const uint32_t *h, uint32_t *__restrict__ dst, int nb,
+                                           int nthreads = WG)
 {
-    for (int i = threadIdx.x; i < nb; i += WG) {
+    for (int i = threadIdx.x; i < nb; i += nthreads) {
         const uint32_t c = h[i];
         if (c) atomicAdd(&dst[i], c);
     }
@@ -483,28 +486,33 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
 
 /* acc = grad + residual over a span, written over residual (Sec. 4.2 Step 3: what top-k
  * filters out is accumulated locally; the add is that), the exact level-0 histogram, and the
- * candidates.  Each wavefront owns a contiguous quarter of the span and its own staging
- * segment, so candidates come out in index order without any cross-wavefront exchange. */
+ * candidates.  Each wavefront owns a contiguous share of the span and its own staging
+ * segment, so candidates come out in index order without any cross-wavefront exchange.
+ * Launched with 64 << segSh threads: large spans run 8 or 16 wavefronts per workgroup (one
+ * or two tiles each), which keeps more loads in flight per compute unit than four do. */
+constexpr uint32_t MAX_SEG_WAVES = 16;
 template <bool EMIT, int NT, bool PRUNE>
-__global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
+__global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
                                                 Tables t, uint32_t *__restrict__ hist0, Cand c,
                                                 double *__restrict__ span_sq)
 {
     __shared__ uint32_t h[NB0];
-    __shared__ double sq_w[WG / 64];
+    __shared__ double sq_w[MAX_SEG_WAVES];
     double sq = 0.0;                     /* sum of grad^2 over this thread's elements */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < NB0; i += WG) h[i] = 0;
+    const uint32_t nthreads = 64u << t.segSh;
+    for (uint32_t i = tid; i < NB0; i += nthreads) h[i] = 0;
     const SpanGeo s = span_geo(t, blockIdx.x);
     const uint32_t L = EMIT ? t.L[s.b] : NONE;
     const uint64_t lt = (1ull << lane) - 1ull;
-    const uint32_t ss = blockIdx.x * 4 + wave;
+    const uint32_t ss = (blockIdx.x << t.segSh) + wave;
     const uint64_t cbase = (uint64_t)ss * c.cap;
     uint32_t wcount = 0;
     __syncthreads();
-    /* this wavefront's wave-tiles: [wave * spanT, (wave + 1) * spanT) of the span's 4 * ntiles */
-    const uint32_t wt0 = wave * t.spanT;
-    const uint32_t wt1 = min(s.ntiles * 4u, wt0 + t.spanT);
+    /* this wavefront's wave-tiles: [wave * per, (wave + 1) * per) of the span's 4 * ntiles */
+    const uint32_t per = (t.spanT * 4u) >> t.segSh;
+    const uint32_t wt0 = wave * per;
+    const uint32_t wt1 = min(s.ntiles * 4u, wt0 + per);
     for (uint32_t wt = wt0; wt < wt1; ++wt) {
         const uint64_t wb = s.base + (uint64_t)wt * WTILE;
         if (wb >= s.lo && wb + WTILE <= s.hi) {
@@ -554,8 +562,12 @@ __global__ __launch_bounds__(WG) void k_ef_emit(const float *__restrict__ g, flo
     for (int d = 32; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, 64);
     if (lane == 0) sq_w[wave] = sq;
     __syncthreads();
-    if (tid == 0) span_sq[blockIdx.x] = (sq_w[0] + sq_w[1]) + (sq_w[2] + sq_w[3]);
-    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
+    if (tid == 0) {
+        double tot = 0.0;
+        for (uint32_t w = 0; w < (1u << t.segSh); w += 4) tot += (sq_w[w] + sq_w[w + 1]) + (sq_w[w + 2] + sq_w[w + 3]);
+        span_sq[blockIdx.x] = tot;
+    }
+    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0, (int)nthreads);
 }
 
 constexpr uint32_t MARGIN_INIT = 1u << 20;   /* 1/8 octave below the last threshold */
@@ -579,7 +591,7 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restric
         for (uint32_t s = t.span0[b] + tid; s < t.span0[b + 1]; s += WG) acc += span_sq[s];
         uint32_t cc = 0;
         if (have_cand)
-            for (uint32_t ss = t.span0[b] * 4 + tid; ss < t.span0[b + 1] * 4; ss += WG) cc += cand_cnt[ss];
+            for (uint32_t ss = (t.span0[b] << t.segSh) + tid; ss < (t.span0[b + 1] << t.segSh); ss += WG) cc += cand_cnt[ss];
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) { acc += __shfl_xor(acc, d, 64); cc += __shfl_xor(cc, d, 64); }
         if ((tid & 63) == 0) { red[tid >> 6] = acc; redc[tid >> 6] = cc; }
@@ -635,45 +647,37 @@ __global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
 
 /* ------------------------------------------------------------------ candidate path */
 
-/* The candidate kernels walk the staging segments.  A segment usually holds a few dozen
- * entries, so a wavefront takes four segments at a time, 16 lanes each: the table look-ups of
- * four segments are in flight together and the lanes stay busy. */
-/* GROUP = lanes per segment: 16 when segments are short (low ratios), 64 otherwise. */
-struct Seg {
-    uint32_t ss, b, cnt, sub, gl;
+/* The candidate kernels walk the staging segments, 64 consecutive ones per wavefront at a
+ * time.  Lane l first fetches what describes segment 64 * chunk + l (bucket, entry count,
+ * threshold): one round of look-ups for 64 segments.  Then the wavefront goes through them
+ * 64 / GROUP at a time, GROUP lanes per segment, taking each description from the lane that
+ * holds it.  GROUP is 16 when segments are short (low ratios), 64 otherwise.  Entries are
+ * fetched four per lane before any is used, so a segment costs about one memory round trip.
+ * When there are fewer chunks than wavefronts, 2^splitSh wavefronts share a chunk and take
+ * every 2^splitSh-th round of it. */
+struct SegMeta {
+    uint32_t ss, b, cnt;
     uint32_t T;          /* the bucket's threshold key / prefix so far */
-    uint64_t base;
-    bool active;
+    bool in_range, active;
 };
 
-/* segment handled by this lane's group in round `it` of a grid-stride walk */
-template <uint32_t GROUP>
-__device__ __forceinline__ Seg seg_of(const Tables &t, const Cand &c, uint32_t bid, uint32_t nblk, uint32_t it)
+__device__ __forceinline__ SegMeta seg_meta(const Tables &t, const Cand &c, uint32_t chunk)
 {
-    Seg g;
-    const uint32_t lane = threadIdx.x & 63;
-    g.sub = lane / GROUP;
-    g.gl = lane % GROUP;
-    const uint32_t wave_g = bid * 4 + (threadIdx.x >> 6);
-    g.ss = (it * nblk * 4 + wave_g) * (64 / GROUP) + g.sub;
-    const bool in_range = g.ss < t.n_spans * 4;
+    SegMeta m;
+    m.ss = chunk * 64 + (threadIdx.x & 63);
+    m.in_range = m.ss < (t.n_spans << t.segSh);
     /* independent loads first (segment -> bucket, entry count), then the bucket's state */
-    g.b = in_range ? t.span_b[g.ss >> 2] : 0u;
-    const uint32_t cnt = in_range ? c.cnt[g.ss] : 0u;
-    const uint32_t fast = t.fast[g.b];
-    g.T = t.T[g.b];
-    g.active = in_range && fast;
-    g.cnt = g.active ? cnt : 0u;
-    g.base = (uint64_t)g.ss * c.cap;
-    return g;
+    m.b = m.in_range ? t.span_b[m.ss >> t.segSh] : 0u;
+    const uint32_t cnt = m.in_range ? c.cnt[m.ss] : 0u;
+    m.T = t.T[m.b];
+    m.active = m.in_range && t.fast[m.b] != 0u;
+    m.cnt = m.active ? cnt : 0u;
+    return m;
 }
 
-template <uint32_t GROUP>
-__device__ __forceinline__ uint32_t seg_rounds(const Tables &t, uint32_t nblk)
-{
-    const uint32_t per_round = nblk * 4 * (64 / GROUP);
-    return (t.n_spans * 4 + per_round - 1) / per_round;
-}
+__device__ __forceinline__ uint32_t seg_chunks(const Tables &t) { return ((t.n_spans << t.segSh) + 63u) / 64u; }
+
+constexpr uint32_t CU = 4;   /* entries a lane fetches ahead */
 
 /* Next-digit histogram over the candidates that carry the prefix found so far (LEVEL 1:
  * 12-bit prefix, digit = key bits 18..7; LEVEL 2: 24-bit prefix, digit = bits 6..0).  The
@@ -685,13 +689,34 @@ __device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uin
     constexpr int NB = LEVEL == 1 ? NB1 : NB2;
     constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
     constexpr int DSH = LEVEL == 1 ? SH1 : 0;
-    const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
-    for (uint32_t it = 0; it < rounds; ++it) {
-        const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
-        const uint32_t prefix = g.T;
-        for (uint32_t i = g.gl; i < g.cnt; i += GROUP) {
-            const uint32_t key = keyof(c.val[g.base + i]);
-            if ((key >> PSH) == prefix) atomicAdd(&hist[(uint64_t)g.b * NB + ((key >> DSH) & (NB - 1))], 1u);
+    constexpr uint32_t SPR = 64 / GROUP;             /* segments per round */
+    const uint32_t lane = threadIdx.x & 63, sub = lane / GROUP, gl = lane % GROUP;
+    const uint32_t n_chunks = seg_chunks(t);
+    const uint32_t split = 1u << c.splitSh;
+    for (uint32_t v = bid * 4 + (threadIdx.x >> 6); v < (n_chunks << c.splitSh); v += nblk * 4) {
+        const uint32_t chunk = v >> c.splitSh;
+        const SegMeta m = seg_meta(t, c, chunk);
+        if (__ballot(m.cnt != 0u) == 0ull) continue;
+        for (uint32_t rd = v & (split - 1u); rd < GROUP; rd += split) {
+            const uint32_t src = rd * SPR + sub;
+            const uint32_t cnt = __shfl(m.cnt, src, 64);
+            if (__ballot(cnt != 0u) == 0ull) continue;
+            const uint32_t prefix = __shfl(m.T, src, 64), b = __shfl(m.b, src, 64);
+            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
+            for (uint32_t i0 = gl; i0 < cnt; i0 += CU * GROUP) {
+                float x[CU];
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t i = i0 + u * GROUP;
+                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t key = keyof(x[u]);
+                    if (i0 + u * GROUP < cnt && (key >> PSH) == prefix)
+                        atomicAdd(&hist[(uint64_t)b * NB + ((key >> DSH) & (NB - 1))], 1u);
+                }
+            }
         }
     }
 }
@@ -733,50 +758,96 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
     }
 }
 
-/* Per segment: how many candidates exceed the threshold, how many equal it. */
+/* Per segment: how many candidates exceed the threshold, how many equal it.  The counts of
+ * a chunk's 64 segments are gathered back into the lanes that described them and stored
+ * side by side. */
 template <uint32_t GROUP>
 __device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint32_t bid, uint32_t nblk)
 {
-    const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
-    for (uint32_t it = 0; it < rounds; ++it) {
-        const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
-        const uint32_t T = g.T;
-        uint32_t ng = 0, ne = 0;
-        for (uint32_t i = g.gl; i < g.cnt; i += GROUP) {
-            const uint32_t key = keyof(c.val[g.base + i]);
-            ng += key > T ? 1u : 0u;
-            ne += key == T ? 1u : 0u;
-        }
+    constexpr uint32_t SPR = 64 / GROUP;
+    const uint32_t lane = threadIdx.x & 63, sub = lane / GROUP, gl = lane % GROUP;
+    const uint32_t n_chunks = seg_chunks(t);
+    const uint32_t split = 1u << c.splitSh;
+    for (uint32_t v = bid * 4 + (threadIdx.x >> 6); v < (n_chunks << c.splitSh); v += nblk * 4) {
+        const uint32_t chunk = v >> c.splitSh, part = v & (split - 1u);
+        const SegMeta m = seg_meta(t, c, chunk);
+        if (__ballot(m.active) == 0ull) continue;
+        uint32_t my_g = 0, my_e = 0;             /* results for segment 64 * chunk + lane */
+        for (uint32_t rd = part; rd < GROUP; rd += split) {
+            const uint32_t src = rd * SPR + sub;
+            const uint32_t cnt = __shfl(m.cnt, src, 64);
+            if (__ballot(cnt != 0u) == 0ull) continue;
+            const uint32_t T = __shfl(m.T, src, 64);
+            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
+            uint32_t ng = 0, ne = 0;
+            for (uint32_t i0 = gl; i0 < cnt; i0 += CU * GROUP) {
+                float x[CU];
 #pragma unroll
-        for (int d = GROUP / 2; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
-        if (g.active && g.gl == 0) { c.G[g.ss] = ng; c.E[g.ss] = ne; }
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t i = i0 + u * GROUP;
+                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t key = keyof(x[u]);
+                    const bool in = i0 + u * GROUP < cnt;
+                    ng += (in && key > T) ? 1u : 0u;
+                    ne += (in && key == T) ? 1u : 0u;
+                }
+            }
+#pragma unroll
+            for (int d = GROUP / 2; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
+            /* segment rd * SPR + j was counted by the group of lanes starting at j * GROUP */
+            const uint32_t from = (lane % SPR) * GROUP;
+            const uint32_t got_g = __shfl(ng, from, 64), got_e = __shfl(ne, from, 64);
+            if (lane / SPR == rd) { my_g = got_g; my_e = got_e; }
+        }
+        /* this wavefront took the rounds congruent to `part` */
+        if (m.active && ((lane / SPR) & (split - 1u)) == part) { c.G[m.ss] = my_g; c.E[m.ss] = my_e; }
     }
 }
 
-/* Per bucket: exclusive scan, in place, of per-unit counts (units: the bucket's subspans on
- * the candidate path, its tiles on the fallback path). */
+/* Per bucket: exclusive scan, in place, of per-unit counts (units: the bucket's staging
+ * segments on the candidate path, its tiles on the fallback path).  Both counts of a unit
+ * travel as one 64-bit word (neither total can reach 2^32: a bucket has fewer elements), and
+ * every thread takes four consecutive units, so a round covers 1024 units with one scan. */
 __global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
                                              uint32_t *__restrict__ tG, uint32_t *__restrict__ tE)
 {
-    __shared__ uint32_t tmp[WG];
-    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    __shared__ uint64_t tmp[WG / 64];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t mode = t.fast[b];
     uint32_t *G = mode ? cG : tG, *E = mode ? cE : tE;
-    const uint32_t t0 = mode ? t.span0[b] * 4 : t.tile0[b];
-    const uint32_t t1 = mode ? t.span0[b + 1] * 4 : t.tile0[b + 1];
-    uint32_t carry_g = 0, carry_e = 0;
-    for (uint32_t base = t0; base < t1; base += WG) {
-        const uint32_t i = base + tid;
-        const uint32_t g = i < t1 ? G[i] : 0u, e = i < t1 ? E[i] : 0u;
-        const uint32_t ig = block_incl_scan(g, tmp);
-        const uint32_t tot_g = tmp[WG - 1];
+    const uint32_t t0 = mode ? t.span0[b] << t.segSh : t.tile0[b];
+    const uint32_t t1 = mode ? t.span0[b + 1] << t.segSh : t.tile0[b + 1];
+    uint64_t carry = 0;
+    for (uint32_t base = t0; base < t1; base += WG * 4) {
+        const uint32_t i0 = base + tid * 4;
+        uint64_t v[4], x = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v[j] = i0 + j < t1 ? ((uint64_t)G[i0 + j] << 32) | (uint64_t)E[i0 + j] : 0ull;
+            x += v[j];
+        }
+        const uint64_t own = x;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t hi = __shfl_up((uint32_t)(x >> 32), d, 64), lo = __shfl_up((uint32_t)x, d, 64);
+            if (lane >= (uint32_t)d) x += ((uint64_t)hi << 32) | (uint64_t)lo;
+        }
+        if (lane == 63) tmp[wave] = x;
         __syncthreads();
-        const uint32_t ie = block_incl_scan(e, tmp);
-        const uint32_t tot_e = tmp[WG - 1];
+        uint64_t before = carry, total = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < WG / 64; ++w) { before += w < wave ? tmp[w] : 0ull; total += tmp[w]; }
         __syncthreads();
-        if (i < t1) { G[i] = carry_g + ig - g; E[i] = carry_e + ie - e; }
-        carry_g += tot_g;
-        carry_e += tot_e;
+        uint64_t run = before + x - own;         /* exclusive prefix of this thread's first unit */
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i0 + j < t1) { G[i0 + j] = (uint32_t)(run >> 32); E[i0 + j] = (uint32_t)run; }
+            run += v[j];
+        }
+        carry += total;
     }
 }
 
@@ -786,42 +857,59 @@ template <uint32_t GROUP>
 __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint32_t *__restrict__ idx_out,
                                             float *__restrict__ v_out, uint32_t bid, uint32_t nblk)
 {
-    const uint32_t rounds = seg_rounds<GROUP>(t, nblk);
-    for (uint32_t it = 0; it < rounds; ++it) {
-        const Seg g = seg_of<GROUP>(t, c, bid, nblk, it);
-        const uint32_t T = g.T, e_b = t.need[g.b];
-        const uint64_t Pb = t.P[g.b];
-        const bool in_range = g.ss < t.n_spans * 4;
-        uint32_t run_g = in_range ? c.G[g.ss] : 0u, run_e = in_range ? c.E[g.ss] : 0u;
-        const uint32_t shift = g.sub * GROUP;
-        const uint64_t below = (1ull << g.gl) - 1ull;
-        const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << (GROUP % 64)) - 1ull);
-        /* the four groups of the wavefront advance together: ballots need every lane */
-        uint32_t maxcnt = g.cnt;
+    constexpr uint32_t SPR = 64 / GROUP;
+    const uint32_t lane = threadIdx.x & 63, sub = lane / GROUP, gl = lane % GROUP;
+    const uint32_t shift = sub * GROUP;
+    const uint64_t below = (1ull << gl) - 1ull;
+    const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << (GROUP % 64)) - 1ull);
+    const uint32_t n_chunks = seg_chunks(t);
+    const uint32_t split = 1u << c.splitSh;
+    for (uint32_t v = bid * 4 + (threadIdx.x >> 6); v < (n_chunks << c.splitSh); v += nblk * 4) {
+        const uint32_t chunk = v >> c.splitSh;
+        const SegMeta m = seg_meta(t, c, chunk);
+        if (__ballot(m.cnt != 0u) == 0ull) continue;
+        const uint32_t m_g = m.in_range ? c.G[m.ss] : 0u, m_e = m.in_range ? c.E[m.ss] : 0u;
+        const uint32_t m_need = t.need[m.b];
+        const uint64_t m_P = t.P[m.b];
+        for (uint32_t rd = v & (split - 1u); rd < GROUP; rd += split) {
+            const uint32_t src = rd * SPR + sub;
+            const uint32_t cnt = __shfl(m.cnt, src, 64);
+            /* the groups of the wavefront advance together: ballots need every lane */
+            uint32_t maxcnt = cnt;
 #pragma unroll
-        for (int d = 32; d >= (int)GROUP; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
-        for (uint32_t i0 = 0; i0 < maxcnt; i0 += GROUP) {
-            const uint32_t i = i0 + g.gl;
-            float x = 0.0f;
-            uint32_t li = 0;
-            bool isg = false, ise = false;
-            if (i < g.cnt) {
-                x = c.val[g.base + i];
-                li = c.idx[g.base + i];
-                const uint32_t key = keyof(x);
-                isg = key > T;
-                ise = key == T;
+            for (int d = 32; d >= (int)GROUP; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
+            if (maxcnt == 0u) continue;
+            const uint32_t T = __shfl(m.T, src, 64), e_b = __shfl(m_need, src, 64);
+            uint32_t run_g = __shfl(m_g, src, 64), run_e = __shfl(m_e, src, 64);
+            const uint64_t Pb = ((uint64_t)__shfl((uint32_t)(m_P >> 32), src, 64) << 32) |
+                                (uint64_t)__shfl((uint32_t)m_P, src, 64);
+            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
+            for (uint32_t i0 = 0; i0 < maxcnt; i0 += CU * GROUP) {
+                float x[CU];
+                uint32_t li[CU];
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t i = i0 + u * GROUP + gl;
+                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
+                    li[u] = i < cnt ? c.idx[base + i] : 0u;
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t key = keyof(x[u]);
+                    const bool in = i0 + u * GROUP + gl < cnt;
+                    const bool isg = in && key > T, ise = in && key == T;
+                    const uint64_t bg = (__ballot(isg) >> shift) & gmask;
+                    const uint64_t be = (__ballot(ise) >> shift) & gmask;
+                    const uint32_t pg = run_g + __popcll(bg & below), pe = run_e + __popcll(be & below);
+                    if (isg || (ise && pe < e_b)) {
+                        const uint64_t pos = Pb + pg + min(e_b, pe);
+                        idx_out[pos] = li[u];
+                        v_out[pos] = x[u];
+                    }
+                    run_g += __popcll(bg);
+                    run_e += __popcll(be);
+                }
             }
-            const uint64_t bg = (__ballot(isg) >> shift) & gmask;
-            const uint64_t be = (__ballot(ise) >> shift) & gmask;
-            const uint32_t pg = run_g + __popcll(bg & below), pe = run_e + __popcll(be & below);
-            if (isg || (ise && pe < e_b)) {
-                const uint64_t pos = Pb + pg + min(e_b, pe);
-                idx_out[pos] = li;
-                v_out[pos] = x;
-            }
-            run_g += __popcll(bg);
-            run_e += __popcll(be);
         }
     }
 }
@@ -1368,12 +1456,14 @@ struct nsml_ctx {
     std::vector<uint64_t> h_off;
     uint32_t B;
     uint64_t n;
-    uint32_t n_tiles, n_spans, n_samp, spanT;
+    uint32_t n_tiles, n_spans, n_samp, spanT, segSh;
     bool tables_valid;
     double t_ratio; int t_bits;       /* what d_k/d_P/... were computed for */
     uint64_t K, NC;                   /* totals for (layout, t_ratio, t_bits) */
     void *pinned; size_t pinned_bytes;
     int span_override;
+    int seg_override;      /* wavefronts per workgroup of the streaming pass (0: by span size) */
+    int group_override;    /* lanes per staging segment in the candidate kernels (0: by ratio) */
     int force_dense;
     int nt_mode;
     int nt_dense;          /* non-temporal stores for the dense output of decompress */
@@ -1443,7 +1533,7 @@ Tables tables_of(const nsml_ctx *c)
     t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.fast = c->d_fast;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
     t.kw = c->d_kw; t.pmask = nullptr; t.margin = c->d_margin;
-    t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.chunk = c->chunk;
+    t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk;
     return t;
 }
 
@@ -1451,7 +1541,8 @@ Cand cand_of(const nsml_ctx *c)
 {
     Cand k;
     k.idx = c->d_cidx; k.val = c->d_cval; k.cnt = c->d_ccnt; k.G = c->d_cG; k.E = c->d_cE;
-    k.cap = c->spanT * 256u;
+    k.cap = (c->spanT * (TILE / 4)) >> c->segSh;
+    k.splitSh = 0;
     return k;
 }
 
@@ -1475,15 +1566,16 @@ int prof_end(nsml_ctx *c, int kid, hipStream_t st)
     return NSML_OK;
 }
 
-#define LAUNCH(ctx, kid, st, kernel, grid, ...)                                     \
+#define LAUNCHB(ctx, kid, st, kernel, grid, block, ...)                             \
     do {                                                                            \
         int rc_ = prof_begin(ctx, kid, st);                                         \
         if (rc_) return rc_;                                                        \
-        hipLaunchKernelGGL(kernel, dim3(grid), dim3(WG), 0, st, __VA_ARGS__);       \
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, st, __VA_ARGS__);    \
         NSML_HIP(ctx, hipGetLastError());                                           \
         rc_ = prof_end(ctx, kid, st);                                               \
         if (rc_) return rc_;                                                        \
     } while (0)
+#define LAUNCH(ctx, kid, st, kernel, grid, ...) LAUNCHB(ctx, kid, st, kernel, grid, WG, __VA_ARGS__)
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -1498,6 +1590,19 @@ uint32_t pick_span_tiles(uint32_t n_tiles, int override_)
     if (n_tiles >= 4u * 1024u) return 4;
     if (n_tiles >= 2u * 512u) return 2;
     return 1;
+}
+
+/* log2 of the wavefronts per workgroup of the streaming pass (= staging segments per span):
+ * one wavefront per tile for spans of 8 and 16 tiles, four wavefronts otherwise.  Every
+ * wavefront gets at least one wave-tile. */
+uint32_t pick_seg_shift(uint32_t spanT, int override_)
+{
+    uint32_t w = override_ > 0 ? (uint32_t)override_ : (spanT > 4 ? spanT : 4u);
+    const uint32_t hi = spanT * 4u < MAX_SEG_WAVES ? spanT * 4u : MAX_SEG_WAVES;
+    if (w > hi) w = hi;
+    uint32_t sh = 2;
+    while ((2u << sh) <= w) ++sh;
+    return sh;
 }
 
 /* Validate a bucket layout; (re)build the layout tables if it differs from the cached one. */
@@ -1569,6 +1674,7 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
     c->h_off.assign(off, off + B + 1);
     c->B = B; c->n = n;
     c->n_tiles = (uint32_t)nt; c->n_spans = (uint32_t)ns; c->n_samp = (uint32_t)nsamp; c->spanT = spanT;
+    c->segSh = pick_seg_shift(spanT, c->seg_override);
     return NSML_OK;
 }
 
@@ -1614,6 +1720,11 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_nofast = nullptr;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
+    const char *sw = getenv("NSML_SEG_WAVES");
+    c->seg_override = sw ? atoi(sw) : 0;
+    c->segSh = 2;
+    const char *go = getenv("NSML_GROUP");
+    c->group_override = go ? atoi(go) : 0;
     const char *fd = getenv("NSML_FORCE_DENSE");
     c->force_dense = (fd && atoi(fd) != 0) ? 1 : 0;
     const char *ntm = getenv("NSML_NT");
@@ -1654,7 +1765,9 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_span_b, mt));
     A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
     A(dev_alloc(c, &c->d_tG, mt)); A(dev_alloc(c, &c->d_tE, mt));
-    A(dev_alloc(c, &c->d_ccnt, 4 * mt)); A(dev_alloc(c, &c->d_cG, 4 * mt)); A(dev_alloc(c, &c->d_cE, 4 * mt));
+    /* segments: at most 4 per tile-sized span, or one per tile plus a partly filled span per bucket */
+    const uint64_t msg = 4 * mt + (uint64_t)MAX_SEG_WAVES * B1;
+    A(dev_alloc(c, &c->d_ccnt, msg)); A(dev_alloc(c, &c->d_cG, msg)); A(dev_alloc(c, &c->d_cE, msg));
     A(dev_alloc(c, &c->d_cidx, c->max_cand)); A(dev_alloc(c, &c->d_cval, c->max_cand));
     A(dev_alloc(c, &c->d_v, max_n));
     A(dev_alloc(c, &c->d_ts, mt + B1 + 1));
@@ -1713,13 +1826,13 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     if (rc) return rc;
 
     Tables t = tables_of(c);
-    const Cand cd = cand_of(c);
+    const Cand cd0 = cand_of(c);
     const Hists h = hists_of(c, B);
     const uint64_t zw = zero_words(B);
     const uint32_t clear_grid = (uint32_t)((zw + WG * 8 - 1) / (WG * 8));
     float *vdst = bits == 32 ? static_cast<float *>(val) : c->d_v;
-    const uint32_t n_ss = c->n_spans * 4;
-    const uint32_t cgrid = (n_ss + 3) / 4 < SIDE_GRID ? (n_ss + 3) / 4 : SIDE_GRID;
+    const uint32_t n_ss = c->n_spans << c->segSh;
+    const uint32_t eblock = 64u << c->segSh;
     const uint32_t fgrid = c->n_spans < SIDE_GRID ? c->n_spans : SIDE_GRID;
 
     if (weights) {
@@ -1731,12 +1844,12 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
         LAUNCH(c, KID_WHIST, st, k_whist, c->n_spans, weights, tw, h.h0);
         LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0);
-        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, weights, tw, cd, h.c1, h.f1, 0u);
+        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, weights, tw, cd0, h.c1, h.f1, 0u);
         LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
-        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, weights, tw, cd, h.c2, h.f2, 0u);
+        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, weights, tw, cd0, h.c2, h.f2, 0u);
         LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, 0);
-        LAUNCH(c, KID_COUNT, st, k_count<64>, fgrid, weights, tw, cd, c->d_tG, c->d_tE, 0u);
-        LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cd.G, cd.E, c->d_tG, c->d_tE);
+        LAUNCH(c, KID_COUNT, st, k_count<64>, fgrid, weights, tw, cd0, c->d_tG, c->d_tE, 0u);
+        LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cd0.G, cd0.E, c->d_tG, c->d_tE);
         LAUNCH(c, KID_WMASK, st, k_wmask, fgrid, weights, tw, (const uint32_t *)c->d_tG,
                (const uint32_t *)c->d_tE, c->d_pmask);
         t.pmask = c->d_pmask;
@@ -1757,28 +1870,38 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
     }
     if (c->force_dense) {
-        if (weights) LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, true>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
-        else LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
+        if (weights) LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, true>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq);
+        else LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq);
     } else if (weights) {
-        LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, true>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq);
+        LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, true>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq);
     } else {
         switch (c->nt_mode) {
-        case 1:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 1, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
-        case 3:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 3, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
-        case 5:  LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 5, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
-        default: LAUNCH(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, false>), c->n_spans, grad, residual, t, h.h0, cd, c->d_span_sq); break;
+        case 1:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 1, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
+        case 3:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 3, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
+        case 5:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 5, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
+        default: LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
         }
     }
-    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const uint32_t *)cd.cnt,
+    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const uint32_t *)cd0.cnt,
            c->force_dense ? 0 : 1, (const double *)c->d_span_sq, c->d_l2sq);
     LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
     /* every stage serves both kinds of bucket: candidate segments first, then the dense
      * spans of the buckets the candidates could not decide */
-    const uint32_t cg = c->force_dense ? 0u : cgrid;
     const float *acc = residual;
     /* lanes per candidate segment: a segment is expected to hold about 1.5 * ratio of the
      * elements it covers */
-    const bool narrow = 1.5 * ratio * (double)(c->spanT * WTILE) < 48.0;
+    const bool narrow = c->group_override ? c->group_override == 16
+                                          : 1.5 * ratio * (double)((c->spanT * TILE) >> c->segSh) < 48.0;
+    /* wavefronts of the candidate role: one per chunk of 64 segments, or several per chunk
+     * (each taking a share of its rounds) while that does not fill the grid */
+    Cand cd = cd0;
+    const uint32_t n_chunks = (n_ss + 63) / 64;
+    const uint32_t max_split = narrow ? 4u : 6u;          /* log2 of the rounds per chunk */
+    cd.splitSh = 0;
+    while (cd.splitSh < max_split && ((uint64_t)n_chunks << cd.splitSh) < 4ull * SIDE_GRID) ++cd.splitSh;
+    const uint64_t cwaves = (uint64_t)n_chunks << cd.splitSh;
+    const uint32_t cgrid = (uint32_t)((cwaves + 3) / 4 < SIDE_GRID ? (cwaves + 3) / 4 : SIDE_GRID);
+    const uint32_t cg = c->force_dense ? 0u : cgrid;
     if (narrow) {
         LAUNCH(c, KID_REFINE1, st, (k_refine<1, 16>), cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
     } else {

@@ -152,6 +152,28 @@ def test_bert_shaped_scaled(ratio, bits):
     c.step(ratio, bits)
 
 
+@pytest.mark.parametrize("span_tiles,seg_waves,group", [(1, 4, 16), (2, 8, 64), (4, 16, 16), (8, 8, 16),
+                                                        (16, 4, 64), (16, 8, 16), (16, 16, 16), (16, 16, 64)])
+def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
+    """The library picks tiles per workgroup, wavefronts per workgroup and lanes per staging
+    segment from the size of the gradient; the large-gradient shapes are forced here on a
+    gradient the oracle sorts in a second: ragged buckets, last spans with fewer tiles than
+    wavefronts, ties at the threshold, two error-feedback steps."""
+    monkeypatch.setenv("NSML_SPAN_TILES", str(span_tiles))
+    monkeypatch.setenv("NSML_SEG_WAVES", str(seg_waves))
+    monkeypatch.setenv("NSML_GROUP", str(group))
+    sizes = [200_003, 65_536 * 3 + 1, 4_099, 0, 333_333, 70_001]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    say("geometry", span_tiles, seg_waves, group, n)
+    g = _rand(n, 4242)
+    g[5_000:9_000] = torch.round(g[5_000:9_000] * 2e3) / 2e3          # plateaus of equal magnitudes
+    c = Case(g, off, chunk=512)
+    c.step(0.02, 8)
+    c.set_grad(_rand(n, 4243))
+    c.step(0.004, 4)
+
+
 def test_same_input_twice_gives_identical_bytes():
     """Determinism (the practical race detector): two runs, byte-identical outputs."""
     sizes = [300_000, 17, 200_003]
