@@ -651,7 +651,7 @@ __global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
  * time.  Lane l first fetches what describes segment 64 * chunk + l (bucket, entry count,
  * threshold): one round of look-ups for 64 segments.  Then the wavefront goes through them
  * 64 / GROUP at a time, GROUP lanes per segment, taking each description from the lane that
- * holds it.  GROUP is 16 when segments are short (low ratios), 64 otherwise.  Entries are
+ * holds it.  GROUP is 4 or 16 when segments are short (low ratios), 64 otherwise.  Entries are
  * fetched four per lane before any is used, so a segment costs about one memory round trip.
  * When there are fewer chunks than wavefronts, 2^splitSh wavefronts share a chunk and take
  * every 2^splitSh-th round of it. */
@@ -1889,44 +1889,43 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
      * spans of the buckets the candidates could not decide */
     const float *acc = residual;
     /* lanes per candidate segment: a segment is expected to hold about 1.5 * ratio of the
-     * elements it covers */
-    const bool narrow = c->group_override ? c->group_override == 16
-                                          : 1.5 * ratio * (double)((c->spanT * TILE) >> c->segSh) < 48.0;
+     * elements it covers, and a group of lanes fetches 4 entries per lane at a time */
+    const double per_seg = 1.5 * ratio * (double)((c->spanT * TILE) >> c->segSh);
+    uint32_t group = per_seg < 7.0 ? 4u : per_seg < 48.0 ? 16u : 64u;
+    if (c->group_override == 4 || c->group_override == 16 || c->group_override == 64) group = (uint32_t)c->group_override;
     /* wavefronts of the candidate role: one per chunk of 64 segments, or several per chunk
      * (each taking a share of its rounds) while that does not fill the grid */
     Cand cd = cd0;
     const uint32_t n_chunks = (n_ss + 63) / 64;
-    const uint32_t max_split = narrow ? 4u : 6u;          /* log2 of the rounds per chunk */
+    const uint32_t max_split = group == 4 ? 2u : group == 16 ? 4u : 6u;   /* log2 of the rounds per chunk */
     cd.splitSh = 0;
     while (cd.splitSh < max_split && ((uint64_t)n_chunks << cd.splitSh) < 4ull * SIDE_GRID) ++cd.splitSh;
     const uint64_t cwaves = (uint64_t)n_chunks << cd.splitSh;
     const uint32_t cgrid = (uint32_t)((cwaves + 3) / 4 < SIDE_GRID ? (cwaves + 3) / 4 : SIDE_GRID);
     const uint32_t cg = c->force_dense ? 0u : cgrid;
-    if (narrow) {
-        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 16>), cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
-    } else {
-        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cg + fgrid, acc, t, cd, h.c1, h.f1, cg);
-    }
+#define NSML_BY_GROUP(kid, K, ...)                                                          \
+    do {                                                                                    \
+        if (group == 4) LAUNCH(c, kid, st, (K(4)), cg + fgrid, __VA_ARGS__);                \
+        else if (group == 16) LAUNCH(c, kid, st, (K(16)), cg + fgrid, __VA_ARGS__);         \
+        else LAUNCH(c, kid, st, (K(64)), cg + fgrid, __VA_ARGS__);                          \
+    } while (0)
+#define NSML_K_REFINE1(G) k_refine<1, G>
+#define NSML_K_REFINE2(G) k_refine<2, G>
+#define NSML_K_COUNT(G) k_count<G>
+#define NSML_K_WRITE(G) k_write<G>
+    NSML_BY_GROUP(KID_REFINE1, NSML_K_REFINE1, acc, t, cd, h.c1, h.f1, cg);
     LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
-    if (narrow) {
-        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 16>), cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
-    } else {
-        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cg + fgrid, acc, t, cd, h.c2, h.f2, cg);
-    }
+    NSML_BY_GROUP(KID_REFINE2, NSML_K_REFINE2, acc, t, cd, h.c2, h.f2, cg);
     LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, write_next);
-    if (narrow) {
-        LAUNCH(c, KID_COUNT, st, k_count<16>, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
-    } else {
-        LAUNCH(c, KID_COUNT, st, k_count<64>, cg + fgrid, acc, t, cd, c->d_tG, c->d_tE, cg);
-    }
+    NSML_BY_GROUP(KID_COUNT, NSML_K_COUNT, acc, t, cd, c->d_tG, c->d_tE, cg);
     LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE);
-    if (narrow) {
-        LAUNCH(c, KID_WRITE, st, k_write<16>, cg + fgrid, acc, t, cd, (const uint32_t *)c->d_tG,
-               (const uint32_t *)c->d_tE, idx, vdst, cg);
-    } else {
-        LAUNCH(c, KID_WRITE, st, k_write<64>, cg + fgrid, acc, t, cd, (const uint32_t *)c->d_tG,
-               (const uint32_t *)c->d_tE, idx, vdst, cg);
-    }
+    NSML_BY_GROUP(KID_WRITE, NSML_K_WRITE, acc, t, cd, (const uint32_t *)c->d_tG, (const uint32_t *)c->d_tE,
+                  idx, vdst, cg);
+#undef NSML_BY_GROUP
+#undef NSML_K_REFINE1
+#undef NSML_K_REFINE2
+#undef NSML_K_COUNT
+#undef NSML_K_WRITE
     const uint32_t qgrid = (uint32_t)c->NC;
     switch (bits) {
     case 32: LAUNCH(c, KID_QUANT, st, k_quant<32>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;

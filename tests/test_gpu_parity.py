@@ -153,7 +153,7 @@ def test_bert_shaped_scaled(ratio, bits):
 
 
 @pytest.mark.parametrize("span_tiles,seg_waves,group", [(1, 4, 16), (2, 8, 64), (4, 16, 16), (8, 8, 16),
-                                                        (16, 4, 64), (16, 8, 16), (16, 16, 16), (16, 16, 64)])
+                                                        (16, 4, 64), (16, 8, 16), (16, 16, 16), (16, 16, 64), (16, 16, 4), (2, 4, 4)])
 def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
     """The library picks tiles per workgroup, wavefronts per workgroup and lanes per staging
     segment from the size of the gradient; the large-gradient shapes are forced here on a
