@@ -16,21 +16,24 @@
  *   ef_emit   acc = grad + residual (written over residual), exact level-0 histogram, and
  *             every element with key >= L_b appended, in index order, to a per-wavefront
  *             staging segment ("candidates")                                  12 B/element
- *   plan      per bucket: exact level-0 digit b0 of the k-th key; the candidates are a
- *             superset of the top k iff digit(L_b) <= b0 and no staging segment overflowed
- *   crefine1/2, pick1/2   remaining digits from the candidates only -> threshold key T_b and
+ *   plan      per bucket: exact level-0 digit b0 of the k-th key; the candidates (exactly
+ *             the elements with key >= L_b) decide the bucket iff there are at least k of
+ *             them and no staging segment overflowed
+ *   refine1/2, pick1/2   remaining digits from the candidates only -> threshold key T_b and
  *             e_b = how many elements equal to T_b are admitted (lowest indices first)
- *   ccount, cscan, cwrite  survivors to their final, index-ordered slots
- *   fb_*      buckets whose candidates are not a superset (huge groups of equal keys, ratio
- *             near 1, an unlucky sample) take the same steps over the dense accumulator
- *             instead: four more reads of that bucket only.  Results are identical.
+ *   count, scan, write   survivors to their final, index-ordered slots
+ *   fallback  buckets whose candidates cannot decide (huge groups of equal keys, ratio near
+ *             1, an unlucky sample) take the same steps over the dense accumulator instead,
+ *             in the last workgroups of the same launches: four more reads of that bucket
+ *             only.  Results are identical.
  *   quant     per chunk of survivors: absmax scale, codes, packing, residual update
- *   decomp    payload -> dense, each output line written once, tile staged in LDS
+ *   tilestart, decomp    payload -> dense, each output line written once, tile staged in LDS
  *
  * Geometry: a bucket [lo, hi) is cut into tiles of 4096 elements starting at lo rounded down
  * to a multiple of 4, so every 16-byte access is aligned; elements of an edge tile outside
- * [lo, hi) are masked.  A workgroup (256 threads = 4 wavefronts) owns a span of up to 16
- * consecutive tiles of one bucket.
+ * [lo, hi) are masked.  A workgroup owns a span of up to 16 consecutive tiles of one bucket.
+ * Workgroups have 256 threads, except in the streaming pass, which runs one wavefront per
+ * tile (512 or 1024 threads) on spans of 8 and 16 tiles.
  */
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
