@@ -215,11 +215,13 @@ def main():
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     kernels = {k: {"launches": c, "avg_ms": round(ms / c, 5)} for k, (c, ms) in prof.items()}
+    cand_buckets, dense_buckets = ctx.path_stats()      # of the last step, outside the timed region
     ef = prof.get("ef_emit")
     ef_ms = ef[1] / ef[0]
     achieved = EF_HIST_BYTES_PER_ELEM * n / (ef_ms * 1e-3) / 1e9
 
     traffic = None
+    step_traffic = None
     # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, calibrated on a
     # plain copy); the figure is kept in the committed profile summary of this workload
     tpath = os.path.join(ROOT, "profiles", f"ef_emit_{args.workload}.txt")
@@ -227,6 +229,8 @@ def main():
         import re
         m = re.search(r"hbm_bytes_per_launch:\s*([0-9.eE+]+)", open(tpath).read())
         traffic = float(m.group(1)) if m else None
+        m = re.search(r"hbm_bytes_per_step:\s*([0-9.eE+]+)", open(tpath).read())
+        step_traffic = float(m.group(1)) if m else None
 
     value = 4.0 * n / (ms_per_step * 1e-3) / 1e9
     floor_bytes = 16.0 * n + 2.0 * payload
@@ -241,10 +245,13 @@ def main():
                    "weight_pruning": bool(args.prune), "hip_graph": bool(args.graph)},
         "hbm_roofline_frac": round(floor_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "floor_bytes_per_step": floor_bytes,
+        "measured_hbm_bytes_per_step": step_traffic,
+        "measured_hbm_gbs": round(step_traffic / (ms_per_step * 1e-3) / 1e9, 1) if step_traffic else None,
         "roofline": {"kernel": "ef_emit", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "avg_ms": round(ef_ms, 5),
                      "algorithmic_bytes_per_launch": EF_HIST_BYTES_PER_ELEM * n},
+        "selection_paths": {"candidate_buckets": cand_buckets, "dense_fallback_buckets": dense_buckets},
         "kernels": kernels,
         "ms_per_step_profiled": round(wall_prof / args.steps * 1e3, 4),
     }
