@@ -96,7 +96,11 @@ struct Tables {
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
     uint32_t *margin;        /* B   history mode: how far below the last threshold key L is placed */
     uint32_t *kw;            /* B   parameters the pruning step keeps (only with weights) */
-    const uint32_t *pmask;   /* pruning bitmap, 128 words per tile, bit = pruned; NULL: no pruning */
+    const float *w;          /* weights when Algorithm 2 Step 2 is on, else NULL */
+    const uint32_t *wT;      /* B   with weights: threshold key of |w|; NONE: the bucket's mask is in the bitmap */
+    const uint32_t *wcut;    /* B   with weights: among parameters with key(w) == wT, those up to this
+                              *     bucket-local index are kept (kept: key > wT, or key == wT and index <= wcut) */
+    const uint32_t *pmask;   /* pruning bitmap, 128 words per tile, bit = pruned (buckets with wT = NONE) */
     uint32_t B;
     uint32_t n_spans;
     uint32_t spanT;          /* tiles per span */
@@ -184,6 +188,25 @@ __device__ __forceinline__ uint32_t load_quad(const float *__restrict__ p, uint6
         if (gi + j >= lo && gi + j < hi) { x[j] = p[gi + j]; m |= 1u << j; }
     }
     return m;
+}
+
+/* The four pruning bits (1 = pruned) of the quad at aligned element index gi, which is quad
+ * `quad` of tile `tile_abs`, in a bucket [lo, hi) whose weight threshold is wT and whose last
+ * kept index among the weights equal to the threshold is cut. */
+__device__ __forceinline__ uint32_t pruned_quad(const Tables &t, uint32_t wT, uint32_t cut, uint32_t tile_abs,
+                                                uint32_t quad, uint64_t gi, uint64_t lo, uint64_t hi)
+{
+    if (wT == 0xFFFFFFFFu) return pruned_bits(t.pmask, tile_abs, quad);
+    float x[4];
+    load_quad(t.w, gi, lo, hi, x);
+    const uint32_t li = (uint32_t)(gi - lo);        /* meaningless below lo: those lanes are masked anyway */
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t key = __float_as_uint(x[j]) & 0x7FFFFFFFu;
+        bits |= ((key < wT || (key == wT && li + j > cut)) ? 1u : 0u) << j;
+    }
+    return bits;
 }
 
 /* ------------------------------------------------------------------ setup / clear */
@@ -362,6 +385,7 @@ struct DigitWalk {
 
 /* Level-0 histogram of a sample of acc = grad + residual: runs of 32 consecutive elements,
  * every run of a small bucket, one run in 64 of a large one. */
+template <bool SUM>   /* SUM: keys of g + r; else keys of g alone (the weight stage) */
 __global__ __launch_bounds__(WG) void k_sample(const float *__restrict__ g, const float *__restrict__ r,
                                                Tables t, uint32_t *__restrict__ hist_s)
 {
@@ -383,14 +407,15 @@ __global__ __launch_bounds__(WG) void k_sample(const float *__restrict__ g, cons
             const uint64_t gi = a0 + run * run_elems + (tid & 7u) * 4;
             float x[4], y[4];
             uint32_t m = load_quad(g, gi, lo, hi, x);
-            load_quad(r, gi, lo, hi, y);
-            if (t.pmask) {
+            if (SUM) load_quad(r, gi, lo, hi, y);
+            if (SUM && t.w) {
                 const uint64_t rel = gi - a0;
-                m &= ~pruned_bits(t.pmask, t.tile0[b] + (uint32_t)(rel / TILE), (uint32_t)(rel % TILE) / 4);
+                m &= ~pruned_quad(t, t.wT[b], t.wcut[b], t.tile0[b] + (uint32_t)(rel / TILE),
+                                  (uint32_t)(rel % TILE) / 4, gi, lo, hi);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if ((m >> j) & 1u) atomicAdd(&h[keyof(__fadd_rn(x[j], y[j])) >> SH0], 1u);
+                if ((m >> j) & 1u) atomicAdd(&h[keyof(SUM ? __fadd_rn(x[j], y[j]) : x[j]) >> SH0], 1u);
         }
     }
     __syncthreads();
@@ -418,7 +443,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
     const bool exact = nb < SAMPLE_ALL_BELOW;
     /* the sample was drawn from the parameters that can be selected: all of them, or the
      * ones the pruning step kept */
-    const double pop = t.pmask ? (double)t.kw[b] : (double)nb;
+    const double pop = t.w ? (double)t.kw[b] : (double)nb;
     const double ks = (double)k * (double)m / pop;
     const double want_d = exact ? (double)k : ceil(ks + 4.0 * sqrt(ks) + 4.0);
     const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
@@ -435,6 +460,33 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
 }
 
 /* ------------------------------------------------------------------ the streaming pass */
+
+/* Append the flagged elements of a row (64 lanes x 4 consecutive elements) to the wavefront's
+ * staging segment, in index order: ranks come from ballots, nothing crosses wavefronts.  Every
+ * lane of the wavefront must call this. */
+__device__ __forceinline__ void emit_quad(const bool (&f)[4], const float (&a)[4], uint32_t li, const Cand &c,
+                                          uint64_t cbase, uint32_t &wcount, uint64_t lt)
+{
+    if (__ballot(f[0] | f[1] | f[2] | f[3]) == 0ull) return;
+    uint64_t bal[4];
+    uint32_t pos = wcount;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        bal[j] = __ballot(f[j]);
+        /* flagged entries in lower lanes */
+        pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal[j] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal[j], pos));
+    }
+    (void)lt;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (f[j]) {
+            if (pos < c.cap) { c.idx[cbase + pos] = li + j; c.val[cbase + pos] = a[j]; }
+            ++pos;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wcount += __popcll(bal[j]);
+}
 
 /* One row of the streaming pass: 64 lanes x 4 consecutive elements (one contiguous 1 KiB).
  * a[] is the accumulator quad of this lane, m its validity mask, li the bucket-local index
@@ -469,21 +521,7 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
         bool f[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) f[j] = ((cm >> j) & 1u) && key[j] >= L;
-        if (__ballot(f[0] | f[1] | f[2] | f[3]) != 0ull) {
-            uint64_t bal[4];
-            uint32_t pos = wcount;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { bal[j] = __ballot(f[j]); pos += __popcll(bal[j] & lt); }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (f[j]) {
-                    if (pos < c.cap) { c.idx[cbase + pos] = li + j; c.val[cbase + pos] = a[j]; }
-                    ++pos;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) wcount += __popcll(bal[j]);
-        }
+        emit_quad(f, a, li, c, cbase, wcount, lt);
     }
 }
 
@@ -507,6 +545,8 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     for (uint32_t i = tid; i < NB0; i += nthreads) h[i] = 0;
     const SpanGeo s = span_geo(t, blockIdx.x);
     const uint32_t L = EMIT ? t.L[s.b] : NONE;
+    const uint32_t wT = PRUNE ? t.wT[s.b] : 0u;          /* NONE: this bucket's mask is in the bitmap */
+    const uint32_t wcut = PRUNE ? t.wcut[s.b] : 0u;
     const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t ss = (blockIdx.x << t.segSh) + wave;
     const uint64_t cbase = (uint64_t)ss * c.cap;
@@ -519,7 +559,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     for (uint32_t wt = wt0; wt < wt1; ++wt) {
         const uint64_t wb = s.base + (uint64_t)wt * WTILE;
         if (wb >= s.lo && wb + WTILE <= s.hi) {
-            f4 gv[4], rv[4];
+            f4 gv[4], rv[4], wv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
@@ -527,6 +567,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
                                  : *reinterpret_cast<const f4 *>(g + gi);
                 rv[u] = (NT & 2) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r + gi))
                                  : *reinterpret_cast<const f4 *>(r + gi);
+                if (PRUNE && wT != NONE) wv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(t.w + gi));
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -537,7 +578,17 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
                 sq += (double)(__fmaf_rn(gv[u].x, gv[u].x, __fmul_rn(gv[u].y, gv[u].y)) +
                                __fmaf_rn(gv[u].z, gv[u].z, __fmul_rn(gv[u].w, gv[u].w)));
                 uint32_t cm = 0xFu;
-                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
+                if (PRUNE) {
+                    if (wT != NONE) {
+                        const uint32_t li = (uint32_t)(gi - s.lo);
+                        const uint32_t kx = keyof(wv[u].x), ky = keyof(wv[u].y), kz = keyof(wv[u].z), kq = keyof(wv[u].w);
+                        cm = ((kx > wT || (kx == wT && li <= wcut)) ? 1u : 0u) |
+                             ((ky > wT || (ky == wT && li + 1 <= wcut)) ? 2u : 0u) |
+                             ((kz > wT || (kz == wT && li + 2 <= wcut)) ? 4u : 0u) |
+                             ((kq > wT || (kq == wT && li + 3 <= wcut)) ? 8u : 0u);
+                    } else
+                        cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
+                }
                 ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         } else {
@@ -550,7 +601,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
 #pragma unroll
                 for (int j = 0; j < 4; ++j) { a[j] = __fadd_rn(x[j], y[j]); sq += (double)__fmul_rn(x[j], x[j]); }
                 uint32_t cm = m;
-                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
+                if (PRUNE) cm &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
                 ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
             }
         }
@@ -724,20 +775,91 @@ __device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uin
     }
 }
 
+/* The same histogram when a large share of the staged elements carries the prefix (the weight
+ * stage: a whole level-0 digit of the weights): a workgroup walks a contiguous range of
+ * chunks, which almost always lies inside one bucket, counts in LDS and adds its histogram to
+ * the bucket's once.  Groups of chunks that straddle two buckets count straight into global
+ * memory.  h: NB words of LDS. */
+template <int LEVEL, uint32_t GROUP>
+__device__ __forceinline__ void crefine_agg_body(const Tables &t, const Cand &c, uint32_t *__restrict__ hist,
+                                                 uint32_t *h, uint32_t bid, uint32_t nblk)
+{
+    constexpr int NB = LEVEL == 1 ? NB1 : NB2;
+    constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
+    constexpr int DSH = LEVEL == 1 ? SH1 : 0;
+    constexpr uint32_t SPR = 64 / GROUP;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sub = lane / GROUP, gl = lane % GROUP;
+    const uint32_t n_segs = t.n_spans << t.segSh;
+    const uint32_t n_chunks = seg_chunks(t);
+    const uint32_t per = (n_chunks + nblk - 1) / nblk;
+    const uint32_t start = min(n_chunks, bid * per), end = min(n_chunks, start + per);
+    for (int i = tid; i < NB; i += WG) h[i] = 0;
+    __syncthreads();
+    uint32_t cur_b = NONE;               /* bucket whose counts sit in LDS (same in every thread) */
+    for (uint32_t g0 = start; g0 < end; g0 += 4) {
+        /* the segments of this group of up to four chunks: one bucket or several? */
+        const uint32_t seg_a = g0 * 64, seg_z = min(n_segs, min(end, g0 + 4) * 64) - 1u;
+        const uint32_t b_a = t.span_b[seg_a >> t.segSh], b_z = t.span_b[seg_z >> t.segSh];
+        const bool one = b_a == b_z;
+        if (one && b_a != cur_b) {
+            __syncthreads();
+            if (cur_b != NONE) hist_flush(h, hist + (uint64_t)cur_b * NB, NB);
+            __syncthreads();
+            for (int i = tid; i < NB; i += WG) h[i] = 0;
+            __syncthreads();
+            cur_b = b_a;
+        }
+        const uint32_t chunk = g0 + wave;
+        if (chunk >= end) continue;
+        const SegMeta m = seg_meta(t, c, chunk);
+        if (__ballot(m.cnt != 0u) == 0ull) continue;
+        for (uint32_t rd = 0; rd < GROUP; ++rd) {
+            const uint32_t src = rd * SPR + sub;
+            const uint32_t cnt = __shfl(m.cnt, src, 64);
+            if (__ballot(cnt != 0u) == 0ull) continue;
+            const uint32_t prefix = __shfl(m.T, src, 64), b = __shfl(m.b, src, 64);
+            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
+            for (uint32_t i0 = gl; i0 < cnt; i0 += CU * GROUP) {
+                float x[CU];
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t i = i0 + u * GROUP;
+                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t key = keyof(x[u]);
+                    if (i0 + u * GROUP < cnt && (key >> PSH) == prefix) {
+                        const uint32_t d = (key >> DSH) & (NB - 1);
+                        if (one) atomicAdd(&h[d], 1u);
+                        else atomicAdd(&hist[(uint64_t)b * NB + d], 1u);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (cur_b != NONE) hist_flush(h, hist + (uint64_t)cur_b * NB, NB);
+}
+
 /* Per bucket, levels 1 and 2: walk the level's histogram (the candidates' one or the dense
  * fallback's, whichever path the bucket is on) to the digit holding the need-th entry and
  * append it to the prefix. */
 template <int LEVEL>
 __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
                                              const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
-                                             int write_next)
+                                             int write_next, uint32_t *__restrict__ wT_out = nullptr)
 {
     constexpr int NB = LEVEL == 2 ? NB2 : NB1;
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const uint32_t want = t.need[b];
-    if (want == 0) return;
+    if (want == 0) {
+        /* empty bucket */
+        if (LEVEL == 2 && wT_out && tid == 0) wT_out[b] = 0u;
+        return;
+    }
     const uint32_t *hist = t.fast[b] ? hist_c : hist_f;
     DigitWalk<NB> w;
     w.load(hist + (uint64_t)b * NB, tmp);
@@ -750,6 +872,10 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
         const uint32_t T = (t.T[b] << BITS) | digit;
         t.T[b] = T;
         t.need[b] = want - above;
+        /* weight stage: buckets decided from the candidates hand the gradient kernels the
+         * threshold itself (and, next, the last kept index among equal weights); the others a
+         * bitmap */
+        if (LEVEL == 2 && wT_out) wT_out[b] = t.fast[b] ? T : NONE;
         if (LEVEL == 2 && write_next) {
             /* history mode: next call's candidate bound sits a margin below this threshold */
             const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
@@ -856,7 +982,8 @@ __global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG
 
 /* Per segment: copy the admitted candidates (key > T, or key == T and among the first e_b
  * equal ones of the bucket in index order) to their final slots. */
-template <uint32_t GROUP>
+template <uint32_t GROUP, bool CUT = false>   /* CUT (weight stage): only record, per bucket in idx_out[b],
+                                               * the index of the last admitted entry equal to the threshold */
 __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint32_t *__restrict__ idx_out,
                                             float *__restrict__ v_out, uint32_t bid, uint32_t nblk)
 {
@@ -886,6 +1013,7 @@ __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint
             uint32_t run_g = __shfl(m_g, src, 64), run_e = __shfl(m_e, src, 64);
             const uint64_t Pb = ((uint64_t)__shfl((uint32_t)(m_P >> 32), src, 64) << 32) |
                                 (uint64_t)__shfl((uint32_t)m_P, src, 64);
+            const uint32_t bkt = __shfl(m.b, src, 64);
             const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
             for (uint32_t i0 = 0; i0 < maxcnt; i0 += CU * GROUP) {
                 float x[CU];
@@ -904,7 +1032,9 @@ __device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint
                     const uint64_t bg = (__ballot(isg) >> shift) & gmask;
                     const uint64_t be = (__ballot(ise) >> shift) & gmask;
                     const uint32_t pg = run_g + __popcll(bg & below), pe = run_e + __popcll(be & below);
-                    if (isg || (ise && pe < e_b)) {
+                    if (CUT) {
+                        if (ise && pe + 1u == e_b) idx_out[bkt] = li[u];
+                    } else if (isg || (ise && pe < e_b)) {
                         const uint64_t pos = Pb + pg + min(e_b, pe);
                         idx_out[pos] = li[u];
                         v_out[pos] = x[u];
@@ -945,7 +1075,7 @@ __device__ __forceinline__ void fb_refine_body(const float *__restrict__ r, cons
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
                 float x[4];
                 uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-                if (t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
+                if (t.w) m &= ~pruned_quad(t, t.wT[b], t.wcut[b], s.tile_g + ti, u * WG + tid, gi, s.lo, s.hi);
                 uint32_t d[4];
                 uint32_t hit = 0;
 #pragma unroll
@@ -995,7 +1125,7 @@ __device__ __forceinline__ void fb_count_body(const float *__restrict__ r, const
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
                 float x[4];
                 uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-                if (t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
+                if (t.w) m &= ~pruned_quad(t, t.wT[b], t.wcut[b], s.tile_g + ti, u * WG + tid, gi, s.lo, s.hi);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t key = keyof(x[j]);
@@ -1045,7 +1175,7 @@ __device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
                 uint32_t m = load_quad(r, gi, s.lo, s.hi, x[u]);
-                if (!MASKOUT && t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
+                if (!MASKOUT && t.w) m &= ~pruned_quad(t, t.wT[b], t.wcut[b], s.tile_g + ti, u * WG + tid, gi, s.lo, s.hi);
                 fg[u] = fe[u] = 0;
                 if (MASKOUT) {
                     vm[u] = m;
@@ -1112,14 +1242,16 @@ __device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const
 /* Each selection stage is one launch: the first cgrid workgroups walk the candidate segments,
  * the others walk the dense spans of the fallback buckets (usually none: they read the empty
  * list and leave). */
-template <int LEVEL, uint32_t GROUP>
+template <int LEVEL, uint32_t GROUP, bool AGG = false>
 __global__ __launch_bounds__(WG) void k_refine(const float *__restrict__ r, Tables t, Cand c,
                                                uint32_t *__restrict__ hist_c, uint32_t *__restrict__ hist_f,
                                                uint32_t cgrid)
 {
     __shared__ uint32_t h[LEVEL == 1 ? NB1 : NB2];
-    if (blockIdx.x < cgrid) crefine_body<LEVEL, GROUP>(t, c, hist_c, blockIdx.x, cgrid);
-    else fb_refine_body<LEVEL>(r, t, hist_f, h, blockIdx.x - cgrid, gridDim.x - cgrid);
+    if (blockIdx.x < cgrid) {
+        if (AGG) crefine_agg_body<LEVEL, GROUP>(t, c, hist_c, h, blockIdx.x, cgrid);
+        else crefine_body<LEVEL, GROUP>(t, c, hist_c, blockIdx.x, cgrid);
+    } else fb_refine_body<LEVEL>(r, t, hist_f, h, blockIdx.x - cgrid, gridDim.x - cgrid);
 }
 
 template <uint32_t GROUP>
@@ -1147,61 +1279,168 @@ __global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Table
 /* ------------------------------------------------------------------ model pruning (optional) */
 
 /* Algorithm 2 Step 2 on the GPU: the kept parameters of a bucket are its n_b - floor(0.5 (1 -
- * ratio) n_b) largest |weight| (ties: lower index kept), found with the same dense radix
- * select as a fallback bucket; the result is a bitmap (1 = pruned) that the gradient kernels
- * consult so that pruned parameters are neither counted nor emitted.  Their accumulated
- * gradient is still written to the residual: pruning is not permanent. */
-__global__ __launch_bounds__(WG) void k_whist(const float *__restrict__ w, Tables t, uint32_t *__restrict__ hist0)
+ * ratio) n_b) largest |weight| (ties: lower index kept).  The kept set is more than half of
+ * the bucket, so "candidates above a bound" would be most of it; instead the threshold is
+ * bracketed: a sample of |w| gives a band of level-0 digits that holds the kw-th largest key
+ * with a wide margin, one pass over the weights builds the exact level-0 histogram and stages
+ * the elements inside the band, and the remaining digits, the threshold key T and the index
+ * of the last kept element among those equal to T come from the staged elements alone.  The
+ * gradient kernels then decide "kept" from the weight itself as they stream it (key > T, or
+ * key == T and index <= cut).  A bucket whose band missed or overflowed (a sample that was
+ * unlucky, a huge group of equal weights) takes the dense ordered passes instead, which leave
+ * a bitmap (1 = pruned).  Either way pruned parameters are neither counted nor emitted, and
+ * their accumulated gradient is still written to the residual: pruning is not permanent. */
+
+/* Per bucket: the band of keys [lo, hi) to stage, from the sample histogram of |w|. */
+__global__ __launch_bounds__(WG) void k_wpredict(Tables t, const uint32_t *__restrict__ hist_s,
+                                                 uint32_t *__restrict__ wLo, uint32_t *__restrict__ wHi,
+                                                 int force_dense)
+{
+    __shared__ uint32_t tmp[WG];
+    __shared__ uint32_t res[6];          /* digit, above, at for the upper and the lower rank */
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint64_t nb = t.off[b + 1] - t.off[b];
+    const uint32_t k = t.k[b];
+    if (nb == 0 || k == 0 || force_dense) {
+        if (tid == 0) { wLo[b] = NONE; wHi[b] = 0u; }
+        return;
+    }
+    DigitWalk<NB0> w;
+    w.load(hist_s + (uint64_t)b * NB0, tmp);
+    const uint32_t m = w.total;
+    if (m == 0) {
+        if (tid == 0) { wLo[b] = NONE; wHi[b] = 0u; }
+        return;
+    }
+    const bool exact = nb < SAMPLE_ALL_BELOW;
+    const double ks = (double)k * (double)m / (double)nb;      /* sample rank of the threshold, from the top */
+    const double dev = exact ? 0.0 : 4.0 * sqrt(ks) + 4.0;
+    double r_up = floor(ks - dev), r_dn = ceil(ks + dev);
+    if (r_up < 1.0) r_up = 1.0;
+    if (r_dn < 1.0) r_dn = 1.0;
+    if (r_dn > (double)m) r_dn = (double)m;
+    if (r_up > (double)m) r_up = (double)m;
+    uint32_t digit, above, at;
+    if (w.find((uint32_t)r_up, digit, above, at)) { res[0] = digit; res[1] = above; res[2] = at; }
+    if (w.find((uint32_t)r_dn, digit, above, at)) { res[3] = digit; res[4] = above; res[5] = at; }
+    __syncthreads();
+    if (tid == 0) {
+        /* sample entries inside the band -> expected staged elements */
+        const double in_band = (double)(res[4] + res[5]) - (double)res[1];
+        const double est = in_band * (double)nb / (double)m;
+        const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
+        /* a bucket sampled in full whose kept set is all of it needs no band either way */
+        if (est <= 0.8 * cap_b) { wLo[b] = res[3] << SH0; wHi[b] = (res[0] + 1u) << SH0; }
+        else { wLo[b] = NONE; wHi[b] = 0u; }
+    }
+}
+
+/* One pass over the weights: exact level-0 histogram of |w|, and every element whose key lies
+ * in the bucket's band appended, in index order, to its wavefront's staging segment.  Same
+ * geometry as the streaming pass of the gradient (64 << segSh threads, one contiguous share
+ * of the span per wavefront). */
+__global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_whist(const float *__restrict__ w, Tables t,
+                                                              uint32_t *__restrict__ hist0, Cand c,
+                                                              const uint32_t *__restrict__ wLo,
+                                                              const uint32_t *__restrict__ wHi)
 {
     __shared__ uint32_t h[NB0];
-    const uint32_t tid = threadIdx.x;
-    for (int i = tid; i < NB0; i += WG) h[i] = 0;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t nthreads = 64u << t.segSh;
+    for (uint32_t i = tid; i < NB0; i += nthreads) h[i] = 0;
     const SpanGeo s = span_geo(t, blockIdx.x);
+    const uint32_t lo_k = wLo[s.b], hi_k = wHi[s.b];       /* NONE, 0: nothing is staged */
+    const uint64_t lt = (1ull << lane) - 1ull;
+    const uint32_t ss = (blockIdx.x << t.segSh) + wave;
+    const uint64_t cbase = (uint64_t)ss * c.cap;
+    uint32_t wcount = 0;
     __syncthreads();
-    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-        const uint64_t tb = s.base + (uint64_t)ti * TILE;
-        const bool interior = tb >= s.lo && tb + TILE <= s.hi;
+    const uint32_t per = (t.spanT * 4u) >> t.segSh;
+    const uint32_t wt0 = wave * per;
+    const uint32_t wt1 = min(s.ntiles * 4u, wt0 + per);
+    for (uint32_t wt = wt0; wt < wt1; ++wt) {
+        const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+        if (wb >= s.lo && wb + WTILE <= s.hi) {
+            f4 wv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-            float x[4];
-            const uint32_t m = load_quad(w, gi, s.lo, s.hi, x);
-            if (interior) {
-                hist_quad_full(h, keyof(x[0]) >> SH0, keyof(x[1]) >> SH0, keyof(x[2]) >> SH0, keyof(x[3]) >> SH0);
-            } else {
+            for (int u = 0; u < 4; ++u)
+                wv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(w + wb + (uint64_t)(u * 64 + lane) * 4));
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if ((m >> j) & 1u) atomicAdd(&h[keyof(x[j]) >> SH0], 1u);
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                const float a[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+                uint32_t key[4];
+                bool f[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { key[j] = keyof(a[j]); f[j] = key[j] >= lo_k && key[j] < hi_k; }
+                hist_quad_full(h, key[0] >> SH0, key[1] >> SH0, key[2] >> SH0, key[3] >> SH0);
+                emit_quad(f, a, (uint32_t)(gi - s.lo), c, cbase, wcount, lt);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                float a[4];
+                const uint32_t m = load_quad(w, gi, s.lo, s.hi, a);
+                bool f[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = keyof(a[j]);
+                    const bool in = (m >> j) & 1u;
+                    if (in) atomicAdd(&h[key >> SH0], 1u);
+                    f[j] = in && key >= lo_k && key < hi_k;
+                }
+                emit_quad(f, a, (uint32_t)(gi - s.lo), c, cbase, wcount, lt);
             }
         }
     }
+    if (lane == 0) {
+        c.cnt[ss] = min(wcount, c.cap);
+        if (wcount > c.cap) t.ovf[s.b] = 1u;
+    }
     __syncthreads();
-    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0);
+    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0, (int)nthreads);
 }
 
-/* Per bucket: level-0 digit of the kw-th largest |weight|. */
-__global__ __launch_bounds__(WG) void k_wplan(Tables t, const uint32_t *__restrict__ hist0)
+/* Per bucket: level-0 digit of the kw-th largest |weight|, and whether the staged band can
+ * decide the rest: it holds every element of that digit iff the digit lies inside the band
+ * and no staging segment overflowed. */
+__global__ __launch_bounds__(WG) void k_wplan(Tables t, const uint32_t *__restrict__ hist0,
+                                              const uint32_t *__restrict__ wLo, const uint32_t *__restrict__ wHi)
 {
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const uint32_t want = t.k[b];
     if (want == 0) {
-        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; }
+        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; t.fast[b] = 1u; }
         return;
     }
     DigitWalk<NB0> w;
     w.load(hist0 + (uint64_t)b * NB0, tmp);
     uint32_t digit, above, at;
-    if (w.find(want, digit, above, at)) { t.T[b] = digit; t.need[b] = want - above; }
+    if (w.find(want, digit, above, at)) {
+        t.T[b] = digit;
+        t.need[b] = want - above;
+        const uint32_t lo_k = wLo[b], hi_k = wHi[b];
+        const bool valid = lo_k != NONE && (lo_k >> SH0) <= digit && digit < (hi_k >> SH0) && !t.ovf[b];
+        t.fast[b] = valid ? 1u : 0u;
+    }
 }
 
-__global__ __launch_bounds__(WG) void k_wmask(const float *__restrict__ w, Tables t,
-                                              const uint32_t *__restrict__ tG, const uint32_t *__restrict__ tE,
-                                              uint32_t *__restrict__ mask_out)
+/* Last stage of the weight select.  Candidate role: per bucket, the index of the last kept
+ * element among those equal to the threshold.  Fallback role: the bitmap of a bucket that
+ * went through the dense passes. */
+template <uint32_t GROUP>
+__global__ __launch_bounds__(WG) void k_wfinish(const float *__restrict__ w, Tables t, Cand c,
+                                                const uint32_t *__restrict__ tG, const uint32_t *__restrict__ tE,
+                                                uint32_t *__restrict__ wcut, uint32_t *__restrict__ mask_out,
+                                                uint32_t cgrid)
 {
     __shared__ uint32_t tot[16][2];
     __shared__ uint32_t bitmap[TILE / 32];
-    fb_write_body<true>(w, t, tG, tE, nullptr, nullptr, tot, bitmap, mask_out, blockIdx.x, gridDim.x);
+    if (blockIdx.x < cgrid) cwrite_body<GROUP, true>(t, c, wcut, nullptr, blockIdx.x, cgrid);
+    else fb_write_body<true>(w, t, tG, tE, nullptr, nullptr, tot, bitmap, mask_out, blockIdx.x - cgrid,
+                             gridDim.x - cgrid);
 }
 
 /* ------------------------------------------------------------------ value coding */
@@ -1450,7 +1689,9 @@ struct nsml_ctx {
     float *d_v;            /* survivor values in final order (not used for bits == 32) */
     uint32_t *d_ts;        /* decompress: where each tile's survivors start */
     uint32_t *d_pmask;     /* pruning bitmap, 128 words per tile */
-    uint32_t *d_kw, *d_Tw, *d_needw, *d_nofast;   /* pruning stage: kept counts, threshold, all-zero flags */
+    uint32_t *d_kw, *d_Tw, *d_needw;              /* pruning stage: kept counts, threshold search state */
+    uint32_t *d_wT, *d_wcut, *d_wfast;            /* pruning stage: threshold key and cut index per bucket; path taken */
+    uint32_t *d_wLo, *d_wHi;                      /* pruning stage: band of keys staged per bucket */
     double *d_span_sq;     /* per span: sum of grad^2 */
     double *d_l2sq;        /* per bucket: sum of grad^2 of the last compress call */
     bool have_l2;
@@ -1535,7 +1776,7 @@ Tables tables_of(const nsml_ctx *c)
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
     t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.fast = c->d_fast;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
-    t.kw = c->d_kw; t.pmask = nullptr; t.margin = c->d_margin;
+    t.kw = c->d_kw; t.w = nullptr; t.wT = nullptr; t.wcut = nullptr; t.pmask = nullptr; t.margin = c->d_margin;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk;
     return t;
 }
@@ -1720,7 +1961,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
-    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_nofast = nullptr;
+    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = nullptr;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
     const char *sw = getenv("NSML_SEG_WAVES");
@@ -1777,8 +2018,9 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
     A(dev_alloc(c, &c->d_pmask, mt * (TILE / 32)));
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
-    A(dev_alloc(c, &c->d_nofast, B1)); A(dev_alloc(c, &c->d_margin, B1));
-    if (rc == NSML_OK && hipMemset(c->d_nofast, 0, B1 * sizeof(uint32_t)) != hipSuccess) rc = NSML_EHIP;
+    A(dev_alloc(c, &c->d_margin, B1));
+    A(dev_alloc(c, &c->d_wT, B1)); A(dev_alloc(c, &c->d_wfast, B1)); A(dev_alloc(c, &c->d_wcut, B1));
+    A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1));
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
@@ -1798,7 +2040,8 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
-                    c->d_Tw, c->d_needw, c->d_nofast, c->d_margin};
+                    c->d_Tw, c->d_needw, c->d_margin, c->d_wT, c->d_wfast, c->d_wcut,
+                    c->d_wLo, c->d_wHi};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -1839,22 +2082,38 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     const uint32_t fgrid = c->n_spans < SIDE_GRID ? c->n_spans : SIDE_GRID;
 
     if (weights) {
-        /* Algorithm 2 Step 2: bitmap of the pruned parameters.  Every bucket takes the dense
-         * select (the kept set is more than half of the bucket), on its own set of tables. */
+        /* Algorithm 2 Step 2: threshold and cut of |w| per bucket (bitmap for the buckets that
+         * had to take the dense passes), on its own set of tables */
         Tables tw = t;
-        tw.k = c->d_kw; tw.T = c->d_Tw; tw.need = c->d_needw; tw.fast = c->d_nofast;
-        tw.fspan0 = c->d_span0;
+        tw.k = c->d_kw; tw.T = c->d_Tw; tw.need = c->d_needw; tw.fast = c->d_wfast;
+        Cand cdw = cd0;
+        const uint32_t n_chunks_w = (n_ss + 63) / 64;
+        while (cdw.splitSh < 6u && ((uint64_t)n_chunks_w << cdw.splitSh) < 4ull * SIDE_GRID) ++cdw.splitSh;
+        const uint64_t wwaves = (uint64_t)n_chunks_w << cdw.splitSh;
+        const uint32_t cgw = c->force_dense ? 0u : (uint32_t)((wwaves + 3) / 4 < SIDE_GRID ? (wwaves + 3) / 4 : SIDE_GRID);
         LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
-        LAUNCH(c, KID_WHIST, st, k_whist, c->n_spans, weights, tw, h.h0);
-        LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0);
-        LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, weights, tw, cd0, h.c1, h.f1, 0u);
+        if (!c->force_dense)
+            LAUNCH(c, KID_SAMPLE, st, k_sample<false>, c->n_samp, weights, (const float *)nullptr, tw, h.hs);
+        LAUNCH(c, KID_WPLAN, st, k_wpredict, B, tw, (const uint32_t *)h.hs, c->d_wLo, c->d_wHi, c->force_dense);
+        LAUNCHB(c, KID_WHIST, st, k_whist, c->n_spans, eblock, weights, tw, h.h0, cdw,
+                (const uint32_t *)c->d_wLo, (const uint32_t *)c->d_wHi);
+        LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0, (const uint32_t *)c->d_wLo,
+               (const uint32_t *)c->d_wHi);
+        LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, tw);
+        if (n_chunks_w >= 8u * SIDE_GRID)
+            LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
+        else
+            LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
         LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
-        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, weights, tw, cd0, h.c2, h.f2, 0u);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, 0);
-        LAUNCH(c, KID_COUNT, st, k_count<64>, fgrid, weights, tw, cd0, c->d_tG, c->d_tE, 0u);
-        LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cd0.G, cd0.E, c->d_tG, c->d_tE);
-        LAUNCH(c, KID_WMASK, st, k_wmask, fgrid, weights, tw, (const uint32_t *)c->d_tG,
-               (const uint32_t *)c->d_tE, c->d_pmask);
+        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cgw + fgrid, weights, tw, cdw, h.c2, h.f2, cgw);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, 0, c->d_wT);
+        LAUNCH(c, KID_COUNT, st, k_count<64>, cgw + fgrid, weights, tw, cdw, c->d_tG, c->d_tE, cgw);
+        LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cdw.G, cdw.E, c->d_tG, c->d_tE);
+        LAUNCH(c, KID_WMASK, st, k_wfinish<64>, cgw + fgrid, weights, tw, cdw, (const uint32_t *)c->d_tG,
+               (const uint32_t *)c->d_tE, c->d_wcut, c->d_pmask, cgw);
+        t.w = weights;
+        t.wT = c->d_wT;
+        t.wcut = c->d_wcut;
         t.pmask = c->d_pmask;
     }
 
@@ -1869,7 +2128,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
     if (!from_history) {
         if (!c->force_dense)
-            LAUNCH(c, KID_SAMPLE, st, k_sample, c->n_samp, grad, (const float *)residual, t, h.hs);
+            LAUNCH(c, KID_SAMPLE, st, k_sample<true>, c->n_samp, grad, (const float *)residual, t, h.hs);
         LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
     }
     if (c->force_dense) {
