@@ -136,7 +136,7 @@ typedef struct nsml_ctx nsml_ctx;
 /* Allocate a context and its device workspace on GPU `device` for gradients of up to max_n
  * elements in up to max_buckets buckets, quantized in chunks of `chunk` survivors (2048 in
  * the benchmark configurations; a positive multiple of 8).  Workspace: about 6.2 bytes per
- * element of max_n (survivor values, candidate staging, pruning bitmap) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
+ * element of max_n (survivor values, candidate staging, pruning bitmap for the rare bucket that needs one) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
  * available (there is no CPU fallback). */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 int nsml_destroy(nsml_ctx *ctx);
@@ -221,6 +221,12 @@ int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
  * (fallback).  Both give identical results.  Synchronises the device.  NSML_EINTERNAL if the
  * call tripped a device-side consistency check (its outputs are then not valid). */
 int nsml_path_stats(nsml_ctx *ctx, uint32_t *fast_buckets, uint32_t *fallback_buckets);
+/* The same for the weight-pruning stage of the last nsml_compress_pruned (zeros if the last
+ * compress call had no weights): how many non-empty buckets got their pruning threshold from
+ * the band of weights staged in one pass, and how many needed the dense ordered passes (a
+ * sample that missed, a huge group of equal weights).  Identical results either way.
+ * Synchronises the device.  NSML_EINTERNAL as above. */
+int nsml_prune_stats(nsml_ctx *ctx, uint32_t *band_buckets, uint32_t *dense_buckets);
 /* Measurement aid: a plain device-to-device copy kernel ("k_calib_copy") of `bytes` bytes
  * (a multiple of 16, both pointers 16-byte aligned, dev) on `stream`, on the current device.
  * A profiler's HBM byte counters are scaled by what they report for this copy of known size. */

@@ -66,6 +66,8 @@ _lib.nsml_profile_enable.argtypes = [_vp, _i32]
 _lib.nsml_profile_read.argtypes = [_vp, _vp, _vp]
 _lib.nsml_path_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
 _lib.nsml_path_stats.restype = _i32
+_lib.nsml_prune_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
+_lib.nsml_prune_stats.restype = _i32
 _lib.nsml_decompress_accumulate.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp]
 _lib.nsml_decompress_accumulate.restype = _i32
 _lib.nsml_last_l2norm.argtypes = [_vp, C.POINTER(_dbl), _vp]
@@ -257,6 +259,12 @@ class Context:
         """-> (fast buckets, fallback buckets) of the last compress call (synchronises)."""
         a, b = _u32(), _u32()
         _check(_lib.nsml_path_stats(self._h, C.byref(a), C.byref(b)), "nsml_path_stats", self._h)
+        return a.value, b.value
+
+    def prune_stats(self):
+        """-> (band buckets, dense buckets) of the weight stage of the last compress_pruned (synchronises)."""
+        a, b = _u32(), _u32()
+        _check(_lib.nsml_prune_stats(self._h, C.byref(a), C.byref(b)), "nsml_prune_stats", self._h)
         return a.value, b.value
 
     def profile_enable(self, on: bool = True):

@@ -1294,11 +1294,12 @@ __global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Table
 /* Per bucket: the band of keys [lo, hi) to stage, from the sample histogram of |w|. */
 __global__ __launch_bounds__(WG) void k_wpredict(Tables t, const uint32_t *__restrict__ hist_s,
                                                  uint32_t *__restrict__ wLo, uint32_t *__restrict__ wHi,
-                                                 int force_dense)
+                                                 int force_dense, uint32_t *__restrict__ werr)
 {
     __shared__ uint32_t tmp[WG];
     __shared__ uint32_t res[6];          /* digit, above, at for the upper and the lower rank */
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    if (b == 0 && tid == 0) werr[0] = 0u;        /* the weight stage's own consistency flag */
     const uint64_t nb = t.off[b + 1] - t.off[b];
     const uint32_t k = t.k[b];
     if (nb == 0 || k == 0 || force_dense) {
@@ -1692,6 +1693,8 @@ struct nsml_ctx {
     uint32_t *d_kw, *d_Tw, *d_needw;              /* pruning stage: kept counts, threshold search state */
     uint32_t *d_wT, *d_wcut, *d_wfast;            /* pruning stage: threshold key and cut index per bucket; path taken */
     uint32_t *d_wLo, *d_wHi;                      /* pruning stage: band of keys staged per bucket */
+    uint32_t *d_werr;                             /* pruning stage: consistency flag (1 word) */
+    bool have_prune;                              /* the last compress call had weights */
     double *d_span_sq;     /* per span: sum of grad^2 */
     double *d_l2sq;        /* per bucket: sum of grad^2 of the last compress call */
     bool have_l2;
@@ -1961,7 +1964,8 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
-    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = nullptr;
+    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = c->d_werr = nullptr;
+    c->have_prune = false;
     const char *so = getenv("NSML_SPAN_TILES");
     c->span_override = so ? atoi(so) : 0;
     const char *sw = getenv("NSML_SEG_WAVES");
@@ -2020,7 +2024,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
     A(dev_alloc(c, &c->d_margin, B1));
     A(dev_alloc(c, &c->d_wT, B1)); A(dev_alloc(c, &c->d_wfast, B1)); A(dev_alloc(c, &c->d_wcut, B1));
-    A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1));
+    A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1)); A(dev_alloc(c, &c->d_werr, 1));
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
@@ -2041,7 +2045,7 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
                     c->d_Tw, c->d_needw, c->d_margin, c->d_wT, c->d_wfast, c->d_wcut,
-                    c->d_wLo, c->d_wHi};
+                    c->d_wLo, c->d_wHi, c->d_werr};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -2094,7 +2098,8 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
         if (!c->force_dense)
             LAUNCH(c, KID_SAMPLE, st, k_sample<false>, c->n_samp, weights, (const float *)nullptr, tw, h.hs);
-        LAUNCH(c, KID_WPLAN, st, k_wpredict, B, tw, (const uint32_t *)h.hs, c->d_wLo, c->d_wHi, c->force_dense);
+        LAUNCH(c, KID_WPLAN, st, k_wpredict, B, tw, (const uint32_t *)h.hs, c->d_wLo, c->d_wHi, c->force_dense,
+               c->d_werr);
         LAUNCHB(c, KID_WHIST, st, k_whist, c->n_spans, eblock, weights, tw, h.h0, cdw,
                 (const uint32_t *)c->d_wLo, (const uint32_t *)c->d_wHi);
         LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0, (const uint32_t *)c->d_wLo,
@@ -2104,9 +2109,9 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
         else
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
-        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
+        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_werr, 0);
         LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cgw + fgrid, weights, tw, cdw, h.c2, h.f2, cgw);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, 0, c->d_wT);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_werr, 0, c->d_wT);
         LAUNCH(c, KID_COUNT, st, k_count<64>, cgw + fgrid, weights, tw, cdw, c->d_tG, c->d_tE, cgw);
         LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cdw.G, cdw.E, c->d_tG, c->d_tE);
         LAUNCH(c, KID_WMASK, st, k_wfinish<64>, cgw + fgrid, weights, tw, cdw, (const uint32_t *)c->d_tG,
@@ -2196,6 +2201,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
     }
     c->have_l2 = true;
+    c->have_prune = pruned;
     c->hist_ready = write_next != 0;
     c->hist_ratio = ratio;
     c->hist_pruned = pruned;
@@ -2340,6 +2346,24 @@ int nsml_path_stats(nsml_ctx *c, uint32_t *fast_buckets, uint32_t *fallback_buck
     }
     uint32_t err = 0;
     NSML_HIP(c, hipMemcpy(&err, hists_of(c, c->B).err, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    return err ? NSML_EINTERNAL : NSML_OK;
+}
+
+int nsml_prune_stats(nsml_ctx *c, uint32_t *band_buckets, uint32_t *dense_buckets)
+{
+    if (!c || !band_buckets || !dense_buckets) return NSML_EINVAL;
+    *band_buckets = *dense_buckets = 0;
+    if (c->B == 0 || !c->have_prune) return NSML_OK;
+    DeviceGuard guard(c->device);
+    NSML_HIP(c, hipDeviceSynchronize());
+    std::vector<uint32_t> f(c->B);
+    NSML_HIP(c, hipMemcpy(f.data(), c->d_wfast, sizeof(uint32_t) * c->B, hipMemcpyDeviceToHost));
+    for (uint32_t b = 0; b < c->B; ++b) {
+        if (c->h_off[b + 1] == c->h_off[b]) continue;
+        if (f[b]) *band_buckets += 1; else *dense_buckets += 1;
+    }
+    uint32_t err = 0;
+    NSML_HIP(c, hipMemcpy(&err, c->d_werr, sizeof(uint32_t), hipMemcpyDeviceToHost));
     return err ? NSML_EINTERNAL : NSML_OK;
 }
 

@@ -159,6 +159,59 @@ def test_cfg4_llama7b_full_sampled():
     assert int((dense != 0).sum()) <= K
 
 
+def test_cfg4_llama7b_pruned_full_sampled():
+    """Configuration 4 with Algorithm 2 Step 2 in front: the same 6.74 G-element gradient and
+    N(0, 0.02) weights, one step at the launch configuration the benchmark's --prune run uses;
+    the oracle's pruned chain on the first and the last (short) bucket, the conservation law on
+    everything."""
+    off = W.llama7b_bucket_offsets()
+    n = int(off[-1])
+    B = len(off) - 1
+    g = torch.empty(n, dtype=torch.float32, device=DEV)
+    w = torch.empty(n, dtype=torch.float32, device=DEV)
+    r = torch.zeros(n, dtype=torch.float32, device=DEV)
+    dense = torch.empty(n, dtype=torch.float32, device=DEV)
+    say("cfg4 pruned: generate")
+    W.llama7b_grad(0, DEV, out=g)
+    gen = torch.Generator(device=DEV)
+    for b in range(B):
+        gen.manual_seed((44 << 40) | b)
+        lo, hi = int(off[b]), int(off[b + 1])
+        w[lo:hi] = torch.randn(hi - lo, generator=gen, device=DEV) * 0.02
+    ctx = nsml.Context(n, B, 2048)
+    ratio, bits = 0.001, 4
+    idx, val, sc = ctx.alloc_payload(off, ratio, bits)
+    say("cfg4 pruned: compress")
+    ctx.compress_pruned(g, r, w, off, ratio, bits, idx, val, sc)
+    ctx.decompress(idx, val, sc, n, off, ratio, bits, dense)
+    torch.cuda.synchronize()
+    fast, fb = ctx.path_stats()
+    band, wdense = ctx.prune_stats()
+    say("cfg4 pruned: gradient buckets in one pass", fast, "dense", fb, "| weight buckets from the band", band, "dense", wdense)
+    assert fast >= 250 and band >= 250
+    k_b, K, vb, ns = oracle.layout(off, ratio, bits, 2048)
+    P = np.concatenate([[0], np.cumsum(k_b)]).astype(np.int64)
+    V = np.concatenate([[0], np.cumsum([(int(k) + 1) // 2 for k in k_b])]).astype(np.int64)
+    S = np.concatenate([[0], np.cumsum([-(-int(k) // 2048) for k in k_b])]).astype(np.int64)
+    for b in (0, B - 1):
+        say("cfg4 pruned: oracle on bucket", b)
+        lo, hi = int(off[b]), int(off[b + 1])
+        sub_off = W.offsets_of([hi - lo])
+        r_h = np.zeros(hi - lo, dtype=np.float32)
+        w_idx, w_val, w_sc = oracle.compress_pruned(g[lo:hi].cpu().numpy(), r_h, w[lo:hi].cpu().numpy(), sub_off,
+                                                    ratio, bits, 2048, nthreads=1)
+        got = (idx[P[b]:P[b + 1]].cpu().numpy().view(np.uint32), val[V[b]:V[b + 1]].cpu().numpy(),
+               sc[S[b]:S[b + 1]].cpu().numpy())
+        compare_payload(sub_off, ratio, bits, 2048, got, (w_idx, w_val, w_sc))
+        assert np.array_equal(r[lo:hi].cpu().numpy().view(np.uint32), r_h.view(np.uint32))
+        w_dense = oracle.decompress(w_idx, w_val, w_sc, hi - lo, sub_off, ratio, bits, 2048)
+        assert np.array_equal(dense[lo:hi].cpu().numpy().view(np.uint32), w_dense.view(np.uint32))
+    say("cfg4 pruned: conservation")
+    del w
+    assert torch.equal(dense.add_(r), g)          # residual started at zero: sent + kept back == gradient
+    del dense
+
+
 def test_cfg5_adaptive_run_scaled():
     """Configuration 5: 200 steps, fresh gradient each step, bandwidth trace -> nsml_choose_ratio
     -> (ratio, bits) varying per step.  ResNet-50 shape at 1/16 scale so the oracle chain

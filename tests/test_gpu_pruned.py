@@ -24,7 +24,7 @@ def _rand(n, seed, sigma=1e-3):
     return torch.randn(n, generator=g, device=DEV) * sigma
 
 
-def _run(sizes, ratio, bits, chunk, steps=2, ties=False, seed=0):
+def _run(sizes, ratio, bits, chunk, steps=2, ties=False, seed=0, stats=None):
     off = W.offsets_of(sizes)
     n = int(off[-1])
     ctx = nsml.Context(n, len(sizes), chunk)
@@ -33,13 +33,18 @@ def _run(sizes, ratio, bits, chunk, steps=2, ties=False, seed=0):
     for step in range(steps):
         g = _rand(n, seed + 10 * step)
         w = _rand(n, seed + 10 * step + 1, sigma=0.05)
-        if ties:
+        if ties == "few":
+            w = (w * 20000).round() / 20000      # some hundred equal |w| at the threshold, of both signs
+        elif ties:
             w = (w * 40).round() / 40            # many equal |w|, zeros included
             g = (g * 2e3).round() / 2e3
         idx, val, sc = ctx.compress_pruned(g, r, w, off, ratio, bits)
         dense = ctx.decompress(idx, val, sc, n, off, ratio, bits)
         torch.cuda.synchronize()
-        ctx.path_stats()
+        ctx.path_stats()                         # raise if a device-side consistency check tripped
+        ws = ctx.prune_stats()
+        if stats is not None:
+            stats.append(ws)
         w_idx, w_val, w_sc = oracle.compress_pruned(g.cpu().numpy(), r_h, w.cpu().numpy(), off, ratio,
                                                     bits, chunk, nthreads=8)
         k_b, K, vb, ns = oracle.layout(off, ratio, bits, chunk)
@@ -63,6 +68,16 @@ def test_ratios(ratio):
 def test_many_equal_weights_and_gradients():
     _run([100_000, 150_001, 49_999], 0.02, 4, 128, ties=True)
     _run([100_000, 150_001, 49_999], 0.4, 32, 128, ties=True, seed=5)
+
+
+def test_equal_weights_at_the_threshold_decided_from_the_band(path):
+    """Weights on a grid fine enough that the threshold's level-0 digit holds a few per cent of a
+    bucket (so the weight stage works from the staged band, not the dense passes) and coarse enough
+    that some hundred weights equal the threshold: which of them are kept is decided by index."""
+    stats = []
+    _run([300_000, 1_000_003, 70_000], 0.01, 8, 256, ties="few", seed=21, stats=stats)
+    for band, dense in stats:
+        assert (band, dense) == ((0, 3) if path == "dense" else (3, 0))
 
 
 def test_large_single_bucket():
