@@ -136,7 +136,8 @@ typedef struct nsml_ctx nsml_ctx;
 /* Allocate a context and its device workspace on GPU `device` for gradients of up to max_n
  * elements in up to max_buckets buckets, quantized in chunks of `chunk` survivors (2048 in
  * the benchmark configurations; a positive multiple of 8).  Workspace: about 6.2 bytes per
- * element of max_n (survivor values, candidate staging, pruning bitmap for the rare bucket that needs one) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
+ * element of max_n (survivor values, candidate staging, a pruning bitmap for the rare bucket
+ * that needs one) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
  * available (there is no CPU fallback). */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 int nsml_destroy(nsml_ctx *ctx);
