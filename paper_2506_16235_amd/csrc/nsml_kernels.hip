@@ -465,7 +465,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__rest
  * staging segment, in index order: ranks come from ballots, nothing crosses wavefronts.  Every
  * lane of the wavefront must call this. */
 __device__ __forceinline__ void emit_quad(const bool (&f)[4], const float (&a)[4], uint32_t li, const Cand &c,
-                                          uint64_t cbase, uint32_t &wcount, uint64_t lt)
+                                          uint64_t cbase, uint32_t &wcount)
 {
     if (__ballot(f[0] | f[1] | f[2] | f[3]) == 0ull) return;
     uint64_t bal[4];
@@ -476,7 +476,6 @@ __device__ __forceinline__ void emit_quad(const bool (&f)[4], const float (&a)[4
         /* flagged entries in lower lanes */
         pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal[j] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal[j], pos));
     }
-    (void)lt;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (f[j]) {
@@ -494,7 +493,7 @@ __device__ __forceinline__ void emit_quad(const bool (&f)[4], const float (&a)[4
 template <bool INTERIOR, bool EMIT, int NT, bool PRUNE>
 __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const float (&a)[4],
                                        uint32_t m, uint32_t cm, uint32_t li, uint32_t *h, uint32_t L,
-                                       const Cand &c, uint64_t cbase, uint32_t &wcount, uint64_t lt)
+                                       const Cand &c, uint64_t cbase, uint32_t &wcount)
 {
     uint32_t key[4];
 #pragma unroll
@@ -521,7 +520,7 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
         bool f[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) f[j] = ((cm >> j) & 1u) && key[j] >= L;
-        emit_quad(f, a, li, c, cbase, wcount, lt);
+        emit_quad(f, a, li, c, cbase, wcount);
     }
 }
 
@@ -547,7 +546,6 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     const uint32_t L = EMIT ? t.L[s.b] : NONE;
     const uint32_t wT = PRUNE ? t.wT[s.b] : 0u;          /* NONE: this bucket's mask is in the bitmap */
     const uint32_t wcut = PRUNE ? t.wcut[s.b] : 0u;
-    const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t ss = (blockIdx.x << t.segSh) + wave;
     const uint64_t cbase = (uint64_t)ss * c.cap;
     uint32_t wcount = 0;
@@ -589,7 +587,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
                     } else
                         cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
                 }
-                ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+                ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount);
             }
         } else {
 #pragma unroll
@@ -602,7 +600,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
                 for (int j = 0; j < 4; ++j) { a[j] = __fadd_rn(x[j], y[j]); sq += (double)__fmul_rn(x[j], x[j]); }
                 uint32_t cm = m;
                 if (PRUNE) cm &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
-                ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount, lt);
+                ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount);
             }
         }
     }
@@ -1351,7 +1349,6 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_whist(const float *__res
     for (uint32_t i = tid; i < NB0; i += nthreads) h[i] = 0;
     const SpanGeo s = span_geo(t, blockIdx.x);
     const uint32_t lo_k = wLo[s.b], hi_k = wHi[s.b];       /* NONE, 0: nothing is staged */
-    const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t ss = (blockIdx.x << t.segSh) + wave;
     const uint64_t cbase = (uint64_t)ss * c.cap;
     uint32_t wcount = 0;
@@ -1375,7 +1372,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_whist(const float *__res
 #pragma unroll
                 for (int j = 0; j < 4; ++j) { key[j] = keyof(a[j]); f[j] = key[j] >= lo_k && key[j] < hi_k; }
                 hist_quad_full(h, key[0] >> SH0, key[1] >> SH0, key[2] >> SH0, key[3] >> SH0);
-                emit_quad(f, a, (uint32_t)(gi - s.lo), c, cbase, wcount, lt);
+                emit_quad(f, a, (uint32_t)(gi - s.lo), c, cbase, wcount);
             }
         } else {
 #pragma unroll
@@ -1391,7 +1388,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_whist(const float *__res
                     if (in) atomicAdd(&h[key >> SH0], 1u);
                     f[j] = in && key >= lo_k && key < hi_k;
                 }
-                emit_quad(f, a, (uint32_t)(gi - s.lo), c, cbase, wcount, lt);
+                emit_quad(f, a, (uint32_t)(gi - s.lo), c, cbase, wcount);
             }
         }
     }
