@@ -1526,9 +1526,35 @@ __device__ __forceinline__ float decode(const uint8_t *__restrict__ vb, const fl
 }
 
 /* Where each tile's survivors start in its bucket's ascending index list: ts[tile0[b] + b + i]
- * = number of survivors of bucket b with an index below tile i (i = 0..tiles_b).  One thread
- * per survivor writes the entries of the tiles that begin between its predecessor and itself;
- * the last survivor of a bucket also closes the bucket's remaining tiles. */
+ * = number of survivors of bucket b with an index below tile i (i = 0..tiles_b).  A thread
+ * takes TS_PER consecutive survivors (8 for long payloads, 2 for short ones, which need the
+ * threads more); a survivor whose tile differs from its predecessor's writes the entries of
+ * the tiles that begin between the two, and the last survivor of a bucket also closes the
+ * bucket's remaining tiles. */
+
+__device__ __forceinline__ void tilestart_one(const uint32_t *__restrict__ idx, const Tables &t, uint32_t b,
+                                              uint64_t j, uint32_t *__restrict__ ts)
+{
+    const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
+    const uint32_t kb = t.k[b];
+    const uint32_t jj = (uint32_t)(j - t.P[b]);
+    uint32_t *tsb = ts + t.tile0[b] + b;
+    const uint32_t head = (uint32_t)(t.off[b] & 3ull);
+    /* tile of a local index; indices beyond the bucket (invalid payload) count as the last tile */
+    uint32_t tcur = (uint32_t)(((uint64_t)idx[j] + head) / TILE);
+    tcur = min(tcur, tiles_b - 1);
+    uint32_t tfrom = 0;                         /* first tile this survivor fills */
+    if (jj > 0) {
+        uint32_t tprev = (uint32_t)(((uint64_t)idx[j - 1] + head) / TILE);
+        tprev = min(tprev, tiles_b - 1);
+        tfrom = tprev + 1;
+    }
+    for (uint32_t tt = tfrom; tt <= tcur; ++tt) tsb[tt] = jj;
+    if (jj == kb - 1)
+        for (uint32_t tt = tcur + 1; tt <= tiles_b; ++tt) tsb[tt] = kb;
+}
+
+template <uint32_t TS_PER>
 __global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ idx, Tables t,
                                                   uint64_t K, uint32_t *__restrict__ ts)
 {
@@ -1539,27 +1565,32 @@ __global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ i
         for (uint32_t i = threadIdx.x; i <= t.B; i += WG) sP[i] = t.P[i];
         __syncthreads();
     }
-    const uint64_t stride = (uint64_t)gridDim.x * WG;
-    for (uint64_t j = (uint64_t)blockIdx.x * WG + threadIdx.x; j < K; j += stride) {
-        const uint32_t b = in_lds ? find_bucket<uint64_t>(sP, t.B, j) : find_bucket<uint64_t>(t.P, t.B, j);
-        const uint64_t lo = t.off[b];
-        const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
-        const uint32_t kb = t.k[b];
-        const uint32_t jj = (uint32_t)(j - t.P[b]);
-        uint32_t *tsb = ts + t.tile0[b] + b;
-        const uint32_t head = (uint32_t)(lo & 3ull);
-        /* tile of a local index; indices beyond the bucket (invalid payload) count as the last tile */
-        uint32_t tcur = (uint32_t)(((uint64_t)idx[j] + head) / TILE);
-        tcur = min(tcur, tiles_b - 1);
-        uint32_t tfrom = 0;                         /* first tile this thread fills */
-        if (jj > 0) {
-            uint32_t tprev = (uint32_t)(((uint64_t)idx[j - 1] + head) / TILE);
-            tprev = min(tprev, tiles_b - 1);
-            tfrom = tprev + 1;
+    const uint64_t stride = (uint64_t)gridDim.x * WG * TS_PER;
+    for (uint64_t j0 = ((uint64_t)blockIdx.x * WG + threadIdx.x) * TS_PER; j0 < K; j0 += stride) {
+        const uint32_t b = in_lds ? find_bucket<uint64_t>(sP, t.B, j0) : find_bucket<uint64_t>(t.P, t.B, j0);
+        const uint64_t Pb = t.P[b], Pn = t.P[b + 1];
+        if (j0 > Pb && j0 + TS_PER < Pn) {
+            /* all of them inside one bucket, none its first or last survivor: only tile changes matter */
+            const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
+            const uint32_t head = (uint32_t)(t.off[b] & 3ull);
+            uint32_t *tsb = ts + t.tile0[b] + b;
+            uint32_t v[TS_PER + 1];
+#pragma unroll
+            for (uint32_t i = 0; i <= TS_PER; ++i) v[i] = idx[j0 - 1 + i];
+#pragma unroll
+            for (uint32_t i = 0; i <= TS_PER; ++i) v[i] = min((uint32_t)(((uint64_t)v[i] + head) / TILE), tiles_b - 1);
+            if (v[0] != v[TS_PER]) {
+                const uint32_t jj0 = (uint32_t)(j0 - Pb);
+#pragma unroll
+                for (uint32_t i = 1; i <= TS_PER; ++i)
+                    for (uint32_t tt = v[i - 1] + 1; tt <= v[i]; ++tt) tsb[tt] = jj0 + i - 1;
+            }
+        } else {
+            for (uint64_t j = j0; j < min(K, j0 + TS_PER); ++j) {
+                const uint32_t bj = j < Pn ? b : (in_lds ? find_bucket<uint64_t>(sP, t.B, j) : find_bucket<uint64_t>(t.P, t.B, j));
+                tilestart_one(idx, t, bj, j, ts);
+            }
         }
-        for (uint32_t tt = tfrom; tt <= tcur; ++tt) tsb[tt] = jj;
-        if (jj == kb - 1)
-            for (uint32_t tt = tcur + 1; tt <= tiles_b; ++tt) tsb[tt] = kb;
     }
 }
 
@@ -2236,8 +2267,13 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     rc = ensure_tables(c, ratio, bits, st);
     if (rc) return rc;
     const Tables t = tables_of(c);
-    const uint64_t want = (c->K + WG - 1) / WG;
-    LAUNCH(c, KID_TILESTART, st, k_tilestart, (uint32_t)(want < 16384 ? want : 16384), idx, t, c->K, c->d_ts);
+    if (c->K >= (4ull << 20)) {
+        const uint64_t want = (c->K + (uint64_t)WG * 8 - 1) / ((uint64_t)WG * 8);
+        LAUNCH(c, KID_TILESTART, st, k_tilestart<8>, (uint32_t)(want < 16384 ? want : 16384), idx, t, c->K, c->d_ts);
+    } else {
+        const uint64_t want = (c->K + (uint64_t)WG * 2 - 1) / ((uint64_t)WG * 2);
+        LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, c->K, c->d_ts);
+    }
     const uint32_t *ts = c->d_ts;
     if (c->nt_dense) {
         switch (bits) {
