@@ -138,7 +138,11 @@ typedef struct nsml_ctx nsml_ctx;
  * the benchmark configurations; a positive multiple of 8).  Workspace: about 6.2 bytes per
  * element of max_n (survivor values, candidate staging, a pruning bitmap for the rare bucket
  * that needs one) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
- * available (there is no CPU fallback). */
+ * available (there is no CPU fallback).
+ * A context serialises nothing itself: its calls share the workspace and the cached tables, so
+ * they must not overlap, neither from several host threads nor on different streams (use one
+ * context per stream).  A change of bucket layout between calls makes the next call wait for
+ * the stream once, to rebuild the tables; a change of (ratio, bits) costs one small kernel. */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 int nsml_destroy(nsml_ctx *ctx);
 
@@ -174,7 +178,8 @@ int nsml_compress(nsml_ctx *ctx, const float *grad, float *residual, uint64_t n,
  * survivors are chosen among the kept parameters only.  Pruning is not permanent: a pruned
  * parameter's accumulated gradient is written to the residual like any other unsent element
  * and competes again in later steps.  Outputs, payload layout and errors as nsml_compress.
- * Costs about five extra reads of `weights` per call. */
+ * Costs about two extra reads of `weights` per call (five for a bucket in which a huge group
+ * of equal weights surrounds the pruning threshold). */
 int nsml_compress_pruned(nsml_ctx *ctx, const float *grad, float *residual, const float *weights,
                          uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio,
                          int bits, uint32_t *idx, void *val, float *scales, void *stream);
