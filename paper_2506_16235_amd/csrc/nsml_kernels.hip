@@ -62,6 +62,7 @@ constexpr uint32_t SAMPLE_ALL_BELOW = 262144;  /* buckets smaller than this are 
 constexpr uint32_t SAMPLE_STRIDE = 64;         /* larger ones: 32 elements out of every 2048 */
 constexpr uint32_t RUNS_PER_WG = 128;          /* sample runs (32 elements each) per workgroup */
 constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
+constexpr uint32_t AGG_GRID = 1024;            /* workgroups of the candidate refine that aggregates in LDS */
 
 enum KernelId {
     KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
@@ -1739,6 +1740,7 @@ struct nsml_ctx {
     int span_override;
     int seg_override;      /* wavefronts per workgroup of the streaming pass (0: by span size) */
     int group_override;    /* lanes per staging segment in the candidate kernels (0: by ratio) */
+    int agg_override;      /* level-1 candidate histogram aggregated in LDS: 1 always, 0 never, -1 by size */
     int force_dense;
     int nt_mode;
     int nt_dense;          /* non-temporal stores for the dense output of decompress */
@@ -1999,6 +2001,8 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     const char *sw = getenv("NSML_SEG_WAVES");
     c->seg_override = sw ? atoi(sw) : 0;
     c->segSh = 2;
+    const char *ao = getenv("NSML_AGG");
+    c->agg_override = ao ? (atoi(ao) != 0 ? 1 : 0) : -1;
     const char *go = getenv("NSML_GROUP");
     c->group_override = go ? atoi(go) : 0;
     const char *fd = getenv("NSML_FORCE_DENSE");
@@ -2133,7 +2137,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0, (const uint32_t *)c->d_wLo,
                (const uint32_t *)c->d_wHi);
         LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, tw);
-        if (n_chunks_w >= 8u * SIDE_GRID)
+        if (cgw && (c->agg_override > 0 || (c->agg_override < 0 && n_chunks_w >= 8u * SIDE_GRID)))
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
         else
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
@@ -2208,7 +2212,16 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
 #define NSML_K_REFINE2(G) k_refine<2, G>
 #define NSML_K_COUNT(G) k_count<G>
 #define NSML_K_WRITE(G) k_write<G>
-    NSML_BY_GROUP(KID_REFINE1, NSML_K_REFINE1, acc, t, cd, h.c1, h.f1, cg);
+    if (cg && (c->agg_override > 0 || (c->agg_override < 0 && n_chunks >= 8u * AGG_GRID))) {
+        /* many segments per workgroup: count the level-1 digits in LDS over a contiguous range
+         * of chunks and add each bucket's histogram once (a third of the global atomics) */
+        const uint32_t ag = AGG_GRID;
+        if (group == 4) LAUNCH(c, KID_REFINE1, st, (k_refine<1, 4, true>), ag + fgrid, acc, t, cd, h.c1, h.f1, ag);
+        else if (group == 16) LAUNCH(c, KID_REFINE1, st, (k_refine<1, 16, true>), ag + fgrid, acc, t, cd, h.c1, h.f1, ag);
+        else LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), ag + fgrid, acc, t, cd, h.c1, h.f1, ag);
+    } else {
+        NSML_BY_GROUP(KID_REFINE1, NSML_K_REFINE1, acc, t, cd, h.c1, h.f1, cg);
+    }
     LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
     NSML_BY_GROUP(KID_REFINE2, NSML_K_REFINE2, acc, t, cd, h.c2, h.f2, cg);
     LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, write_next);

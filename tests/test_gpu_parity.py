@@ -155,6 +155,8 @@ def test_bert_shaped_scaled(ratio, bits):
 @pytest.mark.parametrize("span_tiles,seg_waves,group", [(1, 4, 16), (2, 8, 64), (4, 16, 16), (8, 8, 16),
                                                         (16, 4, 64), (16, 8, 16), (16, 16, 16), (16, 16, 64), (16, 16, 4), (2, 4, 4)])
 def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
+    # the level-1 histogram of the candidates aggregated in LDS (the rule from ~2 G elements up)
+    monkeypatch.setenv("NSML_AGG", "1" if (span_tiles + seg_waves + group) % 8 == 4 or group == 4 else "0")
     """The library picks tiles per workgroup, wavefronts per workgroup and lanes per staging
     segment from the size of the gradient; the large-gradient shapes are forced here on a
     gradient the oracle sorts in a second: ragged buckets, last spans with fewer tiles than

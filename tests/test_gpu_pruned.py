@@ -82,3 +82,10 @@ def test_equal_weights_at_the_threshold_decided_from_the_band(path):
 
 def test_large_single_bucket():
     _run([5_000_000], 0.01, 8, 2048, steps=2)
+
+
+def test_aggregated_level1_histogram(monkeypatch):
+    """The weight stage's level-1 histogram counted in LDS per workgroup (the rule for very large
+    gradients), forced on buckets small enough for the oracle."""
+    monkeypatch.setenv("NSML_AGG", "1")
+    _run([700_001, 300_000, 12_345, 1_500_000], 0.01, 8, 512, steps=1, seed=33)
