@@ -126,3 +126,8 @@ def test_create_rejects_bad_arguments():
     assert lib.nsml_create(None, 0, 1024, 1, 2048) == nsml.EINVAL
     assert lib.nsml_compress(None, None, None, 0, None, 0, 0.5, 8, None, None, None, None) == nsml.EINVAL
     assert lib.nsml_decompress(None, None, None, None, 0, None, 0, 0.5, 8, None, None) == nsml.EINVAL
+    a, b = C.c_uint32(7), C.c_uint32(7)
+    assert lib.nsml_path_stats(None, C.byref(a), C.byref(b)) == nsml.EINVAL
+    assert lib.nsml_prune_stats(None, C.byref(a), C.byref(b)) == nsml.EINVAL
+    assert lib.nsml_compress_pruned(None, None, None, None, 0, None, 0, 0.5, 8, None, None, None, None) == nsml.EINVAL
+    assert lib.nsml_decompress_accumulate(None, None, None, None, 0, None, 0, 0.5, 8, None, None) == nsml.EINVAL
