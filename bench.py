@@ -92,9 +92,22 @@ def cpu_baseline(workload, grads, off, ratio, bits, chunk):
         oracle.decompress(idx, val, sc, g.size, sub_off, ratio, bits, chunk, nthreads=cores)
     dt = time.perf_counter() - t0
     used = min(cores, len(pick))
-    return {"value": round(4.0 * gs[0].size * steps / dt / 1e9, 4), "unit": "GB/s", "cores": used,
-            "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"{what}; {gs[0].size} elements per step, compress+decompress, one bucket per thread"}
+    out = {"value": round(4.0 * gs[0].size * steps / dt / 1e9, 4), "unit": "GB/s", "cores": used,
+           "kind": "oracle", "seconds": round(dt, 2),
+           "sample": f"{what}; {gs[0].size} elements per step, compress+decompress, one bucket per thread"}
+    if workload != "llama7b":
+        # the same on one thread (the three small configurations only), fewer steps
+        steps1 = {"bert": 1, "resnet50": 4, "cfg1": 20}[workload]
+        r = np.zeros_like(gs[0])
+        t0 = time.perf_counter()
+        for s in range(steps1):
+            g = gs[s % len(gs)]
+            idx, val, sc = oracle.compress(g, r, sub_off, ratio, bits, chunk, nthreads=1)
+            oracle.decompress(idx, val, sc, g.size, sub_off, ratio, bits, chunk, nthreads=1)
+        dt1 = time.perf_counter() - t0
+        out["single_thread"] = {"value": round(4.0 * gs[0].size * steps1 / dt1 / 1e9, 4), "unit": "GB/s",
+                                "seconds": round(dt1, 2), "steps": steps1}
+    return out
 
 
 def main():
