@@ -1,0 +1,265 @@
+/*
+ * libnsml device code, part 4: value coding of the survivors and the decompress kernels.
+ * Included by nsml_kernels.hip (one translation unit); not a public header.
+ */
+#ifndef NSML_CODEC_HPP
+#define NSML_CODEC_HPP
+
+namespace {
+
+/* ------------------------------------------------------------------ value coding */
+
+/* One workgroup per chunk of `chunk` consecutive survivors of one bucket: absmax, scale,
+ * codes, packing, and the coding error left in the residual.  Every floating-point step is a
+ * single correctly rounded binary32 operation (divide, round-to-nearest-even, multiply,
+ * subtract); nothing may be contracted into an fma. */
+template <int BITS>
+__global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const uint32_t *__restrict__ idx,
+                                              Tables t, float *__restrict__ r, void *__restrict__ val,
+                                              float *__restrict__ scales)
+{
+    __shared__ float red[WG / 64];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t c = blockIdx.x;
+    const uint32_t b = find_bucket<uint64_t>(t.C, t.B, c);
+    const uint64_t cb = c - t.C[b];
+    const uint64_t j0 = cb * t.chunk;                         /* first survivor of the chunk, bucket-local */
+    const uint32_t cnt = (uint32_t)min((uint64_t)t.chunk, (uint64_t)t.k[b] - j0);
+    const uint64_t jg = t.P[b] + j0;                          /* same, global */
+    const uint64_t lo = t.off[b];
+    float scale = 0.0f;
+    if (BITS <= 8) {
+        constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+        float m = 0.0f;
+        for (uint32_t i = tid; i < cnt; i += WG) m = fmaxf(m, fabsf(v[jg + i]));
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+        if ((tid & 63) == 0) red[tid >> 6] = m;
+        __syncthreads();
+        m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        scale = m == 0.0f ? 0.0f : __fdiv_rn(m, QMAX);
+        if (tid == 0) scales[t.S[b] + cb] = scale;
+    }
+    uint8_t *vb = reinterpret_cast<uint8_t *>(val) + t.V[b];
+    /* two survivors per thread per round, so a 4-bit pair is one byte store */
+    for (uint32_t p = tid; 2 * p < cnt; p += WG) {
+        float res[2];
+        int q[2] = {0, 0};
+        const uint32_t i0 = 2 * p;
+        const int have = (i0 + 1 < cnt) ? 2 : 1;
+        for (int h = 0; h < have; ++h) {
+            const float x = v[jg + i0 + h];
+            float deq;
+            if (BITS == 32) {
+                deq = x;
+            } else if (BITS == 16) {
+                const __half hv = __float2half_rn(x);
+                reinterpret_cast<__half *>(vb)[j0 + i0 + h] = hv;
+                deq = __half2float(hv);
+            } else {
+                constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+                if (scale != 0.0f) {
+                    float tq = rintf(__fdiv_rn(x, scale));
+                    tq = fminf(fmaxf(tq, -QMAX), QMAX);
+                    q[h] = (int)tq;
+                }
+                deq = __fmul_rn((float)q[h], scale);
+                if (BITS == 8) reinterpret_cast<int8_t *>(vb)[j0 + i0 + h] = (int8_t)q[h];
+            }
+            res[h] = __fsub_rn(x, deq);
+        }
+        if (BITS == 4) vb[(j0 >> 1) + p] = (uint8_t)((q[0] & 0xF) | ((q[1] & 0xF) << 4));
+        for (int h = 0; h < have; ++h) r[lo + idx[jg + i0 + h]] = res[h];
+    }
+}
+
+/* ------------------------------------------------------------------ decompress */
+
+template <int BITS>
+__device__ __forceinline__ float decode(const uint8_t *__restrict__ vb, const float *__restrict__ sc,
+                                        uint64_t j, uint32_t chunk)
+{
+    if (BITS == 32) return reinterpret_cast<const float *>(vb)[j];
+    if (BITS == 16) return __half2float(reinterpret_cast<const __half *>(vb)[j]);
+    int q;
+    if (BITS == 8) q = reinterpret_cast<const int8_t *>(vb)[j];
+    else {
+        const uint32_t byte = vb[j >> 1];
+        const int nib = (j & 1) ? (int)(byte >> 4) : (int)(byte & 0xFu);
+        q = nib >= 8 ? nib - 16 : nib;
+    }
+    return __fmul_rn((float)q, sc[j / chunk]);
+}
+
+/* Where each tile's survivors start in its bucket's ascending index list: ts[tile0[b] + b + i]
+ * = number of survivors of bucket b with an index below tile i (i = 0..tiles_b).  A thread
+ * takes TS_PER consecutive survivors (8 for long payloads, 2 for short ones, which need the
+ * threads more); a survivor whose tile differs from its predecessor's writes the entries of
+ * the tiles that begin between the two, and the last survivor of a bucket also closes the
+ * bucket's remaining tiles. */
+
+__device__ __forceinline__ void tilestart_one(const uint32_t *__restrict__ idx, const Tables &t, uint32_t b,
+                                              uint64_t j, uint32_t *__restrict__ ts)
+{
+    const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
+    const uint32_t kb = t.k[b];
+    const uint32_t jj = (uint32_t)(j - t.P[b]);
+    uint32_t *tsb = ts + t.tile0[b] + b;
+    const uint32_t head = (uint32_t)(t.off[b] & 3ull);
+    /* tile of a local index; indices beyond the bucket (invalid payload) count as the last tile */
+    uint32_t tcur = (uint32_t)(((uint64_t)idx[j] + head) / TILE);
+    tcur = min(tcur, tiles_b - 1);
+    uint32_t tfrom = 0;                         /* first tile this survivor fills */
+    if (jj > 0) {
+        uint32_t tprev = (uint32_t)(((uint64_t)idx[j - 1] + head) / TILE);
+        tprev = min(tprev, tiles_b - 1);
+        tfrom = tprev + 1;
+    }
+    for (uint32_t tt = tfrom; tt <= tcur; ++tt) tsb[tt] = jj;
+    if (jj == kb - 1)
+        for (uint32_t tt = tcur + 1; tt <= tiles_b; ++tt) tsb[tt] = kb;
+}
+
+template <uint32_t TS_PER>
+__global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ idx, Tables t,
+                                                  uint64_t K, uint32_t *__restrict__ ts)
+{
+    constexpr uint32_t LDS_B = 2047;
+    __shared__ uint64_t sP[LDS_B + 1];
+    const bool in_lds = t.B <= LDS_B;
+    if (in_lds) {
+        for (uint32_t i = threadIdx.x; i <= t.B; i += WG) sP[i] = t.P[i];
+        __syncthreads();
+    }
+    const uint64_t stride = (uint64_t)gridDim.x * WG * TS_PER;
+    for (uint64_t j0 = ((uint64_t)blockIdx.x * WG + threadIdx.x) * TS_PER; j0 < K; j0 += stride) {
+        const uint32_t b = in_lds ? find_bucket<uint64_t>(sP, t.B, j0) : find_bucket<uint64_t>(t.P, t.B, j0);
+        const uint64_t Pb = t.P[b], Pn = t.P[b + 1];
+        if (j0 > Pb && j0 + TS_PER < Pn) {
+            /* all of them inside one bucket, none its first or last survivor: only tile changes matter */
+            const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
+            const uint32_t head = (uint32_t)(t.off[b] & 3ull);
+            uint32_t *tsb = ts + t.tile0[b] + b;
+            uint32_t v[TS_PER + 1];
+#pragma unroll
+            for (uint32_t i = 0; i <= TS_PER; ++i) v[i] = idx[j0 - 1 + i];
+#pragma unroll
+            for (uint32_t i = 0; i <= TS_PER; ++i) v[i] = min((uint32_t)(((uint64_t)v[i] + head) / TILE), tiles_b - 1);
+            if (v[0] != v[TS_PER]) {
+                const uint32_t jj0 = (uint32_t)(j0 - Pb);
+#pragma unroll
+                for (uint32_t i = 1; i <= TS_PER; ++i)
+                    for (uint32_t tt = v[i - 1] + 1; tt <= v[i]; ++tt) tsb[tt] = jj0 + i - 1;
+            }
+        } else {
+            for (uint64_t j = j0; j < min(K, j0 + TS_PER); ++j) {
+                const uint32_t bj = j < Pn ? b : (in_lds ? find_bucket<uint64_t>(sP, t.B, j) : find_bucket<uint64_t>(t.P, t.B, j));
+                tilestart_one(idx, t, bj, j, ts);
+            }
+        }
+    }
+}
+
+/* Dense output for a span of tiles: each tile is assembled in LDS (zeros, then the decoded
+ * survivors that fall inside it, found through the tile-start table) and written out once with
+ * aligned 16-byte stores, so no output line is touched twice and no atomics are needed.  The
+ * loads of the next tile's survivors are issued before the current tile is written out. */
+template <int BITS, bool NTS>
+__global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx, const void *__restrict__ val,
+                                               const float *__restrict__ scales, Tables t,
+                                               const uint32_t *__restrict__ ts, float *__restrict__ dense)
+{
+    __shared__ float tile[TILE];
+    __shared__ uint32_t sts[MAX_SPAN_TILES + 1];
+    const uint32_t tid = threadIdx.x;
+    const SpanGeo s = span_geo(t, blockIdx.x);
+    const uint32_t kb = t.k[s.b];
+    const uint32_t *ib = idx + t.P[s.b];
+    const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[s.b];
+    const float *sb = BITS <= 8 ? scales + t.S[s.b] : nullptr;
+    const uint32_t nb = (uint32_t)(s.hi - s.lo);
+    const uint32_t first = s.tile_g - t.tile0[s.b];
+    if (tid <= s.ntiles) sts[tid] = min(ts[t.tile0[s.b] + s.b + first + tid], kb);
+    __syncthreads();
+
+    /* survivor number j0 + tid of a tile, if it exists: local index and decoded value */
+    uint32_t p_li = NONE;
+    float p_x = 0.0f;
+    auto fetch = [&](uint32_t ti) {
+        p_li = NONE;
+        if (ti < s.ntiles) {
+            const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
+            const uint64_t j = (uint64_t)j0 + tid;
+            if (j < j1) { p_li = ib[j]; p_x = decode<BITS>(vb, sb, j, t.chunk); }
+        }
+    };
+    fetch(0);
+    for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
+        const uint64_t tb = s.base + (uint64_t)ti * TILE;
+        const uint64_t shift = s.lo - tb;                   /* slot = local index + lo - tb (mod 2^64) */
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *reinterpret_cast<f4 *>(&tile[(u * WG + tid) * 4]) = f4{0.f, 0.f, 0.f, 0.f};
+        __syncthreads();
+        if (p_li < nb) {
+            const uint64_t slot = (uint64_t)p_li + shift;
+            if (slot < TILE) tile[slot] = p_x;
+        }
+        /* more than 256 survivors in the tile (ratio above 6 %) */
+        const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
+        for (uint64_t j = (uint64_t)j0 + WG + tid; j < j1; j += WG) {
+            const uint32_t li = ib[j];
+            const uint64_t slot = (uint64_t)li + shift;
+            if (li < nb && slot < TILE) tile[slot] = decode<BITS>(vb, sb, j, t.chunk);
+        }
+        fetch(ti + 1);
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t sl = (u * WG + tid) * 4;
+            const uint64_t gi = tb + sl;
+            if (gi >= s.lo && gi + 4 <= s.hi) {
+                const f4 v = *reinterpret_cast<const f4 *>(&tile[sl]);
+                if (NTS) __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dense + gi));
+                else *reinterpret_cast<f4 *>(dense + gi) = v;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (gi + j >= s.lo && gi + j < s.hi) dense[gi + j] = tile[sl + j];
+            }
+        }
+    }
+}
+
+/* Receiver side of an all-gather of payloads: add one worker's decoded survivors into a dense
+ * gradient that is being accumulated (nothing else is touched).  One thread per survivor;
+ * the indices of a payload are distinct, so plain read-modify-write needs no atomics. */
+template <int BITS>
+__global__ __launch_bounds__(WG) void k_decomp_acc(const uint32_t *__restrict__ idx, const void *__restrict__ val,
+                                                   const float *__restrict__ scales, Tables t, uint64_t K,
+                                                   float *__restrict__ dense)
+{
+    constexpr uint32_t LDS_B = 2047;
+    __shared__ uint64_t sP[LDS_B + 1];
+    const bool in_lds = t.B <= LDS_B;
+    if (in_lds) {
+        for (uint32_t i = threadIdx.x; i <= t.B; i += WG) sP[i] = t.P[i];
+        __syncthreads();
+    }
+    const uint64_t stride = (uint64_t)gridDim.x * WG;
+    for (uint64_t j = (uint64_t)blockIdx.x * WG + threadIdx.x; j < K; j += stride) {
+        const uint32_t b = in_lds ? find_bucket<uint64_t>(sP, t.B, j) : find_bucket<uint64_t>(t.P, t.B, j);
+        const uint64_t lo = t.off[b], nb = t.off[b + 1] - lo;
+        const uint64_t jj = j - t.P[b];
+        const uint32_t li = idx[j];
+        if (li >= nb) continue;                       /* invalid payload: never leave the bucket */
+        const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[b];
+        const float *sb = BITS <= 8 ? scales + t.S[b] : nullptr;
+        const float x = decode<BITS>(vb, sb, jj, t.chunk);
+        dense[lo + li] = __fadd_rn(dense[lo + li], x);
+    }
+}
+
+}  // namespace
+
+#endif

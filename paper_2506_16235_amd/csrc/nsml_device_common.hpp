@@ -1,0 +1,344 @@
+/*
+ * libnsml device code, part 1: constants, device-resident tables, geometry, set-up kernels, histogram helpers.
+ * Included by nsml_kernels.hip (one translation unit); not a public header.
+ */
+#ifndef NSML_DEVICE_COMMON_HPP
+#define NSML_DEVICE_COMMON_HPP
+
+namespace {
+
+constexpr int WG = 256;
+constexpr int TILE = 4096;        /* elements per tile */
+constexpr int WTILE = 1024;       /* elements one wavefront covers per iteration in ef_emit */
+constexpr int NB0 = 4096, NB1 = 4096, NB2 = 128;
+constexpr int SH0 = 19;   /* key >> 19         : level-0 digit (sign-less exponent + 4 mantissa bits) */
+constexpr int SH1 = 7;    /* (key >> 7) & 4095 : level-1 digit;  key & 127 : level-2 digit */
+constexpr int MAX_SPAN_TILES = 16;
+constexpr uint32_t NONE = 0xFFFFFFFFu;
+constexpr uint32_t SAMPLE_ALL_BELOW = 262144;  /* buckets smaller than this are sampled in full */
+constexpr uint32_t SAMPLE_STRIDE = 64;         /* larger ones: 32 elements out of every 2048 */
+constexpr uint32_t RUNS_PER_WG = 128;          /* sample runs (32 elements each) per workgroup */
+constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
+constexpr uint32_t AGG_GRID = 1024;            /* workgroups of the candidate refine that aggregates in LDS */
+
+enum KernelId {
+    KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
+    KID_REFINE1, KID_PICK1, KID_REFINE2, KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE,
+    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_WHIST, KID_WPLAN, KID_WMASK, KID_N
+};
+const char *const kKernelNames[KID_N] = {
+    "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan", "fb_plan",
+    "refine1", "pick1", "refine2", "pick2", "count", "scan", "write",
+    "quant", "tilestart", "decomp", "decomp_acc", "whist", "wplan", "wmask"
+};
+static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
+
+/* Device-resident tables.  Layout part: fixed by the bucket offsets.  Call part: fixed by
+ * (ratio, bits).  State part: rewritten by every compress call. */
+struct Tables {
+    const uint64_t *off;     /* B+1 bucket offsets */
+    const uint32_t *tile0;   /* B+1 prefix of tile counts */
+    const uint32_t *span0;   /* B+1 prefix of span counts */
+    const uint32_t *samp0;   /* B+1 prefix of sample workgroups */
+    const uint32_t *span_b;  /* n_spans: bucket of each span */
+    uint32_t *k;             /* B   survivors per bucket */
+    uint64_t *P;             /* B+1 prefix of k */
+    uint64_t *V;             /* B+1 prefix of value bytes */
+    uint64_t *S;             /* B+1 prefix of scale counts */
+    uint64_t *C;             /* B+1 prefix of chunk counts (all widths) */
+    uint32_t *T;             /* B   threshold key, refined level by level */
+    uint32_t *need;          /* B   how many more to take at the current level */
+    uint32_t *L;             /* B   candidates are the elements with key >= L (NONE: no candidates) */
+    uint32_t *fast;          /* B   1: the candidates decide the bucket, 0: the dense fallback does */
+    uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
+    uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
+    uint32_t *margin;        /* B   history mode: how far below the last threshold key L is placed */
+    uint32_t *kw;            /* B   parameters the pruning step keeps (only with weights) */
+    const float *w;          /* weights when Algorithm 2 Step 2 is on, else NULL */
+    const uint32_t *wT;      /* B   with weights: threshold key of |w|; NONE: the bucket's mask is in the bitmap */
+    const uint32_t *wcut;    /* B   with weights: among parameters with key(w) == wT, those up to this
+                              *     bucket-local index are kept (kept: key > wT, or key == wT and index <= wcut) */
+    const uint32_t *pmask;   /* pruning bitmap, 128 words per tile, bit = pruned (buckets with wT = NONE) */
+    uint32_t B;
+    uint32_t n_spans;
+    uint32_t spanT;          /* tiles per span */
+    uint32_t segSh;          /* log2 of the staging segments per span (= wavefronts of the streaming pass) */
+    uint32_t chunk;
+};
+
+/* Candidate staging: segment ss = (span << segSh) + wavefront owns entries [ss * cap, ss * cap + cnt[ss]) */
+struct Cand {
+    uint32_t *idx;   /* bucket-local index */
+    float *val;      /* accumulator value */
+    uint32_t *cnt;   /* entries per segment */
+    uint32_t *G;     /* per segment: #(key > T), later its exclusive prefix inside the bucket */
+    uint32_t *E;     /* per segment: #(key == T), later its exclusive prefix */
+    uint32_t cap;    /* entries per segment: a quarter of the elements it covers */
+    uint32_t splitSh; /* log2 of the wavefronts that share a chunk of 64 segments in the candidate kernels */
+};
+
+typedef float f4 __attribute__((ext_vector_type(4)));   /* one aligned 16-byte access */
+
+__device__ __forceinline__ uint32_t keyof(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+/* largest b with pre[b] <= x; pre has B+1 non-decreasing entries and pre[B] > x */
+template <typename T>
+__device__ __forceinline__ uint32_t find_bucket(const T *__restrict__ pre, uint32_t B, T x)
+{
+    uint32_t lo = 0, hi = B;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (pre[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+struct SpanGeo {
+    uint32_t b;        /* bucket */
+    uint32_t ntiles;   /* tiles in this span */
+    uint32_t tile_g;   /* global id of the first tile */
+    uint64_t lo, hi;   /* bucket range */
+    uint64_t base;     /* aligned global element index where the first tile starts */
+};
+
+/* span number si of bucket b */
+__device__ __forceinline__ SpanGeo span_geo_b(const Tables &t, uint32_t b, uint32_t si)
+{
+    SpanGeo g;
+    g.b = b;
+    g.lo = t.off[b];
+    g.hi = t.off[b + 1];
+    const uint32_t tiles_b = t.tile0[b + 1] - t.tile0[b];
+    const uint32_t first = si * t.spanT;
+    g.ntiles = min(t.spanT, tiles_b - first);
+    g.tile_g = t.tile0[b] + first;
+    g.base = (g.lo & ~3ull) + (uint64_t)first * TILE;
+    return g;
+}
+
+/* global span s */
+__device__ __forceinline__ SpanGeo span_geo(const Tables &t, uint32_t s)
+{
+    const uint32_t b = t.span_b[s];
+    return span_geo_b(t, b, s - t.span0[b]);
+}
+
+/* The four pruning bits of quad `quad` (0..1023) of tile `tile_abs`. */
+__device__ __forceinline__ uint32_t pruned_bits(const uint32_t *__restrict__ pm, uint32_t tile_abs, uint32_t quad)
+{
+    return (pm[(uint64_t)tile_abs * (TILE / 32) + (quad >> 3)] >> ((quad & 7u) * 4u)) & 0xFu;
+}
+
+/* Load the quad at aligned element index gi, masking what lies outside [lo, hi).
+ * Returns the 4-bit validity mask. */
+__device__ __forceinline__ uint32_t load_quad(const float *__restrict__ p, uint64_t gi,
+                                              uint64_t lo, uint64_t hi, float (&x)[4])
+{
+    if (gi >= lo && gi + 4 <= hi) {
+        const f4 v = *reinterpret_cast<const f4 *>(p + gi);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        return 0xFu;
+    }
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        x[j] = 0.0f;
+        if (gi + j >= lo && gi + j < hi) { x[j] = p[gi + j]; m |= 1u << j; }
+    }
+    return m;
+}
+
+/* The four pruning bits (1 = pruned) of the quad at aligned element index gi, which is quad
+ * `quad` of tile `tile_abs`, in a bucket [lo, hi) whose weight threshold is wT and whose last
+ * kept index among the weights equal to the threshold is cut. */
+__device__ __forceinline__ uint32_t pruned_quad(const Tables &t, uint32_t wT, uint32_t cut, uint32_t tile_abs,
+                                                uint32_t quad, uint64_t gi, uint64_t lo, uint64_t hi)
+{
+    if (wT == 0xFFFFFFFFu) return pruned_bits(t.pmask, tile_abs, quad);
+    float x[4];
+    load_quad(t.w, gi, lo, hi, x);
+    const uint32_t li = (uint32_t)(gi - lo);        /* meaningless below lo: those lanes are masked anyway */
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t key = __float_as_uint(x[j]) & 0x7FFFFFFFu;
+        bits |= ((key < wT || (key == wT && li + j > cut)) ? 1u : 0u) << j;
+    }
+    return bits;
+}
+
+/* ------------------------------------------------------------------ setup / clear */
+
+__device__ __forceinline__ uint64_t survivors_dev(double ratio, uint64_t nb)
+{
+    if (nb == 0) return 0;
+    const double want = ceil(ratio * (double)nb);   /* one IEEE double product, then ceil */
+    if (want < 1.0) return 1;
+    if (want >= (double)nb) return nb;
+    return (uint64_t)want;
+}
+
+/* One workgroup: k_b and the four prefix tables for (ratio, bits, chunk). */
+__global__ __launch_bounds__(WG) void k_setup(Tables t, double ratio, int bits)
+{
+    __shared__ uint64_t part[4][WG];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t per = (t.B + WG - 1) / WG;
+    const uint32_t b0 = min(t.B, tid * per), b1 = min(t.B, b0 + per);
+    uint64_t sk = 0, sv = 0, ss = 0, sc = 0;
+    for (uint32_t b = b0; b < b1; ++b) {
+        const uint64_t k = survivors_dev(ratio, t.off[b + 1] - t.off[b]);
+        const uint64_t ch = (k + t.chunk - 1) / t.chunk;
+        sk += k;
+        sv += bits == 32 ? 4 * k : bits == 16 ? 2 * k : bits == 8 ? k : (k + 1) / 2;
+        ss += bits <= 8 ? ch : 0;
+        sc += ch;
+    }
+    part[0][tid] = sk; part[1][tid] = sv; part[2][tid] = ss; part[3][tid] = sc;
+    __syncthreads();
+    if (tid < 4) {
+        uint64_t run = 0;
+        for (int i = 0; i < WG; ++i) { const uint64_t x = part[tid][i]; part[tid][i] = run; run += x; }
+    }
+    __syncthreads();
+    uint64_t pk = part[0][tid], pv = part[1][tid], ps = part[2][tid], pc = part[3][tid];
+    for (uint32_t b = b0; b < b1; ++b) {
+        const uint64_t k = survivors_dev(ratio, t.off[b + 1] - t.off[b]);
+        const uint64_t ch = (k + t.chunk - 1) / t.chunk;
+        t.k[b] = (uint32_t)k;
+        {   /* Algorithm 2 Step 2: floor(0.5 * (1 - ratio) * n_b) parameters are pruned */
+            const uint64_t nb = t.off[b + 1] - t.off[b];
+            const double np = floor(0.5 * (1.0 - ratio) * (double)nb);
+            t.kw[b] = (uint32_t)(nb - (uint64_t)(np < 0.0 ? 0.0 : np));
+        }
+        t.P[b] = pk; t.V[b] = pv; t.S[b] = ps; t.C[b] = pc;
+        pk += k;
+        pv += bits == 32 ? 4 * k : bits == 16 ? 2 * k : bits == 8 ? k : (k + 1) / 2;
+        ps += bits <= 8 ? ch : 0;
+        pc += ch;
+        if (b == t.B - 1) { t.P[t.B] = pk; t.V[t.B] = pv; t.S[t.B] = ps; t.C[t.B] = pc; }
+    }
+}
+
+/* span -> bucket map, once per bucket layout */
+__global__ __launch_bounds__(WG) void k_spanmap(const uint32_t *__restrict__ span0, uint32_t B,
+                                                uint32_t n_spans, uint32_t *__restrict__ span_b)
+{
+    const uint32_t s = blockIdx.x * WG + threadIdx.x;
+    if (s < n_spans) span_b[s] = find_bucket<uint32_t>(span0, B, s);
+}
+
+__global__ __launch_bounds__(WG) void k_clear(uint32_t *__restrict__ p, uint64_t n)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * WG;
+    for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+__global__ __launch_bounds__(WG) void k_fill_u32(uint32_t *__restrict__ p, uint32_t n, uint32_t v)
+{
+    const uint32_t i = blockIdx.x * WG + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+/* Plain 16-byte copy, the yardstick for the profiler's HBM byte counters. */
+__global__ __launch_bounds__(WG) void k_calib_copy(const f4 *__restrict__ src, f4 *__restrict__ dst, uint64_t n16)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * WG;
+    for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+/* ------------------------------------------------------------------ histograms */
+
+/* Add the four level digits of a quad to an LDS histogram.  When every lane of the wavefront
+ * carries the same digit in all four slots (runs of zeros, saturated buckets) one lane adds
+ * the whole count: same-address LDS atomics of a wavefront serialise.  All 64 lanes must be
+ * active. */
+__device__ __forceinline__ void hist_quad_full(uint32_t *h, uint32_t d0, uint32_t d1,
+                                               uint32_t d2, uint32_t d3)
+{
+    const uint32_t f = __builtin_amdgcn_readfirstlane(d0);
+    const bool same = (d0 == f) & (d1 == f) & (d2 == f) & (d3 == f);
+    if (__all(same)) {
+        if ((threadIdx.x & 63) == 0) atomicAdd(&h[f], 256u);
+    } else {
+        atomicAdd(&h[d0], 1u); atomicAdd(&h[d1], 1u); atomicAdd(&h[d2], 1u); atomicAdd(&h[d3], 1u);
+    }
+}
+
+__device__ __forceinline__ void hist_flush(const uint32_t *h, uint32_t *__restrict__ dst, int nb,
+                                           int nthreads = WG)
+{
+    for (int i = threadIdx.x; i < nb; i += nthreads) {
+        const uint32_t c = h[i];
+        if (c) atomicAdd(&dst[i], c);
+    }
+}
+
+/* Inclusive scan over the 256 threads of a workgroup: shuffles inside each wavefront, one
+ * exchange of the four wavefront totals through LDS.  tmp needs WG words; on return
+ * tmp[WG - 1] holds the grand total (callers read it, then synchronise before reusing tmp). */
+__device__ __forceinline__ uint32_t block_incl_scan(uint32_t x, uint32_t *tmp)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, 64);
+        if (lane >= (uint32_t)d) x += y;
+    }
+    if (lane == 63) tmp[wave] = x;
+    __syncthreads();
+    uint32_t add = 0;
+#pragma unroll
+    for (int w = 0; w < WG / 64; ++w) add += (uint32_t)w < wave ? tmp[w] : 0u;
+    const uint32_t total = tmp[0] + tmp[1] + tmp[2] + tmp[3];
+    __syncthreads();
+    x += add;
+    if (tid == WG - 1) tmp[WG - 1] = total;
+    __syncthreads();
+    return x;
+}
+
+/* A histogram row seen from the top digit down: thread 0 owns the highest digits. */
+template <int NB>
+struct DigitWalk {
+    static constexpr int PER = NB >= WG ? NB / WG : 1;
+    uint32_t c[PER];
+    uint32_t sum, incl, total;
+    int top;
+
+    /* every thread of the workgroup must call this (it synchronises) */
+    __device__ __forceinline__ void load(const uint32_t *__restrict__ hb, uint32_t *tmp)
+    {
+        top = NB - 1 - (int)threadIdx.x * PER;
+        sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int d = top - i;
+            c[i] = d >= 0 ? hb[d] : 0u;
+            sum += c[i];
+        }
+        incl = block_incl_scan(sum, tmp);
+        total = tmp[WG - 1];
+        __syncthreads();
+    }
+    /* The digit holding the want-th largest entry (1 <= want <= total): exactly one thread
+     * returns true, with the digit, the number of entries in higher digits, and the number
+     * in the digit itself. */
+    __device__ __forceinline__ bool find(uint32_t want, uint32_t &digit, uint32_t &above,
+                                         uint32_t &at) const
+    {
+        const uint32_t before = incl - sum;
+        if (!(before < want && want <= incl)) return false;
+        uint32_t acc = before;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (acc + c[i] >= want) { digit = (uint32_t)(top - i); above = acc; at = c[i]; return true; }
+            acc += c[i];
+        }
+        return false;
+    }
+};
+
+}  // namespace
+
+#endif
