@@ -19,17 +19,24 @@ __global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const
                                               float *__restrict__ scales)
 {
     __shared__ float red[WG / 64];
+    __shared__ uint32_t sh_b;
     const uint32_t tid = threadIdx.x;
     const uint64_t c = blockIdx.x;
-    const uint32_t b = find_bucket<uint64_t>(t.C, t.B, c);
+    const uint32_t b = find_bucket_wg<uint64_t>(t.C, t.B, c, &sh_b);
     const uint64_t cb = c - t.C[b];
     const uint64_t j0 = cb * t.chunk;                         /* first survivor of the chunk, bucket-local */
     const uint32_t cnt = (uint32_t)min((uint64_t)t.chunk, (uint64_t)t.k[b] - j0);
     const uint64_t jg = t.P[b] + j0;                          /* same, global */
     const uint64_t lo = t.off[b];
+    uint8_t *vb = reinterpret_cast<uint8_t *>(val) + t.V[b];
+    /* A thread takes pairs of consecutive survivors (so a 4-bit pair is one byte store), up to
+     * four pairs per block of 2048; the values and indices of a block are fetched before any is
+     * used.  A chunk of up to 2048 is one block and its values are read once; a longer chunk
+     * first takes its absmax in a pass of its own. */
+    constexpr uint32_t BLK = WG * 8;
+    const bool one_block = cnt <= BLK;
     float scale = 0.0f;
-    if (BITS <= 8) {
-        constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+    if (BITS <= 8 && !one_block) {
         float m = 0.0f;
         for (uint32_t i = tid; i < cnt; i += WG) m = fmaxf(m, fabsf(v[jg + i]));
 #pragma unroll
@@ -37,39 +44,70 @@ __global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const
         if ((tid & 63) == 0) red[tid >> 6] = m;
         __syncthreads();
         m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
         scale = m == 0.0f ? 0.0f : __fdiv_rn(m, QMAX);
         if (tid == 0) scales[t.S[b] + cb] = scale;
     }
-    uint8_t *vb = reinterpret_cast<uint8_t *>(val) + t.V[b];
-    /* two survivors per thread per round, so a 4-bit pair is one byte store */
-    for (uint32_t p = tid; 2 * p < cnt; p += WG) {
-        float res[2];
-        int q[2] = {0, 0};
-        const uint32_t i0 = 2 * p;
-        const int have = (i0 + 1 < cnt) ? 2 : 1;
-        for (int h = 0; h < have; ++h) {
-            const float x = v[jg + i0 + h];
-            float deq;
-            if (BITS == 32) {
-                deq = x;
-            } else if (BITS == 16) {
-                const __half hv = __float2half_rn(x);
-                reinterpret_cast<__half *>(vb)[j0 + i0 + h] = hv;
-                deq = __half2float(hv);
-            } else {
-                constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
-                if (scale != 0.0f) {
-                    float tq = rintf(__fdiv_rn(x, scale));
-                    tq = fminf(fmaxf(tq, -QMAX), QMAX);
-                    q[h] = (int)tq;
-                }
-                deq = __fmul_rn((float)q[h], scale);
-                if (BITS == 8) reinterpret_cast<int8_t *>(vb)[j0 + i0 + h] = (int8_t)q[h];
+    for (uint32_t b0 = 0; b0 < cnt; b0 += BLK) {
+        float x[4][2];
+        uint32_t li[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const uint32_t i = b0 + 2 * (tid + u * WG) + hh;
+                x[u][hh] = i < cnt ? v[jg + i] : 0.0f;
+                li[u][hh] = i < cnt ? idx[jg + i] : 0u;
             }
-            res[h] = __fsub_rn(x, deq);
         }
-        if (BITS == 4) vb[(j0 >> 1) + p] = (uint8_t)((q[0] & 0xF) | ((q[1] & 0xF) << 4));
-        for (int h = 0; h < have; ++h) r[lo + idx[jg + i0 + h]] = res[h];
+        if (BITS <= 8 && one_block) {
+            float m = 0.0f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) m = fmaxf(m, fmaxf(fabsf(x[u][0]), fabsf(x[u][1])));   /* absent ones are 0 */
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+            if ((tid & 63) == 0) red[tid >> 6] = m;
+            __syncthreads();
+            m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+            constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+            scale = m == 0.0f ? 0.0f : __fdiv_rn(m, QMAX);
+            if (tid == 0) scales[t.S[b] + cb] = scale;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i0 = b0 + 2 * (tid + u * WG);
+            if (i0 >= cnt) continue;
+            const int have = (i0 + 1 < cnt) ? 2 : 1;
+            float res[2] = {0.0f, 0.0f};
+            int q[2] = {0, 0};
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                if (hh >= have) continue;
+                const float xv = x[u][hh];
+                float deq;
+                if (BITS == 32) {
+                    deq = xv;
+                } else if (BITS == 16) {
+                    const __half hv = __float2half_rn(xv);
+                    reinterpret_cast<__half *>(vb)[j0 + i0 + hh] = hv;
+                    deq = __half2float(hv);
+                } else {
+                    constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+                    if (scale != 0.0f) {
+                        float tq = rintf(__fdiv_rn(xv, scale));
+                        tq = fminf(fmaxf(tq, -QMAX), QMAX);
+                        q[hh] = (int)tq;
+                    }
+                    deq = __fmul_rn((float)q[hh], scale);
+                    if (BITS == 8) reinterpret_cast<int8_t *>(vb)[j0 + i0 + hh] = (int8_t)q[hh];
+                }
+                res[hh] = __fsub_rn(xv, deq);
+            }
+            if (BITS == 4) vb[(j0 + i0) >> 1] = (uint8_t)((q[0] & 0xF) | ((q[1] & 0xF) << 4));
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                if (hh < have) r[lo + li[u][hh]] = res[hh];
+        }
     }
 }
 

@@ -93,6 +93,27 @@ __device__ __forceinline__ uint32_t find_bucket(const T *__restrict__ pre, uint3
     return lo;
 }
 
+/* The same search done by a whole workgroup of 256 threads, 256 ways at a time: one or two
+ * rounds of independent probes instead of a chain of dependent ones.  Every thread must call
+ * it; sh is one word of LDS; returns the same value in every thread. */
+template <typename T>
+__device__ __forceinline__ uint32_t find_bucket_wg(const T *__restrict__ pre, uint32_t B, T x, uint32_t *sh)
+{
+    uint32_t lo = 0, hi = B;                 /* pre[lo] <= x < pre[hi] */
+    while (hi - lo > 1) {
+        const uint32_t step = (hi - lo + 255u) / 256u;
+        const uint32_t p = lo + threadIdx.x * step, q = p + step;
+        /* thread t owns [p, q) clipped to hi; exactly one thread's range holds the answer */
+        if (p < hi && pre[p] <= x && (q >= hi || x < pre[q])) *sh = p;
+        __syncthreads();
+        const uint32_t np = *sh;
+        __syncthreads();
+        lo = np;
+        hi = np + step < hi ? np + step : hi;
+    }
+    return lo;
+}
+
 struct SpanGeo {
     uint32_t b;        /* bucket */
     uint32_t ntiles;   /* tiles in this span */
