@@ -198,12 +198,13 @@ __global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ i
     }
 }
 
-/* Dense output for a span of tiles: each tile is assembled in LDS (zeros, then the decoded
+/* Dense output for a span of tiles, the variant for gradients of up to a few hundred million
+ * elements (256 threads): each tile is assembled in LDS (zeros, then the decoded
  * survivors that fall inside it, found through the tile-start table) and written out once with
  * aligned 16-byte stores, so no output line is touched twice and no atomics are needed.  The
  * loads of the next tile's survivors are issued before the current tile is written out. */
 template <int BITS, bool NTS>
-__global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx, const void *__restrict__ val,
+__global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ idx, const void *__restrict__ val,
                                                const float *__restrict__ scales, Tables t,
                                                const uint32_t *__restrict__ ts, float *__restrict__ dense)
 {
@@ -265,6 +266,78 @@ __global__ __launch_bounds__(WG) void k_decomp(const uint32_t *__restrict__ idx,
                 for (int j = 0; j < 4; ++j)
                     if (gi + j >= s.lo && gi + j < s.hi) dense[gi + j] = tile[sl + j];
             }
+        }
+    }
+}
+
+/* Dense output for a span of tiles, the variant for the largest gradients: one wavefront per
+ * tile (64 x spanT threads).  A wavefront
+ * first fetches its tile's survivors (found through the tile-start table), then writes the
+ * tile's 16 KiB of zeros with aligned 16-byte stores, one contiguous KiB per instruction, waits
+ * for those stores, and drops the decoded survivors into place.  Both writes to a survivor's
+ * line meet in the cache, so the memory sees each output line once; no LDS, no atomics.  (The
+ * wait is what orders the two stores to one address: they come from different lanes.) */
+template <int BITS, bool NTS>
+__global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_decomp(const uint32_t *__restrict__ idx, const void *__restrict__ val,
+                                                               const float *__restrict__ scales, Tables t,
+                                                               const uint32_t *__restrict__ ts, float *__restrict__ dense)
+{
+    constexpr int U = 2;                     /* survivors per lane fetched ahead of the zeros */
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
+    const SpanGeo s = span_geo(t, blockIdx.x);
+    const uint32_t kb = t.k[s.b];
+    const uint32_t *ib = idx + t.P[s.b];
+    const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[s.b];
+    const float *sb = BITS <= 8 ? scales + t.S[s.b] : nullptr;
+    const uint32_t nb = (uint32_t)(s.hi - s.lo);
+    const uint32_t *tsb = ts + t.tile0[s.b] + s.b + (s.tile_g - t.tile0[s.b]);
+    const f4 z = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t ti = wave; ti < s.ntiles; ti += n_waves) {
+        const uint64_t tb = s.base + (uint64_t)ti * TILE;
+        const uint64_t shift = s.lo - tb;                   /* slot in the tile = local index + lo - tb (mod 2^64) */
+        const uint32_t j0 = min(tsb[ti], kb), j1 = min(tsb[ti + 1], kb);
+        uint32_t p_li[U];
+        float p_x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t j = (uint64_t)j0 + lane + 64u * u;
+            p_li[u] = NONE;
+            p_x[u] = 0.0f;
+            if (j < j1) { p_li[u] = ib[j]; p_x[u] = decode<BITS>(vb, sb, j, t.chunk); }
+        }
+        if (tb >= s.lo && tb + TILE <= s.hi) {
+#pragma unroll
+            for (int u = 0; u < TILE / 256; ++u) {
+                f4 *a = reinterpret_cast<f4 *>(dense + tb + (uint64_t)(u * 64 + lane) * 4);
+                if (NTS) __builtin_nontemporal_store(z, a);
+                else *a = z;
+            }
+        } else {
+            for (int u = 0; u < TILE / 256; ++u) {
+                const uint64_t gi = tb + (uint64_t)(u * 64 + lane) * 4;
+                if (gi >= s.lo && gi + 4 <= s.hi) {
+                    *reinterpret_cast<f4 *>(dense + gi) = z;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (gi + j >= s.lo && gi + j < s.hi) dense[gi + j] = 0.0f;
+                }
+            }
+        }
+        /* the zeros must have landed before a survivor is stored over one of them */
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            /* an index outside the bucket or outside this tile (invalid payload) is dropped */
+            const uint64_t slot = (uint64_t)p_li[u] + shift;
+            if (p_li[u] < nb && slot < TILE) dense[s.lo + p_li[u]] = p_x[u];
+        }
+        for (uint64_t j = (uint64_t)j0 + 64u * U + lane; j < j1; j += 64) {
+            const uint32_t li = ib[j];
+            const uint64_t slot = (uint64_t)li + shift;
+            if (li < nb && slot < TILE) dense[s.lo + li] = decode<BITS>(vb, sb, j, t.chunk);
         }
     }
 }

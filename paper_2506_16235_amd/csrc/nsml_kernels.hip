@@ -104,7 +104,7 @@ struct nsml_ctx {
     int agg_override;      /* level-1 candidate histogram aggregated in LDS: 1 always, 0 never, -1 by size */
     int force_dense;
     int nt_mode;
-    int nt_dense;          /* non-temporal stores for the dense output of decompress */
+    int nt_dense;          /* non-temporal stores for the dense output of decompress: 1, 0, or -1 = by variant */
     int use_history;       /* place the candidate bound from the previous call's thresholds */
     bool hist_ready; double hist_ratio; bool hist_pruned;
     uint32_t *d_margin;
@@ -371,7 +371,7 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     const char *ntm = getenv("NSML_NT");
     c->nt_mode = ntm ? atoi(ntm) : 7;
     const char *nd = getenv("NSML_NT_DENSE");
-    c->nt_dense = nd ? (atoi(nd) != 0) : 1;
+    c->nt_dense = nd ? (atoi(nd) != 0 ? 1 : 0) : -1;     /* -1: each variant's own default */
     const char *hs = getenv("NSML_HISTORY");
     /* off by default: while error feedback is still building up, thresholds climb from step to
      * step and bounds taken from the previous step let in about twice the candidates a fresh
@@ -649,19 +649,38 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
         LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, c->K, c->d_ts);
     }
     const uint32_t *ts = c->d_ts;
-    if (c->nt_dense) {
+    if (c->spanT >= MAX_SPAN_TILES) {
+        /* the largest gradients: one wavefront per tile, direct stores (plain unless asked otherwise) */
+        const uint32_t dblock = 64u * c->spanT;
+        if (c->nt_dense > 0) {
+            switch (bits) {
+            case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, true>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 16: LAUNCHB(c, KID_DECOMP, st, (k_decomp<16, true>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 8:  LAUNCHB(c, KID_DECOMP, st, (k_decomp<8, true>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            default: LAUNCHB(c, KID_DECOMP, st, (k_decomp<4, true>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            }
+        } else {
+            switch (bits) {
+            case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, false>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 16: LAUNCHB(c, KID_DECOMP, st, (k_decomp<16, false>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 8:  LAUNCHB(c, KID_DECOMP, st, (k_decomp<8, false>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            default: LAUNCHB(c, KID_DECOMP, st, (k_decomp<4, false>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            }
+        }
+    } else if (c->nt_dense != 0) {
+        /* smaller gradients: tiles assembled in LDS, non-temporal stores unless asked otherwise */
         switch (bits) {
-        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp<32, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp<16, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp<8, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        default: LAUNCH(c, KID_DECOMP, st, (k_decomp<4, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<32, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<16, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<8, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        default: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<4, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
         }
     } else {
         switch (bits) {
-        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp<32, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp<16, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp<8, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        default: LAUNCH(c, KID_DECOMP, st, (k_decomp<4, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<32, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<16, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<8, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
+        default: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<4, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
         }
     }
     return NSML_OK;
