@@ -176,6 +176,42 @@ def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
     c.step(0.004, 4)
 
 
+@pytest.mark.parametrize("span_tiles", [0, 16])
+@pytest.mark.parametrize("bits", [4, 8, 16, 32])
+def test_decompress_of_a_malformed_index_list_stays_inside_the_output(monkeypatch, span_tiles, bits):
+    """The kernels bound every index they are handed: a payload whose index list is not what
+    compress writes (out of range, descending, repeated) gives unspecified values, but nothing
+    outside the dense buffer is touched (sentinels on both sides stay intact), with both
+    decompress variants and with decompress-accumulate."""
+    if span_tiles:
+        monkeypatch.setenv("NSML_SPAN_TILES", str(span_tiles))
+    sizes = [70_001, 3, 150_000, 0, 40_961]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    ratio = 0.05
+    ctx = nsml.Context(n, len(sizes), 256)
+    idx, val, sc = ctx.alloc_payload(off, ratio, bits)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99 + bits)
+    pad = 8192
+    for trial in range(3):
+        raw = torch.randint(0, 2**31 - 1, (idx.numel(),), generator=gen, device=DEV, dtype=torch.int64)
+        if trial == 1:
+            raw = raw % 200_000                      # mostly inside some bucket, unordered, repeated
+        if trial == 2:
+            raw = torch.full_like(raw, -1)           # 0xFFFFFFFF everywhere
+        idx.copy_(raw.to(idx.dtype))
+        val.copy_(torch.randint(0, 256, (val.numel(),), generator=gen, device=DEV, dtype=torch.int64).to(val.dtype))
+        if sc.numel():
+            sc.copy_(torch.rand(sc.numel(), generator=gen, device=DEV))
+        buf = torch.full((n + 2 * pad,), 7.0, device=DEV)
+        dense = buf[pad:pad + n]
+        ctx.decompress(idx, val, sc, n, off, ratio, bits, dense)
+        ctx.decompress_accumulate(idx, val, sc, off, ratio, bits, dense)
+        torch.cuda.synchronize()
+        assert bool((buf[:pad] == 7.0).all()) and bool((buf[pad + n:] == 7.0).all())
+
+
 def test_same_input_twice_gives_identical_bytes():
     """Determinism (the practical race detector): two runs, byte-identical outputs."""
     sizes = [300_000, 17, 200_003]
