@@ -8,7 +8,7 @@
  *   nsml_compress       GPU    Sec. 4.2 Step 3 / Algorithm 2 Step 3: local accumulation
  *                              (error feedback), exact top-k by magnitude, then the value
  *                              coding and index/value/scale payload of the build contract
- *   nsml_decompress     GPU    receiver side of "transmit the sparsified gradient":
+ *   nsml_decompress     GPU    receiver side of Algorithm 2 Step 3's transmission:
  *                              payload -> dense gradient
  *
  * Conventions
@@ -63,7 +63,7 @@ typedef struct nsml_ctl_params {
     double init;        /* 0.01  initial ratio, Algorithm 1 Step 1 */
     double bdp_frac;    /* 0.9   congestion trigger as a fraction of BDP, Eq. (3) */
     double rtt_excess;  /* 2.0   start-up ends when the last transmission time exceeds this
-                                 multiple of RTprop ("excessive RTT") */
+                                 multiple of RTprop (the RTT criterion of Sec. 4.1) */
     double tr_q;        /* 0.1   Algorithm 2 Step 1: quantize when ratio < tr_q ... */
     double tr_q4;       /* 0.01  ... with 4-bit codes when ratio < tr_q4 (quant_mode 0) */
     double tr_d;        /* 0.0   ... and the gradient L2 norm exceeds tr_d */

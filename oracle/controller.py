@@ -1,16 +1,16 @@
 """Oracle for the network-sensing controller -- TEST INFRASTRUCTURE.
 
-Algorithm 1 ("Network Status Sensing and Adaptive Compression Ratio
-Adjustment") with Eq. (1) EBB = data_size / RTT, Eq. (2) BDP = BtlBw * RTprop
-and Eq. (3) the ratio update, followed by the gate of Algorithm 2 Step 1
-("Adaptive Quantization") that decides the value width for the step.
+Algorithm 1 (network sensing and ratio adjustment) with Eq. (1) EBB =
+data_size / RTT, Eq. (2) BDP = BtlBw * RTprop and Eq. (3) the ratio update,
+followed by the gate of Algorithm 2 Step 1 (the quantization step) that
+decides the value width for the step.
 
 Python floats are IEEE doubles, so every +, *, /, max, min below is the same
 operation a C double would perform.
 
 Readings where the paper is silent (each also listed in the design notes):
   * beta1 (start-up increment) is not printed; 0.1 = 10 * beta2 is used.
-  * "excessive RTT" that ends start-up: the last transmission time exceeds
+  * the RTT criterion that ends start-up (Sec. 4.1 gives no number): the last transmission time exceeds
     rtt_excess * RTprop, rtt_excess = 2 (the only figure the paper gives for an
     RTT-reactive trigger, in its discussion of MLT); start-up also ends after
     startup_max steps or when the ratio reaches its cap.  On the call that ends
@@ -38,9 +38,9 @@ STARTUP, NETSENSE = 0, 1
 
 @dataclass
 class CtlParams:
-    alpha: float = 0.5        # Eq. (3), Sec. 4.1 "alpha is 0.5"
+    alpha: float = 0.5        # Eq. (3); value printed in Sec. 4.1
     beta1: float = 0.1        # Algorithm 1 Step 1 (value not printed)
-    beta2: float = 0.01       # Eq. (3), Sec. 4.1 "beta2 is 0.01"
+    beta2: float = 0.01       # Eq. (3); value printed in Sec. 4.1
     floor: float = 0.005      # Eq. (3) lower bound
     cap: float = 1.0          # Eq. (3) upper bound
     init: float = 0.01        # Algorithm 1 Step 1 initial ratio

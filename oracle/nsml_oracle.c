@@ -3,8 +3,8 @@
  *
  * A plain, slow, single-pass-per-definition CPU statement of what one
  * NetSenseML worker does to its own gradient before communication
- * (NetSenseCompression, Algorithm 2, Step 3 "Gradient Sparsification" with the
- * local accumulation of the filtered part described in Sec. 4.2 Step 3), plus
+ * (Algorithm 2 Step 3, the sparsification step, with the local accumulation of
+ * the filtered part described in Sec. 4.2 Step 3), plus
  * the low-bit value coding, the index/value/scale payload and the inverse
  * decompress-and-scatter that the build contract adds around it.
  *

@@ -159,11 +159,53 @@ def _stream(device) -> C.c_void_p:
     return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
 
 
+def validate_buffers(device, bucket_off, ratio, bits, chunk, *, n=None, grad=None, residual=None,
+                     weights=None, idx=None, val=None, scales=None, dense=None):
+    """The C ABI carries no capacities, so the sizes, types and placement of every tensor are
+    checked here, before a pointer reaches a kernel: a short buffer would be an out-of-bounds
+    device write.  Raises ValueError; returns (K, val_bytes, n_scales)."""
+    device = torch.device(device)
+    off = _off(bucket_off)
+    if off.ndim != 1 or len(off) < 2:
+        raise ValueError("bucket_off needs at least two entries")
+    total = int(off[-1])
+    if n is not None and int(n) != total:
+        raise ValueError(f"n = {n} but bucket_off ends at {total}")
+    _, K, vb, ns = payload_layout(off, ratio, bits, chunk)
+
+    def want(name, t, dtype, numel, exact):
+        if t is None:
+            return
+        if not isinstance(t, torch.Tensor):
+            raise ValueError(f"{name} must be a torch tensor")
+        if t.device != device:
+            raise ValueError(f"{name} is on {t.device}, the context is on {device}")
+        if t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+            raise ValueError(f"{name} has dtype {t.dtype}")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} is not contiguous")
+        if (t.numel() != numel) if exact else (t.numel() < numel):
+            raise ValueError(f"{name} holds {t.numel()} elements, needs {'exactly' if exact else 'at least'} {numel}")
+
+    want("grad", grad, torch.float32, total, True)
+    want("residual", residual, torch.float32, total, True)
+    want("weights", weights, torch.float32, total, True)
+    want("dense", dense, torch.float32, total, True)
+    want("idx", idx, (torch.int32, torch.uint32), K, False)
+    want("val", val, (torch.uint8, torch.int8), vb, False)
+    if bits <= 8:
+        if (idx is not None or val is not None) and scales is None:
+            raise ValueError("scales is required for 8- and 4-bit codes")
+        want("scales", scales, torch.float32, ns, False)
+    return K, vb, ns
+
+
 class Context:
     """nsml_ctx: device workspace for gradients of up to max_n elements / max_buckets buckets."""
 
     def __init__(self, max_n: int, max_buckets: int = 1, chunk: int = 2048, device: int = 0):
         self.device, self.chunk = int(device), int(chunk)
+        self._dev = torch.device("cuda", self.device)
         self._h = _vp()
         rc = _lib.nsml_create(C.byref(self._h), self.device, int(max_n), int(max_buckets), self.chunk)
         if rc != OK:
@@ -201,8 +243,8 @@ class Context:
         off = _off(bucket_off)
         if idx is None:
             idx, val, scales = self.alloc_payload(off, ratio, bits)
-        assert grad.dtype == torch.float32 and residual.dtype == torch.float32
-        assert grad.is_contiguous() and residual.is_contiguous()
+        validate_buffers(self._dev, off, ratio, bits, self.chunk, grad=grad, residual=residual,
+                         idx=idx, val=val, scales=scales)
         rc = _lib.nsml_compress(self._h, _ptr(grad), _ptr(residual), grad.numel(), off.ctypes.data,
                                 len(off) - 1, float(ratio), int(bits), _ptr(idx), _ptr(val),
                                 _ptr(scales), _stream(self.device))
@@ -216,9 +258,8 @@ class Context:
         off = _off(bucket_off)
         if idx is None:
             idx, val, scales = self.alloc_payload(off, ratio, bits)
-        assert grad.dtype == residual.dtype == weights.dtype == torch.float32
-        assert grad.is_contiguous() and residual.is_contiguous() and weights.is_contiguous()
-        assert weights.numel() == grad.numel()
+        validate_buffers(self._dev, off, ratio, bits, self.chunk, grad=grad, residual=residual,
+                         weights=weights, idx=idx, val=val, scales=scales)
         rc = _lib.nsml_compress_pruned(self._h, _ptr(grad), _ptr(residual), _ptr(weights), grad.numel(),
                                        off.ctypes.data, len(off) - 1, float(ratio), int(bits),
                                        _ptr(idx), _ptr(val), _ptr(scales), _stream(self.device))
@@ -229,7 +270,9 @@ class Context:
                    bucket_off, ratio: float, bits: int, out: torch.Tensor = None) -> torch.Tensor:
         off = _off(bucket_off)
         if out is None:
-            out = torch.empty(int(n), dtype=torch.float32, device=torch.device("cuda", self.device))
+            out = torch.empty(int(n), dtype=torch.float32, device=self._dev)
+        validate_buffers(self._dev, off, ratio, bits, self.chunk, n=n, idx=idx, val=val, scales=scales,
+                         dense=out)
         rc = _lib.nsml_decompress(self._h, _ptr(idx), _ptr(val), _ptr(scales), int(n),
                                   off.ctypes.data, len(off) - 1, float(ratio), int(bits),
                                   _ptr(out), _stream(self.device))
@@ -240,7 +283,8 @@ class Context:
                               dense: torch.Tensor) -> torch.Tensor:
         """dense[bucket_off[b] + idx[j]] += decoded value j, in place."""
         off = _off(bucket_off)
-        assert dense.dtype == torch.float32 and dense.is_contiguous()
+        validate_buffers(self._dev, off, ratio, bits, self.chunk, idx=idx, val=val, scales=scales,
+                         dense=dense)
         rc = _lib.nsml_decompress_accumulate(self._h, _ptr(idx), _ptr(val), _ptr(scales),
                                              dense.numel(), off.ctypes.data, len(off) - 1,
                                              float(ratio), int(bits), _ptr(dense), _stream(self.device))

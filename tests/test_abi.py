@@ -131,3 +131,42 @@ def test_create_rejects_bad_arguments():
     assert lib.nsml_prune_stats(None, C.byref(a), C.byref(b)) == nsml.EINVAL
     assert lib.nsml_compress_pruned(None, None, None, None, 0, None, 0, 0.5, 8, None, None, None, None) == nsml.EINVAL
     assert lib.nsml_decompress_accumulate(None, None, None, None, 0, None, 0, 0.5, 8, None, None) == nsml.EINVAL
+
+
+def test_binding_rejects_wrong_buffers_before_any_kernel():
+    """The C ABI carries no capacities: the binding must refuse short, misplaced or mistyped
+    tensors itself (CPU tensors stand in for device tensors; only the checks run here)."""
+    off = W.offsets_of([1000, 0, 3000])
+    n, ratio, bits, chunk = 4000, 0.1, 8, 2048
+    k_b, K, vb, ns = nsml.payload_layout(off, ratio, bits, chunk)
+    cpu = torch.device("cpu")
+    good = dict(grad=torch.zeros(n), residual=torch.zeros(n), idx=torch.zeros(K, dtype=torch.int32),
+                val=torch.zeros(vb, dtype=torch.uint8), scales=torch.zeros(ns))
+    assert nsml.validate_buffers(cpu, off, ratio, bits, chunk, **good) == (K, vb, ns)
+    bad = [
+        dict(good, residual=torch.zeros(n - 1)),                       # residual shorter than grad
+        dict(good, grad=torch.zeros(n + 4)),                           # grad does not match the layout
+        dict(good, idx=torch.zeros(K - 1, dtype=torch.int32)),         # idx too short
+        dict(good, val=torch.zeros(vb - 1, dtype=torch.uint8)),        # val too short
+        dict(good, scales=torch.zeros(ns - 1)),                        # scales too short
+        dict(good, scales=None),                                       # scales missing for 8-bit codes
+        dict(good, grad=torch.zeros(n, dtype=torch.float64)),          # wrong dtype
+        dict(good, idx=torch.zeros(K, dtype=torch.int64)),
+        dict(good, residual=torch.zeros(2 * n)[::2]),                  # not contiguous
+    ]
+    for kw in bad:
+        with pytest.raises(ValueError):
+            nsml.validate_buffers(cpu, off, ratio, bits, chunk, **kw)
+    # decompress side: the dense output must have exactly n elements, n must match the layout
+    with pytest.raises(ValueError):
+        nsml.validate_buffers(cpu, off, ratio, bits, chunk, n=n, dense=torch.zeros(n - 1), idx=good["idx"],
+                              val=good["val"], scales=good["scales"])
+    with pytest.raises(ValueError):
+        nsml.validate_buffers(cpu, off, ratio, bits, chunk, n=n + 1, dense=torch.zeros(n + 1))
+    # another device than the context's
+    with pytest.raises(ValueError):
+        nsml.validate_buffers(torch.device("cuda", 0), off, ratio, bits, chunk, **good)
+    # 32-bit values need no scales
+    k_b, K, vb, ns = nsml.payload_layout(off, ratio, 32, chunk)
+    nsml.validate_buffers(cpu, off, ratio, 32, chunk, idx=torch.zeros(K, dtype=torch.int32),
+                          val=torch.zeros(vb, dtype=torch.uint8), scales=None)

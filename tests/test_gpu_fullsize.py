@@ -128,7 +128,10 @@ def test_cfg3_bert_full(ratio, bits):
 
 def test_cfg4_llama7b_full_sampled():
     """Configuration 4: 6,738,415,616 elements in 258 buckets of 25 Mi, ratio 0.001, int4,
-    residual carried over 3 steps; oracle chain on buckets 0, 131 and 257 (the short one)."""
+    residual carried over 3 steps.  The oracle runs its own chain on buckets 0, 131 and 257 (the
+    short one) over all three steps, and on the first step also on seven more spread over the
+    gradient, among them buckets whose spans of 16 tiles straddle a bucket boundary's neighbours
+    (the last full bucket, 1, 64, 128, 192, 255)."""
     off = W.llama7b_bucket_offsets()
     n = int(off[-1])
     g = torch.empty(n, dtype=torch.float32, device=DEV)
@@ -137,6 +140,7 @@ def test_cfg4_llama7b_full_sampled():
     ctx = nsml.Context(n, len(off) - 1, 2048)
     idx, val, sc = ctx.alloc_payload(off, 0.001, 4)
     sb = SampledBuckets(off, [0, 131, 257])
+    sb_first = SampledBuckets(off, [1, 37, 64, 128, 192, 255, 256])
     for step in range(3):
         say("cfg4 step", step, "generate")
         W.llama7b_grad(step, DEV, out=g)
@@ -151,6 +155,9 @@ def test_cfg4_llama7b_full_sampled():
         assert fast >= 250
         say("cfg4 step", step, "oracle")
         sb.check(g, r, idx, val, sc, dense, 0.001, 4)
+        if step == 0:
+            say("cfg4 step 0: oracle on seven more buckets")
+            sb_first.check(g, r, idx, val, sc, dense, 0.001, 4)
     say("cfg4 properties")
     acc = g.add_(r_before)              # g is not needed any more; saves 27 GB
     del r_before
@@ -245,6 +252,44 @@ def test_cfg5_adaptive_run_scaled():
         last_bytes *= 16
     say("cfg5 widths used:", sorted(seen), "final ratio", ctl.state.ratio)
     assert len(seen) >= 2
+
+
+def test_cfg5_adaptive_run_full():
+    """Configuration 5 at its stated size: the 25,557,032-element ResNet-50 layout (161 buckets,
+    spans of several tiles), 200 steps, a fresh seeded gradient per step, the bandwidth trace
+    feeding nsml_choose_ratio (Algorithm 1, Eq. (3), gate of Algorithm 2 Step 1).  The library's
+    controller and the oracle's agree on every decision; payload and residual are compared with
+    the oracle's own 200-step chain at every step, the dense output on every 20th."""
+    sizes = W.resnet50_sizes()
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    assert n == 25_557_032 and len(sizes) == 161
+    sig = W.resnet50_sigmas(5)
+    bw = W.bandwidth_trace(200)
+    ctl = nsml.Controller()
+    octl = oracle.ctl_init()
+    last_bytes = last_t = 0.0
+    c = None
+    seen_bits, seen_ratio = set(), set()
+    g = torch.empty(n, device=DEV)
+    for step in range(200):
+        ratio, bits = ctl.choose_ratio(last_bytes, last_t, 4.0 * n, -1.0)
+        assert (ratio, bits) == oracle.choose_ratio(octl, last_bytes, last_t, 4.0 * n, -1.0), step
+        seen_bits.add(bits)
+        seen_ratio.add(ratio)
+        for b, nb in enumerate(sizes):
+            g[int(off[b]):int(off[b + 1])] = W._normal(nb, float(sig[b]), W._gen(DEV, W.make_seed(5, step, b)), DEV)
+        if c is None:
+            c = Case(g, off)
+        else:
+            c.set_grad(g)
+        if step % 10 == 0:
+            say("cfg5 full step", step, "ratio", ratio, "bits", bits)
+        K, vb, ns = c.step(ratio, bits, check_dense=(step % 20 == 0))
+        last_bytes = float(4 * K + vb + 4 * ns)
+        last_t = W.simulated_tx_seconds(last_bytes, bw[step])
+    say("cfg5 full: widths used", sorted(seen_bits), "distinct ratios", len(seen_ratio), "final ratio", ctl.state.ratio)
+    assert len(seen_bits) >= 2 and len(seen_ratio) >= 10
 
 
 def test_maximum_bucket_size_properties():

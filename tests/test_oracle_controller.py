@@ -117,3 +117,16 @@ def test_quantization_gate():
     assert choose_ratio(ctl_init(p), 0, 0, 0.0, -1.0) == (0.1, 8)    # unknown norm passes
     p = CtlParams(init=0.7, quant_mode=0, tr_q=0.9)
     assert choose_ratio(ctl_init(p), 0, 0) == (1.0, 8)        # doubled ratio is capped
+
+
+def test_eq3_boundary_is_strict():
+    """Eq. (3) halves only when data_size > 0.9 * BDP; a payload of exactly 0.9 * BDP still takes
+    the additive branch."""
+    s = _netsense_only(0.5)
+    s.phase = NETSENSE
+    s.ebb.append(1e7), s.rtt.append(1.0)       # BtlBw = 1e7 B/s, RTprop = 1 s: BDP = 1e7 bytes
+    edge = 0.9 * 1e7
+    assert choose_ratio(s, edge, 1.0)[0] == 0.5 + 0.01 and s.bdp == 1e7
+    above = edge * (1.0 + 2.0 ** -52)
+    assert above > edge
+    assert choose_ratio(s, above, 1.0)[0] == (0.5 + 0.01) * 0.5
