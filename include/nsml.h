@@ -44,8 +44,11 @@ extern "C" {
 #define NSML_EHIP     (-3)  /* a HIP call failed; see nsml_last_hip_error */
 #define NSML_ENOTIMPL (-4)
 #define NSML_ENOMEM   (-5)  /* host allocation failed */
-#define NSML_EINTERNAL (-6) /* a device-side consistency check of the selection failed (a bug in
-                               the library): reported by nsml_path_stats */
+#define NSML_EINTERNAL (-6) /* a device-side consistency check of the selection tripped during an
+                               earlier call on this context (a bug in the library): that call's
+                               outputs are not valid.  Returned once, by the next GPU entry point
+                               called on the context (which then enqueues nothing), and by
+                               nsml_path_stats / nsml_prune_stats */
 
 const char *nsml_strerror(int code);
 
@@ -144,7 +147,32 @@ typedef struct nsml_ctx nsml_ctx;
  * context per stream).  A change of bucket layout between calls makes the next call wait for
  * the stream once, to rebuild the tables; a change of (ratio, bits) costs one small kernel. */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
+/* As nsml_create for callers that never exceed a ratio: the buffer of survivor values is sized
+ * for max_ratio in (0, 1] instead of 1 (nsml_create is nsml_create_ex with max_ratio = 1), which
+ * brings the workspace to about 2.2 + 4 * max_ratio bytes per element.  A compress call with a
+ * larger ratio returns NSML_ECAP. */
+int nsml_create_ex(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk,
+                   double max_ratio);
 int nsml_destroy(nsml_ctx *ctx);
+
+/* Tuning and diagnostic switches of a context.  The defaults are what the library measures as
+ * best; results are identical for every setting (the tests run the path under each of them).
+ * Takes effect from the next call; waits for nothing.  NSML_EINVAL for an unknown name or a value
+ * outside the listed range.
+ *   "span_tiles"   tiles of 4096 elements per workgroup of the streaming kernels: 1..16, 0 = by
+ *                  gradient size
+ *   "seg_waves"    wavefronts per workgroup of the streaming pass (4, 8 or 16), 0 = by span size
+ *   "group"        lanes per staging segment in the candidate kernels (4, 16 or 64), 0 = by ratio
+ *   "agg"          level-1 candidate histogram aggregated in LDS: 1 always, 0 never, -1 by size
+ *   "force_dense"  1: decide every bucket by the dense passes over the accumulator (the path a
+ *                  bucket takes when its candidates cannot decide it), 0: default
+ *   "nt"           bit mask of non-temporal hints in the streaming pass (1 grad loads, 2 residual
+ *                  loads, 4 accumulator stores); default 7
+ *   "nt_dense"     non-temporal stores of the dense output of decompress: 1, 0, -1 = by variant
+ *   "history"      1: candidate bounds from the previous call's thresholds instead of a sample
+ *   "trip_check"   diagnostic: 1 raises the flag a failed device-side consistency check raises,
+ *                  so the error reporting of the next call can be exercised without a failure */
+int nsml_set_option(nsml_ctx *ctx, const char *name, int value);
 
 /* hipError_t of the last failed HIP call made through this context (0 = none). */
 int nsml_last_hip_error(const nsml_ctx *ctx);
@@ -237,6 +265,15 @@ int nsml_prune_stats(nsml_ctx *ctx, uint32_t *band_buckets, uint32_t *dense_buck
  * (a multiple of 16, both pointers 16-byte aligned, dev) on `stream`, on the current device.
  * A profiler's HBM byte counters are scaled by what they report for this copy of known size. */
 int nsml_calibration_copy(const void *src, void *dst, uint64_t bytes, void *stream);
+/* Measurement aid: plain streaming kernels of the shape of the library's own streaming passes
+ * (1024 threads, every wavefront on its own contiguous 16 KiB), to find what this machine
+ * sustains for each access pattern.  a, b: dev, 16-byte aligned, `bytes` a multiple of 262144.
+ *   mode 0 "k_calib_read"  reads a (b receives one word per workgroup)       bytes moved: bytes
+ *   mode 1 "k_calib_fill"  writes zeros to b                                              bytes
+ *   mode 2 "k_calib_add"   b = a + b (the access pattern of the accumulation)         3 * bytes
+ *   mode 3 "k_calib_copy2" b = a                                                      2 * bytes
+ * nontemporal != 0 uses non-temporal loads and stores. */
+int nsml_calibration_stream(int mode, const void *a, void *b, uint64_t bytes, int nontemporal, void *stream);
 /* Name of kernel id (NULL beyond the last). */
 const char *nsml_kernel_name(int id);
 

@@ -54,6 +54,12 @@ _lib.nsml_choose_ratio.argtypes = [C.POINTER(CtlState), _dbl, _dbl, _dbl, _dbl,
 _lib.nsml_payload_layout.argtypes = [_vp, _u32, _dbl, _i32, _u32, _vp, C.POINTER(_u64),
                                      C.POINTER(_u64), C.POINTER(_u64)]
 _lib.nsml_create.argtypes = [C.POINTER(_vp), _i32, _u64, _u32, _u32]
+_lib.nsml_create_ex.argtypes = [C.POINTER(_vp), _i32, _u64, _u32, _u32, _dbl]
+_lib.nsml_create_ex.restype = _i32
+_lib.nsml_set_option.argtypes = [_vp, C.c_char_p, _i32]
+_lib.nsml_set_option.restype = _i32
+_lib.nsml_calibration_stream.argtypes = [_i32, _vp, _vp, _u64, _i32, _vp]
+_lib.nsml_calibration_stream.restype = _i32
 _lib.nsml_destroy.argtypes = [_vp]
 _lib.nsml_last_hip_error.argtypes = [_vp]
 _lib.nsml_workspace_bytes.argtypes = [_vp]
@@ -203,13 +209,23 @@ def validate_buffers(device, bucket_off, ratio, bits, chunk, *, n=None, grad=Non
 class Context:
     """nsml_ctx: device workspace for gradients of up to max_n elements / max_buckets buckets."""
 
-    def __init__(self, max_n: int, max_buckets: int = 1, chunk: int = 2048, device: int = 0):
+    # nsml_set_option settings applied to every new context (the tests run the path under each)
+    default_options: dict = {}
+
+    def __init__(self, max_n: int, max_buckets: int = 1, chunk: int = 2048, device: int = 0,
+                 max_ratio: float = 1.0):
         self.device, self.chunk = int(device), int(chunk)
         self._dev = torch.device("cuda", self.device)
         self._h = _vp()
-        rc = _lib.nsml_create(C.byref(self._h), self.device, int(max_n), int(max_buckets), self.chunk)
+        rc = _lib.nsml_create_ex(C.byref(self._h), self.device, int(max_n), int(max_buckets), self.chunk,
+                                 float(max_ratio))
         if rc != OK:
-            raise NsmlError(rc, "nsml_create")
+            raise NsmlError(rc, "nsml_create_ex")
+        for name, value in self.default_options.items():
+            self.set_option(name, value)
+
+    def set_option(self, name: str, value: int):
+        _check(_lib.nsml_set_option(self._h, name.encode(), int(value)), f"nsml_set_option({name})", self._h)
 
     def close(self):
         if getattr(self, "_h", None):
@@ -329,6 +345,17 @@ class Context:
 
 def decompress_accumulate(ctx: Context, idx, val, scales, bucket_off, ratio, bits, dense):
     return ctx.decompress_accumulate(idx, val, scales, bucket_off, ratio, bits, dense)
+
+
+CALIB_MODES = {"read": 0, "fill": 1, "add": 2, "copy": 3}
+
+
+def calibration_stream(mode: str, a: torch.Tensor, b: torch.Tensor, nontemporal: bool = False):
+    """Plain streaming kernel of the given access pattern over a and b (same byte size)."""
+    nbytes = a.numel() * a.element_size()
+    assert nbytes == b.numel() * b.element_size()
+    _check(_lib.nsml_calibration_stream(CALIB_MODES[mode], _ptr(a), _ptr(b), nbytes, 1 if nontemporal else 0,
+                                        _stream(a.device)), "nsml_calibration_stream")
 
 
 def calibration_copy(src: torch.Tensor, dst: torch.Tensor):

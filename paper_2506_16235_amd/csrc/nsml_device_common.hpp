@@ -268,6 +268,64 @@ __global__ __launch_bounds__(WG) void k_calib_copy(const f4 *__restrict__ src, f
     for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+/* Streaming yardsticks in the shape of the library's own passes: 1024 threads, every wavefront
+ * on its own contiguous 16 KiB (16 rows of 64 lanes x 16 bytes), one such block per workgroup. */
+template <bool NT>
+__device__ __forceinline__ f4 calib_ld(const f4 *p) { return NT ? __builtin_nontemporal_load(p) : *p; }
+template <bool NT>
+__device__ __forceinline__ void calib_st(f4 *p, f4 v) { if (NT) __builtin_nontemporal_store(v, p); else *p = v; }
+__device__ __forceinline__ uint64_t calib_base()
+{
+    return ((uint64_t)blockIdx.x * 16u + (threadIdx.x >> 6)) * 1024u + (threadIdx.x & 63u);   /* in 16-byte units */
+}
+template <bool NT>
+__global__ __launch_bounds__(1024) void k_calib_read(const f4 *__restrict__ a, f4 *__restrict__ out)
+{
+    const uint64_t base = calib_base();
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 16; ++u) { const f4 v = calib_ld<NT>(a + base + u * 64); acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w; }
+    /* keep the loads alive: one store per workgroup at most (never taken for ordinary data) */
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f && threadIdx.x == 0) out[blockIdx.x] = acc;
+}
+template <bool NT>
+__global__ __launch_bounds__(1024) void k_calib_fill(f4 *__restrict__ b)
+{
+    const uint64_t base = calib_base();
+    const f4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 16; ++u) calib_st<NT>(b + base + u * 64, z);
+}
+template <bool NT>
+__global__ __launch_bounds__(1024) void k_calib_add(const f4 *__restrict__ a, f4 *__restrict__ b)
+{
+    const uint64_t base = calib_base();
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        f4 x[4], y[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { x[u] = calib_ld<NT>(a + base + (h * 4 + u) * 64); y[u] = calib_ld<NT>(b + base + (h * 4 + u) * 64); }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            f4 r; r.x = x[u].x + y[u].x; r.y = x[u].y + y[u].y; r.z = x[u].z + y[u].z; r.w = x[u].w + y[u].w;
+            calib_st<NT>(b + base + (h * 4 + u) * 64, r);
+        }
+    }
+}
+template <bool NT>
+__global__ __launch_bounds__(1024) void k_calib_copy2(const f4 *__restrict__ a, f4 *__restrict__ b)
+{
+    const uint64_t base = calib_base();
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        f4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = calib_ld<NT>(a + base + (h * 4 + u) * 64);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) calib_st<NT>(b + base + (h * 4 + u) * 64, x[u]);
+    }
+}
+
 /* ------------------------------------------------------------------ histograms */
 
 /* Add the four level digits of a quad to an LDS histogram.  When every lane of the wavefront

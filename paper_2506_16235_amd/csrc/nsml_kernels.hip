@@ -83,7 +83,9 @@ struct nsml_ctx {
     uint32_t *d_kw, *d_Tw, *d_needw;              /* pruning stage: kept counts, threshold search state */
     uint32_t *d_wT, *d_wcut, *d_wfast;            /* pruning stage: threshold key and cut index per bucket; path taken */
     uint32_t *d_wLo, *d_wHi;                      /* pruning stage: band of keys staged per bucket */
-    uint32_t *d_werr;                             /* pruning stage: consistency flag (1 word) */
+    uint32_t *h_flags;     /* pinned, mapped: [0] consistency flag of the selection, [1] of the pruning stage */
+    uint32_t *d_flags;     /* the same two words as the kernels see them */
+    double max_ratio;      /* largest ratio the survivor-value buffer was sized for */
     bool have_prune;                              /* the last compress call had weights */
     double *d_span_sq;     /* per span: sum of grad^2 */
     double *d_l2sq;        /* per bucket: sum of grad^2 of the last compress call */
@@ -130,7 +132,7 @@ struct DeviceGuard {
 #define NSML_HIP(ctx, call)                                                        \
     do {                                                                           \
         hipError_t e_ = (call);                                                    \
-        if (e_ != hipSuccess) { (ctx)->last_hip = (int)e_; return NSML_EHIP; }     \
+        if (e_ != hipSuccess) { if (ctx) (ctx)->last_hip = (int)e_; return NSML_EHIP; } \
     } while (0)
 
 template <typename T>
@@ -146,7 +148,7 @@ int dev_alloc(nsml_ctx *c, T **p, uint64_t count)
  * 1/2 histograms, overflow flags */
 uint64_t zero_words(uint64_t B) { return B * (uint64_t)(NB0 + NB0 + NB1 + NB2 + NB1 + NB2 + 1) + 16; }
 
-struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *ovf, *ticket, *err; };
+struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *ovf, *ticket; };
 Hists hists_of(const nsml_ctx *c, uint32_t B)
 {
     Hists h;
@@ -158,7 +160,6 @@ Hists hists_of(const nsml_ctx *c, uint32_t B)
     h.f2 = h.f1 + (uint64_t)B * NB1;
     h.ovf = h.f2 + (uint64_t)B * NB2;
     h.ticket = h.ovf + B;
-    h.err = h.ticket + 1;
     return h;
 }
 
@@ -185,9 +186,10 @@ Cand cand_of(const nsml_ctx *c)
 }
 
 /* Profiling brackets */
-int prof_begin(nsml_ctx *c, int kid, hipStream_t st)
+int prof_begin(nsml_ctx *c, int kid, hipStream_t st, bool *recorded)
 {
-    if (!c->prof || c->recs.size() >= 4096) return NSML_OK;
+    *recorded = false;
+    if (!c || !c->prof || c->recs.size() >= 4096) return NSML_OK;
     nsml_ctx::Rec r; r.kid = kid;
     for (hipEvent_t *e : {&r.a, &r.b}) {
         if (!c->pool.empty()) { *e = c->pool.back(); c->pool.pop_back(); }
@@ -195,22 +197,25 @@ int prof_begin(nsml_ctx *c, int kid, hipStream_t st)
     }
     NSML_HIP(c, hipEventRecord(r.a, st));
     c->recs.push_back(r);
+    *recorded = true;
     return NSML_OK;
 }
-int prof_end(nsml_ctx *c, int kid, hipStream_t st)
+/* closes the record prof_begin opened for this launch (and only if it opened one) */
+int prof_end(nsml_ctx *c, bool recorded, hipStream_t st)
 {
-    if (!c->prof || c->recs.empty() || c->recs.back().kid != kid) return NSML_OK;
+    if (!recorded) return NSML_OK;
     NSML_HIP(c, hipEventRecord(c->recs.back().b, st));
     return NSML_OK;
 }
 
 #define LAUNCHB(ctx, kid, st, kernel, grid, block, ...)                             \
     do {                                                                            \
-        int rc_ = prof_begin(ctx, kid, st);                                         \
+        bool rec_ = false;                                                          \
+        int rc_ = prof_begin(ctx, kid, st, &rec_);                                  \
         if (rc_) return rc_;                                                        \
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), 0, st, __VA_ARGS__);    \
         NSML_HIP(ctx, hipGetLastError());                                           \
-        rc_ = prof_end(ctx, kid, st);                                               \
+        rc_ = prof_end(ctx, rec_, st);                                              \
         if (rc_) return rc_;                                                        \
     } while (0)
 #define LAUNCH(ctx, kid, st, kernel, grid, ...) LAUNCHB(ctx, kid, st, kernel, grid, WG, __VA_ARGS__)
@@ -337,13 +342,31 @@ int ensure_tables(nsml_ctx *c, double ratio, int bits, hipStream_t st)
     return NSML_OK;
 }
 
+/* A device-side consistency check that tripped during an earlier call is reported once, by the
+ * next GPU entry point (the kernels raise the flag in host memory they can reach; reading it
+ * needs no synchronisation, so the report comes one call late). */
+bool pending_internal_error(nsml_ctx *c)
+{
+    volatile uint32_t *f = c->h_flags;
+    if (!f || (f[0] | f[1]) == 0u) return false;
+    f[0] = 0u; f[1] = 0u;
+    return true;
+}
+
 }  // namespace
 
 extern "C" {
 
 int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk)
 {
+    return nsml_create_ex(out, device, max_n, max_buckets, chunk, 1.0);
+}
+
+int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk,
+                   double max_ratio)
+{
     if (!out || max_n == 0 || max_buckets == 0 || chunk == 0 || chunk % 8 != 0) return NSML_EINVAL;
+    if (!(max_ratio > 0.0 && max_ratio <= 1.0)) return NSML_EINVAL;
     *out = nullptr;
     nsml_ctx *c = new (std::nothrow) nsml_ctx();
     if (!c) return NSML_ENOMEM;
@@ -355,28 +378,13 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
-    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = c->d_werr = nullptr;
+    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = nullptr;
+    c->h_flags = c->d_flags = nullptr;
     c->have_prune = false;
-    const char *so = getenv("NSML_SPAN_TILES");
-    c->span_override = so ? atoi(so) : 0;
-    const char *sw = getenv("NSML_SEG_WAVES");
-    c->seg_override = sw ? atoi(sw) : 0;
-    c->segSh = 2;
-    const char *ao = getenv("NSML_AGG");
-    c->agg_override = ao ? (atoi(ao) != 0 ? 1 : 0) : -1;
-    const char *go = getenv("NSML_GROUP");
-    c->group_override = go ? atoi(go) : 0;
-    const char *fd = getenv("NSML_FORCE_DENSE");
-    c->force_dense = (fd && atoi(fd) != 0) ? 1 : 0;
-    const char *ntm = getenv("NSML_NT");
-    c->nt_mode = ntm ? atoi(ntm) : 7;
-    const char *nd = getenv("NSML_NT_DENSE");
-    c->nt_dense = nd ? (atoi(nd) != 0 ? 1 : 0) : -1;     /* -1: each variant's own default */
-    const char *hs = getenv("NSML_HISTORY");
-    /* off by default: while error feedback is still building up, thresholds climb from step to
-     * step and bounds taken from the previous step let in about twice the candidates a fresh
-     * sample does; the sample costs 1 % of a step */
-    c->use_history = hs ? (atoi(hs) != 0) : 0;
+    c->max_ratio = max_ratio;
+    /* tuning switches: the measured defaults (see nsml_set_option) */
+    c->span_override = 0; c->seg_override = 0; c->segSh = 2; c->agg_override = -1; c->group_override = 0;
+    c->force_dense = 0; c->nt_mode = 7; c->nt_dense = -1; c->use_history = 0;
     c->hist_ready = false; c->hist_ratio = 0.0; c->hist_pruned = false; c->d_margin = nullptr;
 
     int ndev = 0;
@@ -410,18 +418,36 @@ int nsml_create(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buckets
     const uint64_t msg = 4 * mt + (uint64_t)MAX_SEG_WAVES * B1;
     A(dev_alloc(c, &c->d_ccnt, msg)); A(dev_alloc(c, &c->d_cG, msg)); A(dev_alloc(c, &c->d_cE, msg));
     A(dev_alloc(c, &c->d_cidx, c->max_cand)); A(dev_alloc(c, &c->d_cval, c->max_cand));
-    A(dev_alloc(c, &c->d_v, max_n));
+    {   /* survivor values in final order: ceil(ratio * n_b) per bucket, at most one more than
+         * ratio * n_b each */
+        uint64_t mv = (uint64_t)ceil(max_ratio * (double)max_n) + max_buckets;
+        if (mv > max_n) mv = max_n;
+        A(dev_alloc(c, &c->d_v, mv));
+    }
     A(dev_alloc(c, &c->d_ts, mt + B1 + 1));
     A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
     A(dev_alloc(c, &c->d_pmask, mt * (TILE / 32)));
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
     A(dev_alloc(c, &c->d_margin, B1));
     A(dev_alloc(c, &c->d_wT, B1)); A(dev_alloc(c, &c->d_wfast, B1)); A(dev_alloc(c, &c->d_wcut, B1));
-    A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1)); A(dev_alloc(c, &c->d_werr, 1));
+    A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1));
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 20;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
         if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
+    }
+    if (rc == NSML_OK) {
+        /* two words the kernels write only when a consistency check fails; the host reads them
+         * at the start of the next call, without waiting for anything */
+        void *hp = nullptr, *dp = nullptr;
+        hipError_t e = hipHostMalloc(&hp, 64, hipHostMallocMapped);
+        if (e == hipSuccess) {
+            c->h_flags = static_cast<uint32_t *>(hp);
+            c->h_flags[0] = c->h_flags[1] = 0u;
+            e = hipHostGetDevicePointer(&dp, hp, 0);
+        }
+        if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
+        else c->d_flags = static_cast<uint32_t *>(dp);
     }
     if (rc != NSML_OK) { nsml_destroy(c); return rc; }
     *out = c;
@@ -438,9 +464,10 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
                     c->d_Tw, c->d_needw, c->d_margin, c->d_wT, c->d_wfast, c->d_wcut,
-                    c->d_wLo, c->d_wHi, c->d_werr};
+                    c->d_wLo, c->d_wHi};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
+    if (c->h_flags) (void)hipHostFree(c->h_flags);
     for (auto &r : c->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (auto e : c->pool) (void)hipEventDestroy(e);
     delete c;
@@ -460,6 +487,8 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(idx, 4) || !aligned(val, 4) ||
         !aligned(scales, 4) || !aligned(weights, 16))
         return NSML_EINVAL;
+    if (ratio > c->max_ratio) return NSML_ECAP;
+    if (pending_internal_error(c)) return NSML_EINTERNAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     DeviceGuard guard(c->device);
     if (!guard.ok) { c->last_hip = (int)hipErrorInvalidDevice; return NSML_EHIP; }
@@ -492,7 +521,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         if (!c->force_dense)
             LAUNCH(c, KID_SAMPLE, st, k_sample<false>, c->n_samp, weights, (const float *)nullptr, tw, h.hs);
         LAUNCH(c, KID_WPLAN, st, k_wpredict, B, tw, (const uint32_t *)h.hs, c->d_wLo, c->d_wHi, c->force_dense,
-               c->d_werr);
+               c->d_flags + 1);
         LAUNCHB(c, KID_WHIST, st, k_whist, c->n_spans, eblock, weights, tw, h.h0, cdw,
                 (const uint32_t *)c->d_wLo, (const uint32_t *)c->d_wHi);
         LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0, (const uint32_t *)c->d_wLo,
@@ -502,9 +531,9 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
         else
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
-        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_werr, 0);
+        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags + 1, 0);
         LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cgw + fgrid, weights, tw, cdw, h.c2, h.f2, cgw);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_werr, 0, c->d_wT);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags + 1, 0, c->d_wT);
         LAUNCH(c, KID_COUNT, st, k_count<64>, cgw + fgrid, weights, tw, cdw, c->d_tG, c->d_tE, cgw);
         LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cdw.G, cdw.E, c->d_tG, c->d_tE);
         LAUNCH(c, KID_WMASK, st, k_wfinish<64>, cgw + fgrid, weights, tw, cdw, (const uint32_t *)c->d_tG,
@@ -583,9 +612,9 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     } else {
         NSML_BY_GROUP(KID_REFINE1, NSML_K_REFINE1, acc, t, cd, h.c1, h.f1, cg);
     }
-    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, h.err, 0);
+    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags, 0);
     NSML_BY_GROUP(KID_REFINE2, NSML_K_REFINE2, acc, t, cd, h.c2, h.f2, cg);
-    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, h.err, write_next);
+    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags, write_next);
     NSML_BY_GROUP(KID_COUNT, NSML_K_COUNT, acc, t, cd, c->d_tG, c->d_tE, cg);
     LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE);
     NSML_BY_GROUP(KID_WRITE, NSML_K_WRITE, acc, t, cd, (const uint32_t *)c->d_tG, (const uint32_t *)c->d_tE,
@@ -625,6 +654,57 @@ int nsml_compress_pruned(nsml_ctx *c, const float *grad, float *residual, const 
     return compress_impl(c, grad, residual, weights, n, bucket_off, B, ratio, bits, idx, val, scales, stream);
 }
 
+/* The launches of one decompress: tile-start table, then the dense output.  c may be NULL
+ * (the entry point without a context): then nothing is profiled and no error code is kept. */
+static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint64_t K, uint32_t n_spans,
+                             uint32_t *d_ts, int nt_dense, const uint32_t *idx, const void *val,
+                             const float *scales, int bits, float *dense_out)
+{
+    if (K >= (4ull << 20)) {
+        const uint64_t want = (K + (uint64_t)WG * 8 - 1) / ((uint64_t)WG * 8);
+        LAUNCH(c, KID_TILESTART, st, k_tilestart<8>, (uint32_t)(want < 16384 ? want : 16384), idx, t, K, d_ts);
+    } else {
+        const uint64_t want = (K + (uint64_t)WG * 2 - 1) / ((uint64_t)WG * 2);
+        LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, K, d_ts);
+    }
+    const uint32_t *ts = d_ts;
+    if (t.spanT >= MAX_SPAN_TILES) {
+        /* the largest gradients: one wavefront per tile, direct stores (plain unless asked otherwise) */
+        const uint32_t dblock = 64u * t.spanT;
+        if (nt_dense > 0) {
+            switch (bits) {
+            case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, true>), n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 16: LAUNCHB(c, KID_DECOMP, st, (k_decomp<16, true>), n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 8:  LAUNCHB(c, KID_DECOMP, st, (k_decomp<8, true>),  n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            default: LAUNCHB(c, KID_DECOMP, st, (k_decomp<4, true>),  n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            }
+        } else {
+            switch (bits) {
+            case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, false>), n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 16: LAUNCHB(c, KID_DECOMP, st, (k_decomp<16, false>), n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            case 8:  LAUNCHB(c, KID_DECOMP, st, (k_decomp<8, false>),  n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            default: LAUNCHB(c, KID_DECOMP, st, (k_decomp<4, false>),  n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
+            }
+        }
+    } else if (nt_dense != 0) {
+        /* smaller gradients: tiles assembled in LDS, non-temporal stores unless asked otherwise */
+        switch (bits) {
+        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<32, true>), n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<16, true>), n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<8, true>),  n_spans, idx, val, scales, t, ts, dense_out); break;
+        default: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<4, true>),  n_spans, idx, val, scales, t, ts, dense_out); break;
+        }
+    } else {
+        switch (bits) {
+        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<32, false>), n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<16, false>), n_spans, idx, val, scales, t, ts, dense_out); break;
+        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<8, false>),  n_spans, idx, val, scales, t, ts, dense_out); break;
+        default: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<4, false>),  n_spans, idx, val, scales, t, ts, dense_out); break;
+        }
+    }
+    return NSML_OK;
+}
+
 int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,
                     uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
                     float *dense_out, void *stream)
@@ -633,6 +713,7 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     if ((bits == 8 || bits == 4) && !scales) return NSML_EINVAL;
     if (!aligned(dense_out, 16) || !aligned(idx, 4) || !aligned(val, 4) || !aligned(scales, 4))
         return NSML_EINVAL;
+    if (pending_internal_error(c)) return NSML_EINTERNAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     DeviceGuard guard(c->device);
     if (!guard.ok) { c->last_hip = (int)hipErrorInvalidDevice; return NSML_EHIP; }
@@ -640,50 +721,8 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     if (rc) return rc;
     rc = ensure_tables(c, ratio, bits, st);
     if (rc) return rc;
-    const Tables t = tables_of(c);
-    if (c->K >= (4ull << 20)) {
-        const uint64_t want = (c->K + (uint64_t)WG * 8 - 1) / ((uint64_t)WG * 8);
-        LAUNCH(c, KID_TILESTART, st, k_tilestart<8>, (uint32_t)(want < 16384 ? want : 16384), idx, t, c->K, c->d_ts);
-    } else {
-        const uint64_t want = (c->K + (uint64_t)WG * 2 - 1) / ((uint64_t)WG * 2);
-        LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, c->K, c->d_ts);
-    }
-    const uint32_t *ts = c->d_ts;
-    if (c->spanT >= MAX_SPAN_TILES) {
-        /* the largest gradients: one wavefront per tile, direct stores (plain unless asked otherwise) */
-        const uint32_t dblock = 64u * c->spanT;
-        if (c->nt_dense > 0) {
-            switch (bits) {
-            case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, true>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            case 16: LAUNCHB(c, KID_DECOMP, st, (k_decomp<16, true>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            case 8:  LAUNCHB(c, KID_DECOMP, st, (k_decomp<8, true>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            default: LAUNCHB(c, KID_DECOMP, st, (k_decomp<4, true>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            }
-        } else {
-            switch (bits) {
-            case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, false>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            case 16: LAUNCHB(c, KID_DECOMP, st, (k_decomp<16, false>), c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            case 8:  LAUNCHB(c, KID_DECOMP, st, (k_decomp<8, false>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            default: LAUNCHB(c, KID_DECOMP, st, (k_decomp<4, false>),  c->n_spans, dblock, idx, val, scales, t, ts, dense_out); break;
-            }
-        }
-    } else if (c->nt_dense != 0) {
-        /* smaller gradients: tiles assembled in LDS, non-temporal stores unless asked otherwise */
-        switch (bits) {
-        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<32, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<16, true>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<8, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        default: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<4, true>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        }
-    } else {
-        switch (bits) {
-        case 32: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<32, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 16: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<16, false>), c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        case 8:  LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<8, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        default: LAUNCH(c, KID_DECOMP, st, (k_decomp_lds<4, false>),  c->n_spans, idx, val, scales, t, ts, dense_out); break;
-        }
-    }
-    return NSML_OK;
+    return launch_decompress(c, st, tables_of(c), c->K, c->n_spans, c->d_ts, c->nt_dense, idx, val, scales,
+                             bits, dense_out);
 }
 
 int nsml_decompress_accumulate(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,
@@ -694,6 +733,7 @@ int nsml_decompress_accumulate(nsml_ctx *c, const uint32_t *idx, const void *val
     if ((bits == 8 || bits == 4) && !scales) return NSML_EINVAL;
     if (!aligned(dense_inout, 16) || !aligned(idx, 4) || !aligned(val, 4) || !aligned(scales, 4))
         return NSML_EINVAL;
+    if (pending_internal_error(c)) return NSML_EINTERNAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     DeviceGuard guard(c->device);
     if (!guard.ok) { c->last_hip = (int)hipErrorInvalidDevice; return NSML_EHIP; }
@@ -770,9 +810,7 @@ int nsml_path_stats(nsml_ctx *c, uint32_t *fast_buckets, uint32_t *fallback_buck
         if (c->h_off[b + 1] == c->h_off[b]) continue;
         if (f[b]) *fast_buckets += 1; else *fallback_buckets += 1;
     }
-    uint32_t err = 0;
-    NSML_HIP(c, hipMemcpy(&err, hists_of(c, c->B).err, sizeof(uint32_t), hipMemcpyDeviceToHost));
-    return err ? NSML_EINTERNAL : NSML_OK;
+    return *(volatile uint32_t *)&c->h_flags[0] ? NSML_EINTERNAL : NSML_OK;
 }
 
 int nsml_prune_stats(nsml_ctx *c, uint32_t *band_buckets, uint32_t *dense_buckets)
@@ -788,9 +826,7 @@ int nsml_prune_stats(nsml_ctx *c, uint32_t *band_buckets, uint32_t *dense_bucket
         if (c->h_off[b + 1] == c->h_off[b]) continue;
         if (f[b]) *band_buckets += 1; else *dense_buckets += 1;
     }
-    uint32_t err = 0;
-    NSML_HIP(c, hipMemcpy(&err, c->d_werr, sizeof(uint32_t), hipMemcpyDeviceToHost));
-    return err ? NSML_EINTERNAL : NSML_OK;
+    return *(volatile uint32_t *)&c->h_flags[1] ? NSML_EINTERNAL : NSML_OK;
 }
 
 int nsml_calibration_copy(const void *src, void *dst, uint64_t bytes, void *stream)
@@ -802,6 +838,73 @@ int nsml_calibration_copy(const void *src, void *dst, uint64_t bytes, void *stre
     const uint32_t grid = (uint32_t)(want < 65536 ? want : 65536);
     hipLaunchKernelGGL(k_calib_copy, dim3(grid), dim3(WG), 0, static_cast<hipStream_t>(stream),
                        static_cast<const f4 *>(src), static_cast<f4 *>(dst), n16);
+    return hipGetLastError() == hipSuccess ? NSML_OK : NSML_EHIP;
+}
+
+int nsml_set_option(nsml_ctx *c, const char *name, int value)
+{
+    if (!c || !name) return NSML_EINVAL;
+    auto is = [&](const char *s) { return strcmp(name, s) == 0; };
+    if (is("span_tiles")) {
+        if (value < 0 || value > MAX_SPAN_TILES) return NSML_EINVAL;
+        c->span_override = value;
+        c->B = 0;                              /* the geometry changes: rebuild the layout tables */
+        c->tables_valid = false;
+    } else if (is("seg_waves")) {
+        if (value != 0 && value != 4 && value != 8 && value != 16) return NSML_EINVAL;
+        c->seg_override = value;
+        c->B = 0;
+        c->tables_valid = false;
+    } else if (is("group")) {
+        if (value != 0 && value != 4 && value != 16 && value != 64) return NSML_EINVAL;
+        c->group_override = value;
+    } else if (is("agg")) {
+        if (value < -1 || value > 1) return NSML_EINVAL;
+        c->agg_override = value;
+    } else if (is("force_dense")) {
+        if (value != 0 && value != 1) return NSML_EINVAL;
+        c->force_dense = value;
+        c->hist_ready = false;
+    } else if (is("nt")) {
+        if (value != 1 && value != 3 && value != 5 && value != 7) return NSML_EINVAL;
+        c->nt_mode = value;
+    } else if (is("nt_dense")) {
+        if (value < -1 || value > 1) return NSML_EINVAL;
+        c->nt_dense = value;
+    } else if (is("history")) {
+        if (value != 0 && value != 1) return NSML_EINVAL;
+        c->use_history = value;
+        c->hist_ready = false;
+    } else if (is("trip_check")) {
+        if (value != 1) return NSML_EINVAL;
+        *(volatile uint32_t *)&c->h_flags[0] = 1u;
+    } else {
+        return NSML_EINVAL;
+    }
+    return NSML_OK;
+}
+
+int nsml_calibration_stream(int mode, const void *a, void *b, uint64_t bytes, int nontemporal, void *stream)
+{
+    constexpr uint64_t PER_WG = 16ull * 16384ull;      /* 16 wavefronts x 16 KiB */
+    if (!a || !b || bytes == 0 || bytes % PER_WG != 0 || !aligned(a, 16) || !aligned(b, 16)) return NSML_EINVAL;
+    if (mode < 0 || mode > 3) return NSML_EINVAL;
+    const uint64_t wgs = bytes / PER_WG;
+    if (wgs > 0x7FFFFFFFull) return NSML_ECAP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const f4 *pa = static_cast<const f4 *>(a);
+    f4 *pb = static_cast<f4 *>(b);
+    const dim3 grid((uint32_t)wgs), block(1024);
+    switch (mode * 2 + (nontemporal ? 1 : 0)) {
+    case 0: hipLaunchKernelGGL((k_calib_read<false>), grid, block, 0, st, pa, pb); break;
+    case 1: hipLaunchKernelGGL((k_calib_read<true>), grid, block, 0, st, pa, pb); break;
+    case 2: hipLaunchKernelGGL((k_calib_fill<false>), grid, block, 0, st, pb); break;
+    case 3: hipLaunchKernelGGL((k_calib_fill<true>), grid, block, 0, st, pb); break;
+    case 4: hipLaunchKernelGGL((k_calib_add<false>), grid, block, 0, st, pa, pb); break;
+    case 5: hipLaunchKernelGGL((k_calib_add<true>), grid, block, 0, st, pa, pb); break;
+    case 6: hipLaunchKernelGGL((k_calib_copy2<false>), grid, block, 0, st, pa, pb); break;
+    default: hipLaunchKernelGGL((k_calib_copy2<true>), grid, block, 0, st, pa, pb); break;
+    }
     return hipGetLastError() == hipSuccess ? NSML_OK : NSML_EHIP;
 }
 

@@ -18,10 +18,10 @@ def path(request, monkeypatch):
     """Every case runs three times: with the single-pass candidate path as shipped (candidate
     bounds from a sample of the gradient; buckets fall back to the dense passes on their own
     when they must), with the optional history mode (bounds from the previous call's thresholds
-    when there is one), and with every bucket forced through the dense passes.  The library
-    reads the switches when a context is created."""
-    monkeypatch.setenv("NSML_FORCE_DENSE", "1" if request.param == "dense" else "0")
-    monkeypatch.setenv("NSML_HISTORY", "1" if request.param == "history" else "0")
+    when there is one), and with every bucket forced through the dense passes.  The switches are
+    nsml_set_option settings applied to every context the test creates."""
+    monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if request.param == "dense" else 0)
+    monkeypatch.setitem(nsml.Context.default_options, "history", 1 if request.param == "history" else 0)
     return request.param
 
 
@@ -156,14 +156,14 @@ def test_bert_shaped_scaled(ratio, bits):
                                                         (16, 4, 64), (16, 8, 16), (16, 16, 16), (16, 16, 64), (16, 16, 4), (2, 4, 4)])
 def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
     # the level-1 histogram of the candidates aggregated in LDS (the rule from ~2 G elements up)
-    monkeypatch.setenv("NSML_AGG", "1" if (span_tiles + seg_waves + group) % 8 == 4 or group == 4 else "0")
+    monkeypatch.setitem(nsml.Context.default_options, "agg", 1 if (span_tiles + seg_waves + group) % 8 == 4 or group == 4 else 0)
     """The library picks tiles per workgroup, wavefronts per workgroup and lanes per staging
     segment from the size of the gradient; the large-gradient shapes are forced here on a
     gradient the oracle sorts in a second: ragged buckets, last spans with fewer tiles than
     wavefronts, ties at the threshold, two error-feedback steps."""
-    monkeypatch.setenv("NSML_SPAN_TILES", str(span_tiles))
-    monkeypatch.setenv("NSML_SEG_WAVES", str(seg_waves))
-    monkeypatch.setenv("NSML_GROUP", str(group))
+    monkeypatch.setitem(nsml.Context.default_options, "span_tiles", int(span_tiles))
+    monkeypatch.setitem(nsml.Context.default_options, "seg_waves", int(seg_waves))
+    monkeypatch.setitem(nsml.Context.default_options, "group", int(group))
     sizes = [200_003, 65_536 * 3 + 1, 4_099, 0, 333_333, 70_001]
     off = W.offsets_of(sizes)
     n = int(off[-1])
@@ -184,7 +184,7 @@ def test_decompress_of_a_malformed_index_list_stays_inside_the_output(monkeypatc
     outside the dense buffer is touched (sentinels on both sides stay intact), with both
     decompress variants and with decompress-accumulate."""
     if span_tiles:
-        monkeypatch.setenv("NSML_SPAN_TILES", str(span_tiles))
+        monkeypatch.setitem(nsml.Context.default_options, "span_tiles", int(span_tiles))
     sizes = [70_001, 3, 150_000, 0, 40_961]
     off = W.offsets_of(sizes)
     n = int(off[-1])
@@ -250,7 +250,7 @@ def test_gpu_argument_errors():
         ctx.compress(g, r, off, 0.0, 8)
     assert e.value.code == nsml.EINVAL
     with pytest.raises(nsml.NsmlError) as e:
-        ctx.compress(g, r, W.offsets_of([5_000] * 3)[:4], 0.5, 8)          # 3 buckets > max 2
+        ctx.compress(g, r, W.offsets_of([3_000, 3_000, 4_000]), 0.5, 8)    # 3 buckets > max 2
     assert e.value.code == nsml.ECAP
     big = _rand(20_000, 2)
     with pytest.raises(nsml.NsmlError) as e:
@@ -259,6 +259,8 @@ def test_gpu_argument_errors():
     with pytest.raises(nsml.NsmlError) as e:
         ctx.compress(g[1:], r[1:], W.offsets_of([9_999]), 0.5, 8)          # misaligned
     assert e.value.code == nsml.EINVAL
+    with pytest.raises(ValueError):                                        # the binding's own size check
+        ctx.compress(g, r[:-1], off, 0.5, 8)
 
 
 def test_l2norm_byproduct():
@@ -344,3 +346,46 @@ def test_hip_graph_capture_and_replay(path):
         assert torch.equal(sc[:ns], e_sc[:ns])
         assert torch.equal(r_static, r_eager) and torch.equal(dense, e_dense)
         (g_new * 2).sum().item()          # unrelated eager work and a synchronisation between replays
+
+
+def test_internal_error_is_reported_by_the_next_call_once():
+    """A tripped device-side consistency check is reported by the next GPU entry point called on
+    the context (which enqueues nothing) and then cleared; raised here through the diagnostic
+    option, since no input makes the check fail."""
+    g, off = W.cfg1(DEV)
+    c = Case(g, off)
+    c.step(0.01, 8)
+    c.ctx.set_option("trip_check", 1)
+    r_before = c.r.clone()
+    with pytest.raises(nsml.NsmlError) as e:
+        c.ctx.compress(c.g, c.r, off, 0.01, 8)
+    assert e.value.code == nsml.EINTERNAL
+    torch.cuda.synchronize()
+    assert torch.equal(c.r, r_before)                 # nothing ran
+    c.step(0.01, 8)                                   # reported once: the context works again
+    c.ctx.set_option("trip_check", 1)
+    with pytest.raises(nsml.NsmlError) as e:
+        c.ctx.path_stats()
+    assert e.value.code == nsml.EINTERNAL
+    with pytest.raises(nsml.NsmlError):
+        c.ctx.decompress(*c.ctx.alloc_payload(off, 0.01, 8), c.n, off, 0.01, 8)
+    with pytest.raises(nsml.NsmlError):
+        c.ctx.set_option("no_such_option", 1)
+    with pytest.raises(nsml.NsmlError):
+        c.ctx.set_option("span_tiles", 17)
+
+
+def test_context_sized_for_a_maximum_ratio():
+    """nsml_create_ex: the survivor-value buffer is sized by max_ratio; larger ratios are refused."""
+    sizes = [300_000, 5, 70_001]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    full = nsml.Context(n, len(sizes), 2048)
+    small = nsml.Context(n, len(sizes), 2048, max_ratio=0.1)
+    assert full.workspace_bytes - small.workspace_bytes >= int(0.85 * 4 * n)
+    c = Case(_rand(n, 77), off, ctx=small)
+    c.step(0.1, 8)
+    c.step(0.03, 4)
+    with pytest.raises(nsml.NsmlError) as e:
+        small.compress(c.g, c.r, off, 0.11, 8)
+    assert e.value.code == nsml.ECAP

@@ -13,8 +13,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(autouse=True, params=["auto", "history", "dense"])
 def path(request, monkeypatch):
-    monkeypatch.setenv("NSML_FORCE_DENSE", "1" if request.param == "dense" else "0")
-    monkeypatch.setenv("NSML_HISTORY", "1" if request.param == "history" else "0")
+    monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if request.param == "dense" else 0)
+    monkeypatch.setitem(nsml.Context.default_options, "history", 1 if request.param == "history" else 0)
     return request.param
 
 
@@ -87,5 +87,5 @@ def test_large_single_bucket():
 def test_aggregated_level1_histogram(monkeypatch):
     """The weight stage's level-1 histogram counted in LDS per workgroup (the rule for very large
     gradients), forced on buckets small enough for the oracle."""
-    monkeypatch.setenv("NSML_AGG", "1")
+    monkeypatch.setitem(nsml.Context.default_options, "agg", 1)
     _run([700_001, 300_000, 12_345, 1_500_000], 0.01, 8, 512, steps=1, seed=33)

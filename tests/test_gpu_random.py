@@ -19,14 +19,11 @@ def _case(seed, pruned, monkeypatch):
     st = int(rs.choice([0, 1, 2, 4, 8, 16]))
     sw = int(rs.choice([0, 4, 8, 16]))
     grp = int(rs.choice([0, 4, 16, 64]))
-    for k, v in (("NSML_SPAN_TILES", st), ("NSML_SEG_WAVES", sw), ("NSML_GROUP", grp)):
-        if v:
-            monkeypatch.setenv(k, str(v))
-        else:
-            monkeypatch.delenv(k, raising=False)
-    monkeypatch.setenv("NSML_AGG", str(int(rs.randint(0, 2))))
-    monkeypatch.setenv("NSML_FORCE_DENSE", "1" if rs.rand() < 0.15 else "0")
-    monkeypatch.setenv("NSML_HISTORY", "1" if rs.rand() < 0.3 else "0")
+    for k, v in (("span_tiles", st), ("seg_waves", sw), ("group", grp)):
+        monkeypatch.setitem(nsml.Context.default_options, k, v)
+    monkeypatch.setitem(nsml.Context.default_options, "agg", int(int(rs.randint(0, 2))))
+    monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if rs.rand() < 0.15 else 0)
+    monkeypatch.setitem(nsml.Context.default_options, "history", 1 if rs.rand() < 0.3 else 0)
     B = int(rs.randint(1, 9))
     sizes = []
     for _ in range(B):
