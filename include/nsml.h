@@ -222,6 +222,23 @@ int nsml_decompress(nsml_ctx *ctx, const uint32_t *idx, const void *val, const f
                     uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
                     float *dense_out, void *stream);
 
+/* nsml_decompress for callers that cannot allocate device memory or create a context: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It needs no
+ * nsml_ctx and calls no allocating routine: its tables (bucket geometry, where each tile's
+ * survivors start) live in a fixed device array inside the library, NSML_STATIC_SCRATCH_BYTES
+ * per GPU, held until the process ends.  Same arguments, payload format and result as
+ * nsml_decompress, plus the chunk size; runs on the current device.
+ *   limits   n <= NSML_STATIC_MAX_N, B <= NSML_STATIC_MAX_BUCKETS, else NSML_ECAP
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and give unspecified values; order them on one stream.  The array
+ * keeps the last call's contents; every entry a call reads is written by that call first. */
+#define NSML_STATIC_MAX_N        (1ull << 28)
+#define NSML_STATIC_MAX_BUCKETS  320u
+#define NSML_STATIC_SCRATCH_BYTES (1u << 20)
+int nsml_decompress_static(const uint32_t *idx, const void *val, const float *scales, uint64_t n,
+                           const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                           uint32_t chunk, float *dense_out, void *stream);
+
 /* Receiver side of an all-gather of payloads (the communication pattern the paper reports for
  * sparsified gradients, Sec. 5.3): add one payload into a dense gradient that is being
  * accumulated.  dense_inout[bucket_off[b] + idx[j]] += decoded value j; no other element is

@@ -58,6 +58,8 @@ _lib.nsml_create_ex.argtypes = [C.POINTER(_vp), _i32, _u64, _u32, _u32, _dbl]
 _lib.nsml_create_ex.restype = _i32
 _lib.nsml_set_option.argtypes = [_vp, C.c_char_p, _i32]
 _lib.nsml_set_option.restype = _i32
+_lib.nsml_decompress_static.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _u32, _vp, _vp]
+_lib.nsml_decompress_static.restype = _i32
 _lib.nsml_calibration_stream.argtypes = [_i32, _vp, _vp, _u64, _i32, _vp]
 _lib.nsml_calibration_stream.restype = _i32
 _lib.nsml_destroy.argtypes = [_vp]
@@ -345,6 +347,22 @@ class Context:
 
 def decompress_accumulate(ctx: Context, idx, val, scales, bucket_off, ratio, bits, dense):
     return ctx.decompress_accumulate(idx, val, scales, bucket_off, ratio, bits, dense)
+
+
+def decompress_static(idx: torch.Tensor, val: torch.Tensor, scales: Optional[torch.Tensor], n: int, bucket_off,
+                      ratio: float, bits: int, chunk: int = 2048, out: torch.Tensor = None) -> torch.Tensor:
+    """nsml_decompress_static: decompress without a context and without any allocation inside
+    the library (the output tensor is the caller's), on the tensors' device."""
+    off = _off(bucket_off)
+    dev = idx.device
+    if out is None:
+        out = torch.empty(int(n), dtype=torch.float32, device=dev)
+    validate_buffers(dev, off, ratio, bits, chunk, n=n, idx=idx, val=val, scales=scales, dense=out)
+    with torch.cuda.device(dev):
+        rc = _lib.nsml_decompress_static(_ptr(idx), _ptr(val), _ptr(scales), int(n), off.ctypes.data,
+                                         len(off) - 1, float(ratio), int(bits), int(chunk), _ptr(out), _stream(dev))
+    _check(rc, "nsml_decompress_static")
+    return out
 
 
 CALIB_MODES = {"read": 0, "fill": 1, "add": 2, "copy": 3}

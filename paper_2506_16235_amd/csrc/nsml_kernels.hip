@@ -725,6 +725,130 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
                              bits, dense_out);
 }
 
+/* ---------------------------------------------------------------- no-allocation decompress */
+
+}  // extern "C"
+
+/* Scratch of nsml_decompress_static: the layout tables and the tile-start table of one call.
+ * One copy per GPU, at its own address on each; host code never uses this name as a pointer,
+ * only what hipGetSymbolAddress returns for the current device. */
+static __device__ __align__(256) unsigned char scratch[NSML_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int STATIC_MAX_DEVICES = 64;
+void *g_scratch_ptr[STATIC_MAX_DEVICES];        /* per device, resolved on the first call there */
+
+constexpr uint32_t STATIC_B1 = NSML_STATIC_MAX_BUCKETS + 1;
+constexpr uint64_t STATIC_MAX_TILES = NSML_STATIC_MAX_N / TILE + 2ull * NSML_STATIC_MAX_BUCKETS + 2;
+
+struct StaticOffsets { uint64_t off[STATIC_B1]; };      /* travels as a kernel argument */
+
+/* where each table sits inside the scratch array */
+struct StaticScratch {
+    uint64_t *off, *P, *V, *S, *C;
+    uint32_t *tile0, *span0, *k, *kw, *span_b, *ts;
+};
+StaticScratch carve(void *base)
+{
+    StaticScratch m;
+    uint64_t *q = static_cast<uint64_t *>(base);
+    m.off = q; q += STATIC_B1;
+    m.P = q; q += STATIC_B1;
+    m.V = q; q += STATIC_B1;
+    m.S = q; q += STATIC_B1;
+    m.C = q; q += STATIC_B1;
+    uint32_t *w = reinterpret_cast<uint32_t *>(q);
+    m.tile0 = w; w += STATIC_B1 + 1;
+    m.span0 = w; w += STATIC_B1 + 1;
+    m.k = w; w += STATIC_B1 + 1;
+    m.kw = w; w += STATIC_B1 + 1;
+    m.span_b = w; w += STATIC_MAX_TILES;
+    m.ts = w; w += STATIC_MAX_TILES + STATIC_B1 + 1;
+    return m;
+}
+static_assert(5 * STATIC_B1 * 8 + 4 * (STATIC_B1 + 1) * 4 + (2 * STATIC_MAX_TILES + STATIC_B1 + 1) * 4
+                  <= NSML_STATIC_SCRATCH_BYTES, "scratch array too small for its tables");
+static_assert(sizeof(StaticOffsets) <= 3072, "bucket offsets must fit the kernel argument block");
+
+/* One workgroup: bucket offsets (handed over by value) and the tile / span prefixes they imply. */
+__global__ __launch_bounds__(WG) void k_static_layout(StaticOffsets so, uint32_t B, uint32_t spanT,
+                                                      uint64_t *__restrict__ off, uint32_t *__restrict__ tile0,
+                                                      uint32_t *__restrict__ span0)
+{
+    for (uint32_t b = threadIdx.x; b <= B; b += WG) off[b] = so.off[b];
+    if (threadIdx.x == 0) {
+        uint32_t nt = 0, ns = 0;
+        for (uint32_t b = 0; b < B; ++b) {
+            tile0[b] = nt; span0[b] = ns;
+            const uint64_t lo = so.off[b], hi = so.off[b + 1];
+            const uint32_t tb = hi > lo ? (uint32_t)((hi - (lo & ~3ull) + TILE - 1) / TILE) : 0u;
+            nt += tb;
+            ns += (tb + spanT - 1) / spanT;
+        }
+        tile0[B] = nt; span0[B] = ns;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int nsml_decompress_static(const uint32_t *idx, const void *val, const float *scales, uint64_t n,
+                           const uint64_t *bucket_off, uint32_t B, double ratio, int bits,
+                           uint32_t chunk, float *dense_out, void *stream)
+{
+    if (!idx || !val || !dense_out || !bucket_off || B == 0 || n == 0) return NSML_EINVAL;
+    if ((bits == 8 || bits == 4) && !scales) return NSML_EINVAL;
+    if (!aligned(dense_out, 16) || !aligned(idx, 4) || !aligned(val, 4) || !aligned(scales, 4))
+        return NSML_EINVAL;
+    if (B > NSML_STATIC_MAX_BUCKETS || n > NSML_STATIC_MAX_N) return NSML_ECAP;
+    if (bucket_off[0] != 0 || bucket_off[B] != n) return NSML_EINVAL;
+    uint64_t K = 0;
+    int rc = nsml_payload_layout(bucket_off, B, ratio, bits, chunk, nullptr, &K, nullptr, nullptr);
+    if (rc) return rc;                      /* also rejects descending offsets, bad ratio / bits / chunk */
+    /* the same geometry a context would build, computed without any table on the host */
+    uint64_t nt = 0, ns = 0;
+    for (uint32_t b = 0; b < B; ++b) {
+        const uint64_t lo = bucket_off[b], hi = bucket_off[b + 1];
+        if (hi > lo) nt += (hi - (lo & ~3ull) + TILE - 1) / TILE;
+    }
+    if (nt > STATIC_MAX_TILES) return NSML_ECAP;
+    const uint32_t spanT = pick_span_tiles((uint32_t)nt, 0);
+    StaticOffsets so;
+    for (uint32_t b = 0; b < B; ++b) {
+        const uint64_t lo = bucket_off[b], hi = bucket_off[b + 1];
+        const uint64_t tb = hi > lo ? (hi - (lo & ~3ull) + TILE - 1) / TILE : 0;
+        ns += (tb + spanT - 1) / spanT;
+        so.off[b] = lo;
+    }
+    so.off[B] = n;
+    for (uint32_t b = B + 1; b < STATIC_B1; ++b) so.off[b] = n;
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return NSML_EHIP;
+    void *base = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!base) {
+        /* this GPU's copy of the array; the symbol's own name is no device address on the host */
+        if (hipGetSymbolAddress(&base, HIP_SYMBOL(scratch)) != hipSuccess || !base) return NSML_EHIP;
+        __atomic_store_n(&g_scratch_ptr[dev], base, __ATOMIC_RELEASE);
+    }
+    const StaticScratch m = carve(base);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    nsml_ctx *none = nullptr;
+
+    Tables t;
+    memset(&t, 0, sizeof t);
+    t.off = m.off; t.tile0 = m.tile0; t.span0 = m.span0; t.span_b = m.span_b;
+    t.k = m.k; t.kw = m.kw; t.P = m.P; t.V = m.V; t.S = m.S; t.C = m.C;
+    t.B = B; t.n_spans = (uint32_t)ns; t.spanT = spanT; t.segSh = 2; t.chunk = chunk;
+    LAUNCH(none, KID_SETUP, st, k_static_layout, 1, so, B, spanT, m.off, m.tile0, m.span0);
+    LAUNCH(none, KID_SETUP, st, k_setup, 1, t, ratio, bits);
+    LAUNCH(none, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)m.span0, B,
+           (uint32_t)ns, m.span_b);
+    return launch_decompress(none, st, t, K, (uint32_t)ns, m.ts, -1, idx, val, scales, bits, dense_out);
+}
+
 int nsml_decompress_accumulate(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,
                                uint64_t n, const uint64_t *bucket_off, uint32_t B, double ratio,
                                int bits, float *dense_inout, void *stream)
