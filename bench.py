@@ -287,6 +287,8 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="time the plain streaming kernels (k_calib_read/fill/add/copy2) and print their GB/s")
     ap.add_argument("--source-hash", action="store_true", help="print the kernel-source hash and exit")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
+                    help="nsml_set_option setting applied to every context (tuning experiments), may repeat")
     args = ap.parse_args()
     if args.source_hash:
         print(kernel_source_hash())
@@ -301,6 +303,9 @@ def main():
     from paper_2506_16235_amd import binding as nsml
 
     dev = "cuda:0"
+    for kv in args.opt:
+        name, _, value = kv.partition("=")
+        nsml.Context.default_options[name] = int(value)
     if args.ceilings:
         print(json.dumps({"stream_ceilings": ceilings(dev)}), flush=True)
         return 0
@@ -381,7 +386,8 @@ def main():
         "config": {"workload": args.workload, "elements": n, "buckets": B, "ratio": ratio,
                    "bits": bits, "chunk": chunk, "survivors": K, "payload_bytes": payload,
                    "distinct_gradients": len(grads), "residual": "carried across steps",
-                   "weight_pruning": bool(args.prune), "hip_graph": bool(args.graph)},
+                   "weight_pruning": bool(args.prune), "hip_graph": bool(args.graph),
+                   "options": dict(nsml.Context.default_options)},
         "hbm_roofline_frac": round(floor_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "floor_bytes_per_step": floor_bytes,
         "profiled_offline": {"hbm_bytes_per_step": step_traffic,

@@ -26,6 +26,8 @@ HIP_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
 ]
+# extra hipcc flags for experiments (e.g. "-DNAME"), never needed for a normal build
+HIP_FLAGS += os.environ.get("NSML_HIPCC_EXTRA", "").split()
 C_FLAGS = ["-O2", "-std=c11", "-fPIC", "-fno-fast-math", "-ffp-contract=off", "-Wall", "-Wextra"]
 
 

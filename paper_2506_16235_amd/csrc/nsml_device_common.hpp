@@ -11,6 +11,8 @@ constexpr int WG = 256;
 constexpr int TILE = 4096;        /* elements per tile */
 constexpr int WTILE = 1024;       /* elements one wavefront covers per iteration in ef_emit */
 constexpr int NB0 = 4096, NB1 = 4096, NB2 = 128;
+constexpr int SUB_DIGITS = 4, SUB_BITS = 6, NBS = SUB_DIGITS << SUB_BITS;   /* finer histogram of a few level-0 digits: 64 bins each */
+constexpr int SHS = 19 - SUB_BITS;   /* key >> SHS : level-0 digit and the 6 bits below it */
 constexpr int SH0 = 19;   /* key >> 19         : level-0 digit (sign-less exponent + 4 mantissa bits) */
 constexpr int SH1 = 7;    /* (key >> 7) & 4095 : level-1 digit;  key & 127 : level-2 digit */
 constexpr int MAX_SPAN_TILES = 16;
@@ -21,15 +23,25 @@ constexpr uint32_t RUNS_PER_WG = 128;          /* sample runs (32 elements each)
 constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
 constexpr uint32_t AGG_GRID = 1024;            /* workgroups of the candidate refine that aggregates in LDS */
 
+/* How a bucket's survivors are found once the streaming pass is done. */
+enum Path : uint32_t {
+    PATH_DENSE = 0,   /* the staged elements cannot decide: every step over the dense accumulator */
+    PATH_CAND = 1,    /* staged = everything from L up: threshold and survivors from the staged entries alone */
+    PATH_BAND = 2,    /* staged = a band of keys around the threshold: threshold from the band, survivors from the dense accumulator */
+    PATH_ZERO = 3     /* more survivors than non-zero elements: threshold key 0, known from the counts alone */
+};
+
 enum KernelId {
     KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
     KID_REFINE1, KID_PICK1, KID_REFINE2, KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE,
-    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_WHIST, KID_WPLAN, KID_WMASK, KID_N
+    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_WHIST, KID_WPLAN, KID_WMASK,
+    KID_SELECT, KID_FINISH, KID_ENCODE, KID_N
 };
 const char *const kKernelNames[KID_N] = {
     "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan", "fb_plan",
     "refine1", "pick1", "refine2", "pick2", "count", "scan", "write",
-    "quant", "tilestart", "decomp", "decomp_acc", "whist", "wplan", "wmask"
+    "quant", "tilestart", "decomp", "decomp_acc", "whist", "wplan", "wmask",
+    "select_count", "select_finish", "encode"
 };
 static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
 
@@ -48,11 +60,17 @@ struct Tables {
     uint64_t *C;             /* B+1 prefix of chunk counts (all widths) */
     uint32_t *T;             /* B   threshold key, refined level by level */
     uint32_t *need;          /* B   how many more to take at the current level */
-    uint32_t *L;             /* B   candidates are the elements with key >= L (NONE: no candidates) */
-    uint32_t *fast;          /* B   1: the candidates decide the bucket, 0: the dense fallback does */
+    uint32_t *L;             /* B   the streaming pass stages the elements with L <= key < H (L = NONE: none) */
+    uint32_t *H;             /* B   NONE: no upper bound (everything from L up is staged: "candidates");
+                              *     else a band is staged and the elements with key >= H are counted per segment.
+                              *     L == H == 1: nothing is staged, non-zero and zero keys are counted per segment */
+    uint32_t *fast;          /* B   how the bucket is decided (PATH_*); the weight stage uses 0 / 1 only */
+    uint32_t *subLo;         /* B   first of the SUB_DIGITS level-0 digits whose next 6 key bits the streaming pass
+                              *     also counts (NONE: none) */
+    uint32_t *sh;            /* B   T holds the key bits from this position up (19: the level-0 digit only; 13: six more) */
     uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
-    uint32_t *margin;        /* B   history mode: how far below the last threshold key L is placed */
+    uint32_t *nhard;         /* 1   buckets of this call that are not on PATH_CAND (their kernels leave at once when 0) */
     uint32_t *kw;            /* B   parameters the pruning step keeps (only with weights) */
     const float *w;          /* weights when Algorithm 2 Step 2 is on, else NULL */
     const uint32_t *wT;      /* B   with weights: threshold key of |w|; NONE: the bucket's mask is in the bitmap */
@@ -255,12 +273,6 @@ __global__ __launch_bounds__(WG) void k_clear(uint32_t *__restrict__ p, uint64_t
     for (uint64_t i = (uint64_t)blockIdx.x * WG + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
-__global__ __launch_bounds__(WG) void k_fill_u32(uint32_t *__restrict__ p, uint32_t n, uint32_t v)
-{
-    const uint32_t i = blockIdx.x * WG + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
 /* Plain 16-byte copy, the yardstick for the profiler's HBM byte counters. */
 __global__ __launch_bounds__(WG) void k_calib_copy(const f4 *__restrict__ src, f4 *__restrict__ dst, uint64_t n16)
 {
@@ -399,6 +411,16 @@ struct DigitWalk {
         incl = block_incl_scan(sum, tmp);
         total = tmp[WG - 1];
         __syncthreads();
+    }
+    /* Zero the row again once it has been read (every thread its own digits): the histograms
+     * of a call are left clean for the next one, which saves a fill kernel per call. */
+    __device__ __forceinline__ void clear(uint32_t *__restrict__ hb) const
+    {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int d = top - i;
+            if (d >= 0) hb[d] = 0u;
+        }
     }
     /* The digit holding the want-th largest entry (1 <= want <= total): exactly one thread
      * returns true, with the digit, the number of entries in higher digits, and the number

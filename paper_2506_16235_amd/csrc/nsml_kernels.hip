@@ -57,6 +57,7 @@
 #include "nsml_select.hpp"
 #include "nsml_prune.hpp"
 #include "nsml_codec.hpp"
+#include "nsml_tail.hpp"
 
 /* ====================================================================== host side */
 
@@ -73,6 +74,13 @@ struct nsml_ctx {
     /* device workspace */
     uint64_t *d_off, *d_P, *d_V, *d_S, *d_C;
     uint32_t *d_tile0, *d_span0, *d_samp0, *d_span_b, *d_k, *d_T, *d_need, *d_L, *d_fast, *d_fspan0;
+    uint32_t *d_sel0;      /* B+1 prefix of the workgroups per bucket of k_select_count */
+    uint4 *d_selw;         /* per workgroup of k_select_count: bucket, first and last segment */
+    uint32_t *d_chunk_b;   /* per chunk of the payload: its bucket (fixed by layout, ratio, bits) */
+    uint32_t *d_chunk_seg; /* per chunk: the staging segment that holds its first survivor */
+    uint32_t *d_H, *d_subLo, *d_sh;
+    uint32_t *d_lcnt, *d_lkey;   /* k_select_count: lists of undecided keys per workgroup */
+    uint64_t max_chunks; uint32_t max_sel;
     uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
     uint32_t *d_tG, *d_tE; /* per tile (fallback path) */
     uint32_t *d_ccnt, *d_cG, *d_cE, *d_cidx;   /* candidate staging */
@@ -95,7 +103,7 @@ struct nsml_ctx {
     std::vector<uint64_t> h_off;
     uint32_t B;
     uint64_t n;
-    uint32_t n_tiles, n_spans, n_samp, spanT, segSh;
+    uint32_t n_tiles, n_spans, n_samp, n_sel, spanT, segSh;
     bool tables_valid;
     double t_ratio; int t_bits;       /* what d_k/d_P/... were computed for */
     uint64_t K, NC;                   /* totals for (layout, t_ratio, t_bits) */
@@ -105,11 +113,13 @@ struct nsml_ctx {
     int group_override;    /* lanes per staging segment in the candidate kernels (0: by ratio) */
     int agg_override;      /* level-1 candidate histogram aggregated in LDS: 1 always, 0 never, -1 by size */
     int force_dense;
+    bool zero_clean; uint32_t zero_B;   /* the per-call histograms and flags were left zeroed (for this many buckets) */
+    int persist;           /* workgroups per compute unit of the streaming pass (0: one workgroup per span) */
+    int decomp_variant;    /* decompress: 1 direct stores, 0 tiles assembled in LDS, -1 by gradient size */
+    int n_cu;
+    int force_rescan;      /* diagnostic: k_select_finish filters the staged entries again instead of using the tails */
     int nt_mode;
     int nt_dense;          /* non-temporal stores for the dense output of decompress: 1, 0, or -1 = by variant */
-    int use_history;       /* place the candidate bound from the previous call's thresholds */
-    bool hist_ready; double hist_ratio; bool hist_pruned;
-    uint32_t *d_margin;
 
     /* profiling */
     bool prof;
@@ -146,9 +156,9 @@ int dev_alloc(nsml_ctx *c, T **p, uint64_t count)
 
 /* words of the per-call zeroed area: hist0, sample hist, candidate level 1/2, fallback level
  * 1/2 histograms, overflow flags */
-uint64_t zero_words(uint64_t B) { return B * (uint64_t)(NB0 + NB0 + NB1 + NB2 + NB1 + NB2 + 1) + 16; }
+uint64_t zero_words(uint64_t B) { return B * (uint64_t)(NB0 + NB0 + NB1 + NB2 + NB1 + NB2 + NBS + 2) + 16; }   /* 16 spare words: counters */
 
-struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *ovf, *ticket; };
+struct Hists { uint32_t *h0, *hs, *c1, *c2, *f1, *f2, *h0b, *ovf, *tail_ovf, *nhard; };
 Hists hists_of(const nsml_ctx *c, uint32_t B)
 {
     Hists h;
@@ -158,8 +168,10 @@ Hists hists_of(const nsml_ctx *c, uint32_t B)
     h.c2 = h.c1 + (uint64_t)B * NB1;
     h.f1 = h.c2 + (uint64_t)B * NB2;
     h.f2 = h.f1 + (uint64_t)B * NB1;
-    h.ovf = h.f2 + (uint64_t)B * NB2;
-    h.ticket = h.ovf + B;
+    h.h0b = h.f2 + (uint64_t)B * NB2;       /* finer counts of a few level-0 digits */
+    h.ovf = h.h0b + (uint64_t)B * NBS;
+    h.tail_ovf = h.ovf + B;        /* k_select_count: a segment's tail could not hold its undecided keys */
+    h.nhard = h.tail_ovf + B;      /* k_plan: buckets not on the candidate path */
     return h;
 }
 
@@ -169,9 +181,9 @@ Tables tables_of(const nsml_ctx *c)
     t.off = c->d_off; t.tile0 = c->d_tile0; t.span0 = c->d_span0; t.samp0 = c->d_samp0;
     t.span_b = c->d_span_b;
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
-    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.fast = c->d_fast;
-    t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0;
-    t.kw = c->d_kw; t.w = nullptr; t.wT = nullptr; t.wcut = nullptr; t.pmask = nullptr; t.margin = c->d_margin;
+    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.H = c->d_H; t.fast = c->d_fast; t.subLo = c->d_subLo; t.sh = c->d_sh;
+    t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0; t.nhard = hists_of(c, c->B).nhard;
+    t.kw = c->d_kw; t.w = nullptr; t.wT = nullptr; t.wcut = nullptr; t.pmask = nullptr;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk;
     return t;
 }
@@ -264,7 +276,7 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
 
     /* new layout: tiles start at the bucket start rounded down to a multiple of 4 */
     const size_t B1 = (size_t)B + 1;
-    std::vector<uint32_t> tile0(B1), span0(B1), samp0(B1);
+    std::vector<uint32_t> tile0(B1), span0(B1), samp0(B1), sel0(B1);
     uint64_t nt = 0, nsamp = 0;
     for (uint32_t b = 0; b < B; ++b) {
         tile0[b] = (uint32_t)nt;
@@ -289,17 +301,29 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
     }
     span0[B] = (uint32_t)ns;
     if (ns * 4ull * spanT * 256ull > c->max_cand) return NSML_ECAP;
+    /* k_select_count: one workgroup per SELC_SEGS staging segments of a bucket */
+    const uint32_t segSh = pick_seg_shift(spanT, c->seg_override);
+    uint64_t nsel = 0;
+    for (uint32_t b = 0; b < B; ++b) {
+        sel0[b] = (uint32_t)nsel;
+        const uint64_t segs = (uint64_t)(span0[b + 1] - span0[b]) << segSh;
+        nsel += (segs + SELC_SEGS - 1) / SELC_SEGS;
+    }
+    sel0[B] = (uint32_t)nsel;
+    if (nsel > c->max_sel) return NSML_ECAP;
 
     /* the stream may still be using the old tables */
     NSML_HIP(c, hipStreamSynchronize(st));
     c->tables_valid = false;
     c->B = 0;
-    const size_t need = sizeof(uint64_t) * B1 + 3 * sizeof(uint32_t) * B1;
+    const size_t need = sizeof(uint64_t) * B1 + 4 * sizeof(uint32_t) * B1;
     if (need > c->pinned_bytes) return NSML_ECAP;
     uint8_t *hp = static_cast<uint8_t *>(c->pinned);
     uint8_t *hp_t = hp + sizeof(uint64_t) * B1;
     uint8_t *hp_s = hp_t + sizeof(uint32_t) * B1;
     uint8_t *hp_m = hp_s + sizeof(uint32_t) * B1;
+    uint8_t *hp_l = hp_m + sizeof(uint32_t) * B1;
+    memcpy(hp_l, sel0.data(), sizeof(uint32_t) * B1);
     memcpy(hp, off, sizeof(uint64_t) * B1);
     memcpy(hp_t, tile0.data(), sizeof(uint32_t) * B1);
     memcpy(hp_s, span0.data(), sizeof(uint32_t) * B1);
@@ -308,16 +332,19 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
     NSML_HIP(c, hipMemcpyAsync(c->d_tile0, hp_t, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
     NSML_HIP(c, hipMemcpyAsync(c->d_span0, hp_s, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
     NSML_HIP(c, hipMemcpyAsync(c->d_samp0, hp_m, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
+    NSML_HIP(c, hipMemcpyAsync(c->d_sel0, hp_l, sizeof(uint32_t) * B1, hipMemcpyHostToDevice, st));
     LAUNCH(c, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)c->d_span0, B,
            (uint32_t)ns, c->d_span_b);
-    LAUNCH(c, KID_SPANMAP, st, k_fill_u32, (B + WG - 1) / WG, c->d_margin, B, MARGIN_INIT);
-    c->hist_ready = false;
+    if (nsel)
+        LAUNCH(c, KID_SPANMAP, st, k_selmap, (uint32_t)((nsel + WG - 1) / WG), (const uint32_t *)c->d_sel0,
+               (const uint32_t *)c->d_span0, B, (uint32_t)nsel, segSh, c->d_selw);
     NSML_HIP(c, hipStreamSynchronize(st));
 
     c->h_off.assign(off, off + B + 1);
     c->B = B; c->n = n;
     c->n_tiles = (uint32_t)nt; c->n_spans = (uint32_t)ns; c->n_samp = (uint32_t)nsamp; c->spanT = spanT;
-    c->segSh = pick_seg_shift(spanT, c->seg_override);
+    c->segSh = segSh;
+    c->n_sel = (uint32_t)nsel;
     return NSML_OK;
 }
 
@@ -334,8 +361,9 @@ int ensure_tables(nsml_ctx *c, double ratio, int bits, hipStream_t st)
         if (rc) return rc;
         for (uint32_t b = 0; b < c->B; ++b) nc += (kb[b] + c->chunk - 1) / c->chunk;
     }
-    if (nc >= 0x7FFFFFFFull) return NSML_ECAP;
+    if (nc >= 0x7FFFFFFFull || nc > c->max_chunks) return NSML_ECAP;
     LAUNCH(c, KID_SETUP, st, k_setup, 1, tables_of(c), ratio, bits);
+    if (nc) LAUNCH(c, KID_SETUP, st, k_chunkmap, (uint32_t)((nc + WG - 1) / WG), (const uint64_t *)c->d_C, c->B, nc, c->d_chunk_b);
     c->K = K; c->NC = nc;
     c->t_ratio = ratio; c->t_bits = bits;
     c->tables_valid = true;
@@ -350,6 +378,7 @@ bool pending_internal_error(nsml_ctx *c)
     volatile uint32_t *f = c->h_flags;
     if (!f || (f[0] | f[1]) == 0u) return false;
     f[0] = 0u; f[1] = 0u;
+    c->zero_clean = false;
     return true;
 }
 
@@ -376,6 +405,8 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
+    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = nullptr;
+    c->d_lcnt = c->d_lkey = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
     c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = nullptr;
@@ -384,8 +415,9 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->max_ratio = max_ratio;
     /* tuning switches: the measured defaults (see nsml_set_option) */
     c->span_override = 0; c->seg_override = 0; c->segSh = 2; c->agg_override = -1; c->group_override = 0;
-    c->force_dense = 0; c->nt_mode = 7; c->nt_dense = -1; c->use_history = 0;
-    c->hist_ready = false; c->hist_ratio = 0.0; c->hist_pruned = false; c->d_margin = nullptr;
+    c->zero_clean = false; c->zero_B = 0;
+    c->persist = 0; c->decomp_variant = -1; c->n_cu = 256;
+    c->force_dense = 0; c->force_rescan = 0; c->nt_mode = 7; c->nt_dense = -1;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
@@ -395,6 +427,10 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     }
     DeviceGuard guard(device);
     if (!guard.ok) { delete c; return NSML_EHIP; }
+    {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->n_cu = cus;
+    }
 
     /* every bucket can add one partial tile at each end */
     const uint64_t mt = max_n / TILE + 2ull * max_buckets + 2;
@@ -411,28 +447,37 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_tile0, B1)); A(dev_alloc(c, &c->d_span0, B1)); A(dev_alloc(c, &c->d_samp0, B1));
     A(dev_alloc(c, &c->d_k, B1)); A(dev_alloc(c, &c->d_T, B1)); A(dev_alloc(c, &c->d_need, B1));
     A(dev_alloc(c, &c->d_L, B1)); A(dev_alloc(c, &c->d_fast, B1)); A(dev_alloc(c, &c->d_fspan0, B1));
+    A(dev_alloc(c, &c->d_sel0, B1)); A(dev_alloc(c, &c->d_H, B1)); A(dev_alloc(c, &c->d_subLo, B1)); A(dev_alloc(c, &c->d_sh, B1));
     A(dev_alloc(c, &c->d_span_b, mt));
     A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
     A(dev_alloc(c, &c->d_tG, mt)); A(dev_alloc(c, &c->d_tE, mt));
     /* segments: at most 4 per tile-sized span, or one per tile plus a partly filled span per bucket */
     const uint64_t msg = 4 * mt + (uint64_t)MAX_SEG_WAVES * B1;
     A(dev_alloc(c, &c->d_ccnt, msg)); A(dev_alloc(c, &c->d_cG, msg)); A(dev_alloc(c, &c->d_cE, msg));
+    /* k_select_count workgroups: 16 segments each; the geometries the library picks itself have
+     * at most one segment per tile from 16384 tiles up */
+    c->max_sel = (uint32_t)(((mt > 16384 ? mt : 16384) + (uint64_t)MAX_SEG_WAVES * B1) / SELC_SEGS + B1);
+    A(dev_alloc(c, &c->d_selw, c->max_sel));
+    A(dev_alloc(c, &c->d_lcnt, c->max_sel));
+    A(dev_alloc(c, &c->d_lkey, (uint64_t)c->max_sel * LCAP));
     A(dev_alloc(c, &c->d_cidx, c->max_cand)); A(dev_alloc(c, &c->d_cval, c->max_cand));
     {   /* survivor values in final order: ceil(ratio * n_b) per bucket, at most one more than
          * ratio * n_b each */
         uint64_t mv = (uint64_t)ceil(max_ratio * (double)max_n) + max_buckets;
         if (mv > max_n) mv = max_n;
         A(dev_alloc(c, &c->d_v, mv));
+        /* chunks of the payload: every bucket can end with a short one */
+        c->max_chunks = mv / chunk + max_buckets + 1;
+        A(dev_alloc(c, &c->d_chunk_b, c->max_chunks)); A(dev_alloc(c, &c->d_chunk_seg, c->max_chunks));
     }
     A(dev_alloc(c, &c->d_ts, mt + B1 + 1));
     A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
     A(dev_alloc(c, &c->d_pmask, mt * (TILE / 32)));
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
-    A(dev_alloc(c, &c->d_margin, B1));
     A(dev_alloc(c, &c->d_wT, B1)); A(dev_alloc(c, &c->d_wfast, B1)); A(dev_alloc(c, &c->d_wcut, B1));
     A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1));
     if (rc == NSML_OK) {
-        c->pinned_bytes = B1 * 20;
+        c->pinned_bytes = B1 * 24;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
         if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
     }
@@ -463,8 +508,8 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
-                    c->d_Tw, c->d_needw, c->d_margin, c->d_wT, c->d_wfast, c->d_wcut,
-                    c->d_wLo, c->d_wHi};
+                    c->d_Tw, c->d_needw, c->d_wT, c->d_wfast, c->d_wcut,
+                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->h_flags) (void)hipHostFree(c->h_flags);
@@ -506,6 +551,8 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     const uint32_t n_ss = c->n_spans << c->segSh;
     const uint32_t eblock = 64u << c->segSh;
     const uint32_t fgrid = c->n_spans < SIDE_GRID ? c->n_spans : SIDE_GRID;
+    uint32_t egrid = c->n_spans;         /* streaming pass: one workgroup per span, or a fixed number per compute unit */
+    if (c->persist > 0 && (uint32_t)(c->persist * c->n_cu) < egrid) egrid = (uint32_t)(c->persist * c->n_cu);
 
     if (weights) {
         /* Algorithm 2 Step 2: threshold and cut of |w| per bucket (bitmap for the buckets that
@@ -531,9 +578,9 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
         else
             LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
-        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags + 1, 0);
+        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags + 1);
         LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cgw + fgrid, weights, tw, cdw, h.c2, h.f2, cgw);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags + 1, 0, c->d_wT);
+        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags + 1, c->d_wT);
         LAUNCH(c, KID_COUNT, st, k_count<64>, cgw + fgrid, weights, tw, cdw, c->d_tG, c->d_tE, cgw);
         LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cdw.G, cdw.E, c->d_tG, c->d_tE);
         LAUNCH(c, KID_WMASK, st, k_wfinish<64>, cgw + fgrid, weights, tw, cdw, (const uint32_t *)c->d_tG,
@@ -544,98 +591,78 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         t.pmask = c->d_pmask;
     }
 
-    /* where the candidate bounds L_b come from: the thresholds of the previous call when it had
-     * the same layout, ratio and pruning (k_pick<2> left them in place), else a sample of
-     * this gradient */
     const bool pruned = weights != nullptr;
-    const bool from_history = c->use_history && !c->force_dense && c->hist_ready &&
-                              c->hist_ratio == ratio && c->hist_pruned == pruned;
-    const int write_next = (c->use_history && !c->force_dense) ? 1 : 0;
-    c->hist_ready = false;
-    LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
-    if (!from_history) {
-        if (!c->force_dense)
-            LAUNCH(c, KID_SAMPLE, st, k_sample<true>, c->n_samp, grad, (const float *)residual, t, h.hs);
-        LAUNCH(c, KID_PREDICT, st, k_predict, B, t, (const uint32_t *)h.hs, c->force_dense);
-    }
+    /* the kernels below zero what they have read of the per-call histograms and flags, so a fill
+     * is only needed after something else used the area: the weight stage, another bucket
+     * count, a call that did not get to its end */
+    if (pruned || !c->zero_clean || c->zero_B != B)
+        LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
+    c->zero_clean = false;
+    if (!c->force_dense)
+        LAUNCH(c, KID_SAMPLE, st, k_sample<true>, c->n_samp, grad, (const float *)residual, t, h.hs);
+    LAUNCH(c, KID_PREDICT, st, k_predict, B, t, h.hs, c->force_dense);
     if (c->force_dense) {
-        if (weights) LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, true>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq);
-        else LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq);
+        if (weights) LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, true>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq);
+        else LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<false, 7, false>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq);
     } else if (weights) {
-        LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, true>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq);
+        LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, true>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq);
     } else {
         switch (c->nt_mode) {
-        case 1:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 1, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
-        case 3:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 3, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
-        case 5:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 5, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
-        default: LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, false>), c->n_spans, eblock, grad, residual, t, h.h0, cd0, c->d_span_sq); break;
+        case 1:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 1, false>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq); break;
+        case 3:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 3, false>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq); break;
+        case 5:  LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 5, false>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq); break;
+        default: LAUNCHB(c, KID_EF_EMIT, st, (k_ef_emit<true, 7, false>), egrid, eblock, grad, residual, t, h.h0, h.h0b, cd0, c->d_span_sq); break;
         }
     }
-    LAUNCH(c, KID_PLAN, st, k_plan, B, t, (const uint32_t *)h.h0, (const uint32_t *)cd0.cnt,
-           c->force_dense ? 0 : 1, (const double *)c->d_span_sq, c->d_l2sq);
+    LAUNCH(c, KID_PLAN, st, k_plan, B, t, h.h0, h.h0b, cd0, c->force_dense ? 0 : 1,
+           (const double *)c->d_span_sq, c->d_l2sq);
     LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
-    /* every stage serves both kinds of bucket: candidate segments first, then the dense
-     * spans of the buckets the candidates could not decide */
     const float *acc = residual;
-    /* lanes per candidate segment: a segment is expected to hold about 1.5 * ratio of the
-     * elements it covers, and a group of lanes fetches 4 entries per lane at a time */
-    const double per_seg = 1.5 * ratio * (double)((c->spanT * TILE) >> c->segSh);
-    uint32_t group = per_seg < 7.0 ? 4u : per_seg < 48.0 ? 16u : 64u;
-    if (c->group_override == 4 || c->group_override == 16 || c->group_override == 64) group = (uint32_t)c->group_override;
-    /* wavefronts of the candidate role: one per chunk of 64 segments, or several per chunk
-     * (each taking a share of its rounds) while that does not fill the grid */
-    Cand cd = cd0;
-    const uint32_t n_chunks = (n_ss + 63) / 64;
-    const uint32_t max_split = group == 4 ? 2u : group == 16 ? 4u : 6u;   /* log2 of the rounds per chunk */
-    cd.splitSh = 0;
-    while (cd.splitSh < max_split && ((uint64_t)n_chunks << cd.splitSh) < 4ull * SIDE_GRID) ++cd.splitSh;
-    const uint64_t cwaves = (uint64_t)n_chunks << cd.splitSh;
-    const uint32_t cgrid = (uint32_t)((cwaves + 3) / 4 < SIDE_GRID ? (cwaves + 3) / 4 : SIDE_GRID);
-    const uint32_t cg = c->force_dense ? 0u : cgrid;
-#define NSML_BY_GROUP(kid, K, ...)                                                          \
-    do {                                                                                    \
-        if (group == 4) LAUNCH(c, kid, st, (K(4)), cg + fgrid, __VA_ARGS__);                \
-        else if (group == 16) LAUNCH(c, kid, st, (K(16)), cg + fgrid, __VA_ARGS__);         \
-        else LAUNCH(c, kid, st, (K(64)), cg + fgrid, __VA_ARGS__);                          \
-    } while (0)
-#define NSML_K_REFINE1(G) k_refine<1, G>
-#define NSML_K_REFINE2(G) k_refine<2, G>
-#define NSML_K_COUNT(G) k_count<G>
-#define NSML_K_WRITE(G) k_write<G>
-    if (cg && (c->agg_override > 0 || (c->agg_override < 0 && n_chunks >= 8u * AGG_GRID))) {
-        /* many segments per workgroup: count the level-1 digits in LDS over a contiguous range
-         * of chunks and add each bucket's histogram once (a third of the global atomics) */
-        const uint32_t ag = AGG_GRID;
-        if (group == 4) LAUNCH(c, KID_REFINE1, st, (k_refine<1, 4, true>), ag + fgrid, acc, t, cd, h.c1, h.f1, ag);
-        else if (group == 16) LAUNCH(c, KID_REFINE1, st, (k_refine<1, 16, true>), ag + fgrid, acc, t, cd, h.c1, h.f1, ag);
-        else LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), ag + fgrid, acc, t, cd, h.c1, h.f1, ag);
-    } else {
-        NSML_BY_GROUP(KID_REFINE1, NSML_K_REFINE1, acc, t, cd, h.c1, h.f1, cg);
-    }
-    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags, 0);
-    NSML_BY_GROUP(KID_REFINE2, NSML_K_REFINE2, acc, t, cd, h.c2, h.f2, cg);
-    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags, write_next);
-    NSML_BY_GROUP(KID_COUNT, NSML_K_COUNT, acc, t, cd, c->d_tG, c->d_tE, cg);
-    LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE);
-    NSML_BY_GROUP(KID_WRITE, NSML_K_WRITE, acc, t, cd, (const uint32_t *)c->d_tG, (const uint32_t *)c->d_tE,
-                  idx, vdst, cg);
-#undef NSML_BY_GROUP
-#undef NSML_K_REFINE1
-#undef NSML_K_REFINE2
-#undef NSML_K_COUNT
-#undef NSML_K_WRITE
     const uint32_t qgrid = (uint32_t)c->NC;
+    const uint32_t seg_grid = (n_ss + WG / 64 - 1) / (WG / 64);       /* one wavefront per staging segment ... */
+    const uint32_t hard_grid = seg_grid < 4096u ? seg_grid : 4096u;   /* ... in a grid that loops over them */
+    if (!c->force_dense) {
+        /* buckets decided from their staged elements: undecided keys set apart, threshold and
+         * survivor order per bucket, then the payload of the candidate-path buckets */
+        const uint4 *selw = c->d_selw;
+        LAUNCH(c, KID_SELECT, st, k_select_count, c->n_sel, t, cd0, selw, h.tail_ovf, c->d_lcnt, c->d_lkey);
+        LAUNCHB(c, KID_FINISH, st, k_select_finish, B, SEL_THREADS, t, cd0, (const uint32_t *)c->d_sel0, h.tail_ovf,
+                (const uint32_t *)c->d_lcnt, (const uint32_t *)c->d_lkey, c->d_chunk_seg, c->d_flags,
+                c->force_rescan);
+        {
+            const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
+            switch (bits) {
+            case 32: LAUNCH(c, KID_ENCODE, st, k_encode<32>, qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
+            case 16: LAUNCH(c, KID_ENCODE, st, k_encode<16>, qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
+            case 8:  LAUNCH(c, KID_ENCODE, st, k_encode<8>,  qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
+            default: LAUNCH(c, KID_ENCODE, st, k_encode<4>,  qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
+            }
+        }
+    }
+    /* buckets whose staged elements cannot decide them (usually none: these launches find an
+     * empty work list and leave): threshold by passes over the dense accumulator */
+    Cand cd = cd0;
+    LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, acc, t, cd, h.c1, h.f1, 0u);
+    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags, (uint32_t *)nullptr, 1);
+    LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, acc, t, cd, h.c2, h.f2, 0u);
+    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags, (uint32_t *)nullptr, 1);
+    LAUNCH(c, KID_COUNT, st, k_segcount_dense, hard_grid, acc, t, cd);
+    LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE, 1);
+    /* every bucket whose survivors come from the dense accumulator (band, zero threshold, dense
+     * passes): ordered write of indices and values, then the value coding */
+    const uint32_t dense_paths = (1u << PATH_DENSE) | (1u << PATH_BAND) | (1u << PATH_ZERO);
+    if (bits == 32) LAUNCH(c, KID_WRITE, st, k_write_dense<true>, hard_grid, residual, t, cd, idx, vdst, dense_paths);
+    else LAUNCH(c, KID_WRITE, st, k_write_dense<false>, hard_grid, residual, t, cd, idx, vdst, dense_paths);
     switch (bits) {
-    case 32: LAUNCH(c, KID_QUANT, st, k_quant<32>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
-    case 16: LAUNCH(c, KID_QUANT, st, k_quant<16>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
-    case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
-    default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales); break;
+    case 32: break;        /* the ordered write left values and residual in their final state */
+    case 16: LAUNCH(c, KID_QUANT, st, k_quant<16>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, 1); break;
+    case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, 1); break;
+    default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, 1); break;
     }
     c->have_l2 = true;
     c->have_prune = pruned;
-    c->hist_ready = write_next != 0;
-    c->hist_ratio = ratio;
-    c->hist_pruned = pruned;
+    c->zero_clean = true;
+    c->zero_B = B;
     return NSML_OK;
 }
 
@@ -657,7 +684,7 @@ int nsml_compress_pruned(nsml_ctx *c, const float *grad, float *residual, const 
 /* The launches of one decompress: tile-start table, then the dense output.  c may be NULL
  * (the entry point without a context): then nothing is profiled and no error code is kept. */
 static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint64_t K, uint32_t n_spans,
-                             uint32_t *d_ts, int nt_dense, const uint32_t *idx, const void *val,
+                             uint32_t *d_ts, int nt_dense, int variant, const uint32_t *idx, const void *val,
                              const float *scales, int bits, float *dense_out)
 {
     if (K >= (4ull << 20)) {
@@ -668,7 +695,7 @@ static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint6
         LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, K, d_ts);
     }
     const uint32_t *ts = d_ts;
-    if (t.spanT >= MAX_SPAN_TILES) {
+    if (variant > 0 || (variant < 0 && t.spanT >= MAX_SPAN_TILES)) {
         /* the largest gradients: one wavefront per tile, direct stores (plain unless asked otherwise) */
         const uint32_t dblock = 64u * t.spanT;
         if (nt_dense > 0) {
@@ -721,7 +748,7 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     if (rc) return rc;
     rc = ensure_tables(c, ratio, bits, st);
     if (rc) return rc;
-    return launch_decompress(c, st, tables_of(c), c->K, c->n_spans, c->d_ts, c->nt_dense, idx, val, scales,
+    return launch_decompress(c, st, tables_of(c), c->K, c->n_spans, c->d_ts, c->nt_dense, c->decomp_variant, idx, val, scales,
                              bits, dense_out);
 }
 
@@ -846,7 +873,7 @@ int nsml_decompress_static(const uint32_t *idx, const void *val, const float *sc
     LAUNCH(none, KID_SETUP, st, k_setup, 1, t, ratio, bits);
     LAUNCH(none, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)m.span0, B,
            (uint32_t)ns, m.span_b);
-    return launch_decompress(none, st, t, K, (uint32_t)ns, m.ts, -1, idx, val, scales, bits, dense_out);
+    return launch_decompress(none, st, t, K, (uint32_t)ns, m.ts, -1, -1, idx, val, scales, bits, dense_out);
 }
 
 int nsml_decompress_accumulate(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,
@@ -988,17 +1015,21 @@ int nsml_set_option(nsml_ctx *c, const char *name, int value)
     } else if (is("force_dense")) {
         if (value != 0 && value != 1) return NSML_EINVAL;
         c->force_dense = value;
-        c->hist_ready = false;
     } else if (is("nt")) {
         if (value != 1 && value != 3 && value != 5 && value != 7) return NSML_EINVAL;
         c->nt_mode = value;
     } else if (is("nt_dense")) {
         if (value < -1 || value > 1) return NSML_EINVAL;
         c->nt_dense = value;
-    } else if (is("history")) {
+    } else if (is("persist")) {
+        if (value < 0 || value > 8) return NSML_EINVAL;
+        c->persist = value;
+    } else if (is("decomp_variant")) {
+        if (value < -1 || value > 1) return NSML_EINVAL;
+        c->decomp_variant = value;
+    } else if (is("rescan")) {
         if (value != 0 && value != 1) return NSML_EINVAL;
-        c->use_history = value;
-        c->hist_ready = false;
+        c->force_rescan = value;
     } else if (is("trip_check")) {
         if (value != 1) return NSML_EINVAL;
         *(volatile uint32_t *)&c->h_flags[0] = 1u;

@@ -49,41 +49,88 @@ __global__ __launch_bounds__(WG) void k_sample(const float *__restrict__ g, cons
     hist_flush(h, hist_s + (uint64_t)b * NB0, NB0);
 }
 
-/* Per bucket: choose the candidate bound L_b from the sample histogram.  The sample count
- * above the true k-th key is binomial with mean ks = k * m / n; asking for ks + 4 sqrt(ks) + 4
- * sampled entries above L_b leaves the candidates short of k only a few times in 1e5 buckets,
- * and then the dense fallback still gives the exact result. */
-__global__ __launch_bounds__(WG) void k_predict(Tables t, const uint32_t *__restrict__ hist_s,
+/* Per bucket: what the streaming pass stages, from the sample histogram.  The sample count
+ * above the true k-th key is binomial with mean ks = k * m / n.
+ *   candidates  k at most an eighth of the bucket: L_b = lower edge of the digit that has
+ *               ks + 4 sqrt(ks) + 4 sampled keys above it; everything from L_b up is staged and
+ *               contains the k largest unless the sample was very unlucky
+ *   band        larger k (ratios towards 1): staging everything above a bound would be most of
+ *               the bucket, so only the level-0 digits between the ranks ks +- (4 sqrt(ks) + 4)
+ *               are staged, [L_b, H_b); the elements above H_b are survivors for certain and are
+ *               only counted
+ *   zero        even the optimistic rank lies among keys below 2^19 (in practice: exact zeros,
+ *               as in an embedding whose rows were not touched), or k is the whole bucket: the
+ *               threshold key is 0, nothing is staged, non-zero and zero keys are counted
+ * A bucket for which none of this fits (or whose guess turns out wrong once the exact histogram
+ * is known) takes the dense passes and still gets the exact result. */
+__global__ __launch_bounds__(WG) void k_predict(Tables t, uint32_t *__restrict__ hist_s,
                                                 int force_dense)
 {
     __shared__ uint32_t tmp[WG];
+    __shared__ uint32_t res[9];          /* digit, above, at for three ranks */
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const uint64_t nb = t.off[b + 1] - t.off[b];
     const uint32_t k = t.k[b];
+    if (b == 0 && tid == 0) t.nhard[0] = 0u;       /* counted anew by this call's plan */
     if (nb == 0 || force_dense) {
-        if (tid == 0) t.L[b] = NONE;
+        if (tid == 0) { t.L[b] = NONE; t.H[b] = NONE; t.subLo[b] = NONE; }
+        return;
+    }
+    if ((uint64_t)k == nb) {             /* everything is sent: all keys >= 1, and the zeros as ties of key 0 */
+        if (tid == 0) { t.L[b] = 1u; t.H[b] = 1u; t.subLo[b] = NONE; }
+        for (int i = tid; i < NB0; i += WG) hist_s[(uint64_t)b * NB0 + i] = 0u;     /* left clean for the next call */
         return;
     }
     DigitWalk<NB0> w;
     w.load(hist_s + (uint64_t)b * NB0, tmp);
+    w.clear(hist_s + (uint64_t)b * NB0);
     const uint32_t m = w.total;
+    if (m == 0) {
+        if (tid == 0) { t.L[b] = NONE; t.H[b] = NONE; t.subLo[b] = NONE; }
+        return;
+    }
     const bool exact = nb < SAMPLE_ALL_BELOW;
     /* the sample was drawn from the parameters that can be selected: all of them, or the
      * ones the pruning step kept */
     const double pop = t.w ? (double)t.kw[b] : (double)nb;
     const double ks = (double)k * (double)m / pop;
-    const double want_d = exact ? (double)k : ceil(ks + 4.0 * sqrt(ks) + 4.0);
+    const double dev = exact ? 0.0 : 4.0 * sqrt(ks) + 4.0;
+    const double want_d = exact ? (double)k : ceil(ks + dev);
     const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
-    if (m == 0 || want_d > (double)m || (double)k > 0.5 * cap_b) {
-        /* not enough sample above any bound, or k too large for the staging area */
-        if (tid == 0) t.L[b] = NONE;
-        return;
-    }
+    double r_up = floor(ks - dev), r_dn = ceil(ks + dev);
+    r_up = r_up < 1.0 ? 1.0 : (r_up > (double)m ? (double)m : r_up);
+    r_dn = r_dn < 1.0 ? 1.0 : (r_dn > (double)m ? (double)m : r_dn);
+    const double r_c = want_d > (double)m ? (double)m : (want_d < 1.0 ? 1.0 : want_d);
     uint32_t digit, above, at;
-    if (w.find((uint32_t)want_d, digit, above, at)) {
-        const double est = (double)(above + at) * pop / (double)m;
-        t.L[b] = est <= 0.8 * cap_b ? (digit << SH0) : NONE;
+    if (w.find((uint32_t)r_c, digit, above, at)) { res[0] = digit; res[1] = above; res[2] = at; }
+    if (w.find((uint32_t)r_up, digit, above, at)) { res[3] = digit; res[4] = above; res[5] = at; }
+    if (w.find((uint32_t)r_dn, digit, above, at)) { res[6] = digit; res[7] = above; res[8] = at; }
+    __syncthreads();
+    if (tid != 0) return;
+    uint32_t L = NONE, H = NONE;
+    bool done = false;
+    if (want_d <= (double)m && (double)k <= 0.5 * cap_b) {
+        const double est = (double)(res[1] + res[2]) * pop / (double)m;
+        if (est <= 0.8 * cap_b) { L = res[0] << SH0; done = true; }
     }
+    if (!done) {
+        const uint32_t dig_up = res[3], dig_dn = res[6];
+        if (dig_up == 0u) {
+            L = 1u; H = 1u;
+        } else if (dig_dn != 0u) {
+            const double in_band = (double)(res[7] + res[8]) - (double)res[4];
+            const double est = in_band * pop / (double)m;
+            if (est <= 0.8 * cap_b) { L = dig_dn << SH0; H = (dig_up + 1u) << SH0; }
+        }
+    }
+    t.L[b] = L;
+    t.H[b] = H;
+    /* the k-th key lies, very likely, in one of the level-0 digits between the two ranks: the
+     * streaming pass counts six more key bits inside them, so that the plan knows the threshold to
+     * 18 bits and only 1/64 of such a digit stays undecided.  (With error feedback the
+     * accumulators pile up just below the threshold: one level-0 digit there can hold 4 % of a
+     * bucket.) */
+    t.subLo[b] = (L != NONE && L != H) ? res[6] : NONE;
 }
 
 /* ------------------------------------------------------------------ the streaming pass */
@@ -119,12 +166,22 @@ __device__ __forceinline__ void emit_quad(const bool (&f)[4], const float (&a)[4
  * of a[0].  Stores the accumulator, counts its level-0 digits and appends candidates. */
 template <bool INTERIOR, bool EMIT, int NT, bool PRUNE>
 __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const float (&a)[4],
-                                       uint32_t m, uint32_t cm, uint32_t li, uint32_t *h, uint32_t L,
-                                       const Cand &c, uint64_t cbase, uint32_t &wcount)
+                                       uint32_t m, uint32_t cm, uint32_t li, uint32_t *h, uint32_t *hb, uint32_t subLo,
+                                       uint32_t L, uint32_t H,
+                                       const Cand &c, uint64_t cbase, uint32_t &wcount, uint32_t &n_hi, uint32_t &n_lo)
 {
     uint32_t key[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) key[j] = keyof(a[j]);
+    if (EMIT) {
+        /* the finer histogram of the few digits around the expected threshold */
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t dd = (key[j] >> SH0) - subLo;
+            if (((cm >> j) & 1u) && dd < (uint32_t)SUB_DIGITS)
+                atomicAdd(&hb[(dd << SUB_BITS) | ((key[j] >> SHS) & ((1u << SUB_BITS) - 1u))], 1u);
+        }
+    }
     if (INTERIOR) {
         f4 v; v.x = a[0]; v.y = a[1]; v.z = a[2]; v.w = a[3];
         if (NT & 4) __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(r + gi));
@@ -146,8 +203,16 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
     if (EMIT) {
         bool f[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) f[j] = ((cm >> j) & 1u) && key[j] >= L;
+        for (int j = 0; j < 4; ++j) f[j] = ((cm >> j) & 1u) && key[j] >= L && key[j] < H;
         emit_quad(f, a, li, c, cbase, wcount);
+        if (H != NONE) {
+            /* a band is staged: count what lies above it (survivors for certain) and below it */
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                n_hi += __popcll(__ballot(((cm >> j) & 1u) && key[j] >= H));
+                n_lo += __popcll(__ballot(((cm >> j) & 1u) && key[j] < L));
+            }
+        }
     }
 }
 
@@ -160,20 +225,41 @@ __device__ __forceinline__ void ef_row(float *__restrict__ r, uint64_t gi, const
 constexpr uint32_t MAX_SEG_WAVES = 16;
 template <bool EMIT, int NT, bool PRUNE>
 __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__restrict__ g, float *__restrict__ r,
-                                                Tables t, uint32_t *__restrict__ hist0, Cand c,
-                                                double *__restrict__ span_sq)
+                                                Tables t, uint32_t *__restrict__ hist0, uint32_t *__restrict__ hist0b,
+                                                Cand c, double *__restrict__ span_sq)
 {
     __shared__ uint32_t h[NB0];
+    __shared__ uint32_t hb[NBS];
     __shared__ double sq_w[MAX_SEG_WAVES];
-    double sq = 0.0;                     /* sum of grad^2 over this thread's elements */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nthreads = 64u << t.segSh;
-    for (uint32_t i = tid; i < NB0; i += nthreads) h[i] = 0;
-    const SpanGeo s = span_geo(t, blockIdx.x);
+    /* a workgroup takes a contiguous share of the spans (one span each when the grid has as many
+     * workgroups as there are spans); the LDS histogram is flushed when the bucket changes */
+    const uint32_t share = (t.n_spans + gridDim.x - 1) / gridDim.x;
+    const uint32_t sp0 = blockIdx.x * share, sp1 = min(t.n_spans, sp0 + share);
+    uint32_t cur_b = NONE;
+    for (uint32_t span = sp0; span < sp1; ++span) {
+    double sq = 0.0;                     /* sum of grad^2 over this thread's elements */
+    const SpanGeo s = span_geo(t, span);
+    if (s.b != cur_b) {
+        if (cur_b != NONE) {
+            __syncthreads();
+            hist_flush(h, hist0 + (uint64_t)cur_b * NB0, NB0, (int)nthreads);
+            if (EMIT) hist_flush(hb, hist0b + (uint64_t)cur_b * NBS, NBS, (int)nthreads);
+            __syncthreads();
+        }
+        for (uint32_t i = tid; i < NB0; i += nthreads) h[i] = 0;
+        if (EMIT) for (uint32_t i = tid; i < NBS; i += nthreads) hb[i] = 0;
+        cur_b = s.b;
+    }
+    uint32_t subLo = EMIT ? t.subLo[s.b] : NONE;
+    if (subLo == NONE) subLo = 0x80000000u;              /* no digit is within reach of it */
     const uint32_t L = EMIT ? t.L[s.b] : NONE;
+    const uint32_t H = EMIT ? t.H[s.b] : NONE;           /* NONE: no upper bound */
+    uint32_t n_hi = 0, n_lo = 0;                          /* band mode: elements above / below the band */
     const uint32_t wT = PRUNE ? t.wT[s.b] : 0u;          /* NONE: this bucket's mask is in the bitmap */
     const uint32_t wcut = PRUNE ? t.wcut[s.b] : 0u;
-    const uint32_t ss = (blockIdx.x << t.segSh) + wave;
+    const uint32_t ss = (span << t.segSh) + wave;
     const uint64_t cbase = (uint64_t)ss * c.cap;
     uint32_t wcount = 0;
     __syncthreads();
@@ -214,7 +300,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
                     } else
                         cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
                 }
-                ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount);
+                ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, hb, subLo, L, H, c, cbase, wcount, n_hi, n_lo);
             }
         } else {
 #pragma unroll
@@ -227,13 +313,14 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
                 for (int j = 0; j < 4; ++j) { a[j] = __fadd_rn(x[j], y[j]); sq += (double)__fmul_rn(x[j], x[j]); }
                 uint32_t cm = m;
                 if (PRUNE) cm &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
-                ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, L, c, cbase, wcount);
+                ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, hb, subLo, L, H, c, cbase, wcount, n_hi, n_lo);
             }
         }
     }
     if (EMIT && lane == 0) {
         c.cnt[ss] = min(wcount, c.cap);
         if (wcount > c.cap) t.ovf[s.b] = 1u;
+        if (H != NONE) { c.G[ss] = n_hi; c.E[ss] = n_lo; }
     }
     /* the span's share of |grad|^2 (by-product for the density test of Algorithm 2 Step 1):
      * fixed reduction tree, so the sum does not depend on scheduling */
@@ -244,62 +331,128 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     if (tid == 0) {
         double tot = 0.0;
         for (uint32_t w = 0; w < (1u << t.segSh); w += 4) tot += (sq_w[w] + sq_w[w + 1]) + (sq_w[w + 2] + sq_w[w + 3]);
-        span_sq[blockIdx.x] = tot;
+        span_sq[span] = tot;
     }
-    hist_flush(h, hist0 + (uint64_t)s.b * NB0, NB0, (int)nthreads);
+    }
+    __syncthreads();
+    if (cur_b != NONE) {
+        hist_flush(h, hist0 + (uint64_t)cur_b * NB0, NB0, (int)nthreads);
+        if (EMIT) hist_flush(hb, hist0b + (uint64_t)cur_b * NBS, NBS, (int)nthreads);
+    }
 }
 
-constexpr uint32_t MARGIN_INIT = 1u << 20;   /* 1/8 octave below the last threshold */
-constexpr uint32_t MARGIN_MIN = 1u << 15, MARGIN_MAX = 1u << 22;
-
-/* Per bucket: exact level-0 digit of the k-th largest key, and whether the candidates can
- * decide the bucket: they are exactly the elements with key >= L_b, so they contain the k
- * largest iff there are at least k of them (and no staging segment overflowed).  In history
- * mode the distance between L_b and the threshold is steered by how many candidates came. */
-__global__ __launch_bounds__(WG) void k_plan(Tables t, const uint32_t *__restrict__ hist0,
-                                             const uint32_t *__restrict__ cand_cnt, int have_cand,
+/* Per bucket: exact level-0 digit of the k-th largest key, the gradient's |.|^2, and how the
+ * bucket is decided (PATH_*).  The staged elements can decide it when they are known to hold
+ * every element of that digit: in candidate mode they are exactly the elements with key >= L_b,
+ * so they do iff there are at least k of them; in band mode iff the digit lies inside the band;
+ * in both only if no staging segment overflowed and the undecided keys of the digit are few
+ * enough to fit the free part of the staging area (k_select parks them there).  In zero mode
+ * the counts settle everything: fewer non-zero elements than k means threshold key 0. */
+__global__ __launch_bounds__(WG) void k_plan(Tables t, uint32_t *__restrict__ hist0, uint32_t *__restrict__ hist0b,
+                                             Cand c, int have_cand,
                                              const double *__restrict__ span_sq, double *__restrict__ l2sq)
 {
     __shared__ uint32_t tmp[WG];
+    __shared__ uint32_t fnd[4];          /* digit, above, at of the k-th key; whether any thread found it */
     __shared__ double red[WG / 64];
-    __shared__ uint32_t redc[WG / 64];
+    __shared__ uint32_t redc[WG / 64], redh[WG / 64];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
-    uint32_t n_cand = 0;
-    {   /* |grad|^2 of the bucket: strided partial sums, then a fixed tree; candidates likewise */
+    const uint32_t L = t.L[b], H = t.H[b];
+    uint32_t n_cand = 0, n_hi = 0;
+    {   /* |grad|^2 of the bucket: strided partial sums, then a fixed tree; staged counts likewise */
         double acc = 0.0;
         for (uint32_t s = t.span0[b] + tid; s < t.span0[b + 1]; s += WG) acc += span_sq[s];
-        uint32_t cc = 0;
-        if (have_cand)
-            for (uint32_t ss = (t.span0[b] << t.segSh) + tid; ss < (t.span0[b + 1] << t.segSh); ss += WG) cc += cand_cnt[ss];
+        uint32_t cc = 0, ch = 0;
+        if (have_cand && L != NONE)
+            for (uint32_t ss = (t.span0[b] << t.segSh) + tid; ss < (t.span0[b + 1] << t.segSh); ss += WG) {
+                cc += c.cnt[ss];
+                if (H != NONE) ch += c.G[ss];
+            }
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) { acc += __shfl_xor(acc, d, 64); cc += __shfl_xor(cc, d, 64); }
-        if ((tid & 63) == 0) { red[tid >> 6] = acc; redc[tid >> 6] = cc; }
+        for (int d = 32; d >= 1; d >>= 1) { acc += __shfl_xor(acc, d, 64); cc += __shfl_xor(cc, d, 64); ch += __shfl_xor(ch, d, 64); }
+        if ((tid & 63) == 0) { red[tid >> 6] = acc; redc[tid >> 6] = cc; redh[tid >> 6] = ch; }
         __syncthreads();
         if (tid == 0) l2sq[b] = (red[0] + red[1]) + (red[2] + red[3]);
         n_cand = redc[0] + redc[1] + redc[2] + redc[3];
+        n_hi = redh[0] + redh[1] + redh[2] + redh[3];
     }
     const uint32_t want = t.k[b];
     if (want == 0) {                       /* empty bucket: nothing can match */
-        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; t.fast[b] = 1u; }
+        if (tid == 0) { t.T[b] = NONE; t.need[b] = 0; t.fast[b] = PATH_CAND; }
         return;
     }
     DigitWalk<NB0> w;
     w.load(hist0 + (uint64_t)b * NB0, tmp);
-    uint32_t digit, above, at;
-    if (w.find(want, digit, above, at)) {
-        t.T[b] = digit;
-        t.need[b] = want - above;
-        const uint32_t L = t.L[b];
-        const bool valid = have_cand && L != NONE && n_cand >= want && !t.ovf[b];
-        t.fast[b] = valid ? 1u : 0u;
-        /* margin control for the next call */
-        uint32_t mg = t.margin[b];
-        if (L != NONE) {
-            if (!valid) mg = min(MARGIN_MAX, mg * 4u);
-            else if ((uint64_t)n_cand * 5u > (uint64_t)want * 8u) mg = max(MARGIN_MIN, mg - mg / 4u);   /* > 1.6 k */
-            else if ((uint64_t)n_cand * 20u < (uint64_t)want * 23u) mg = min(MARGIN_MAX, mg + mg / 4u); /* < 1.15 k */
+    w.clear(hist0 + (uint64_t)b * NB0);        /* left clean for the next call, like the overflow flag below */
+    const uint32_t ovf = t.ovf[b];
+    if (tid == 0 && ovf) t.ovf[b] = 0u;
+    /* the finer counts of the digits around the expected threshold: fetched by the first
+     * wavefront (64 bins of whichever digit it turns out to be), zeroed again for the next call */
+    const uint32_t subLo = t.subLo[b];
+    uint32_t subrow[SUB_DIGITS];
+#pragma unroll
+    for (int d = 0; d < SUB_DIGITS; ++d) {
+        uint32_t *p = hist0b + (uint64_t)b * NBS + (d << SUB_BITS) + ((1u << SUB_BITS) - 1u - tid);   /* top bin first */
+        subrow[d] = 0u;
+        if (tid < (1u << SUB_BITS) && subLo != NONE) { subrow[d] = *p; if (subrow[d]) *p = 0u; }
+    }
+    if (tid == 0) fnd[3] = 0u;
+    __syncthreads();
+    {
+        uint32_t digit, above, at;
+        if (w.find(want, digit, above, at)) { fnd[0] = digit; fnd[1] = above; fnd[2] = at; fnd[3] = 1u; }
+    }
+    __syncthreads();
+    if (tid < 64 && fnd[3]) {
+        const uint32_t digit = fnd[0], above = fnd[1];
+        uint32_t at = fnd[2];
+        uint32_t path = PATH_DENSE, T = digit, need = want - above, sh = SH0;
+        /* six more bits of the threshold from the finer counts, when the digit is among them and
+         * the counts add up (they do unless the digit was not covered) */
+        bool fine = false;
+        uint32_t T18 = 0, need18 = 0, at18 = 0;
+        if (subLo != NONE && digit - subLo < (uint32_t)SUB_DIGITS) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int d = 0; d < SUB_DIGITS; ++d) mine = (digit - subLo == (uint32_t)d) ? subrow[d] : mine;
+            uint32_t incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t y = __shfl_up(incl, d, 64);
+                if (tid >= (uint32_t)d) incl += y;
+            }
+            const uint32_t total = __shfl(incl, 63, 64);
+            const bool here = incl - mine < need && need <= incl;      /* lane = 63 - (the six bits) */
+            const uint64_t bal = __ballot(here);
+            if (total == at && bal) {
+                const uint32_t ln = (uint32_t)__builtin_ctzll(bal);
+                T18 = (digit << SUB_BITS) | (63u - ln);
+                need18 = need - (__shfl(incl, ln, 64) - __shfl(mine, ln, 64));
+                at18 = __shfl(mine, ln, 64);
+                fine = true;
+            }
         }
-        t.margin[b] = mg;
+        if (tid != 0) return;
+        if (have_cand && L != NONE && !ovf) {
+            const uint64_t cap_b = (uint64_t)((t.span0[b + 1] - t.span0[b]) << t.segSh) * c.cap;
+            if (fine) at = at18;
+            const bool room = (uint64_t)at * 2u <= cap_b - (uint64_t)n_cand;     /* for the undecided keys in the tails */
+            if (H == NONE) {
+                if (n_cand >= want && room) path = PATH_CAND;
+            } else if (L == H) {
+                /* n_hi = non-zero keys among the selectable elements: if they are no more than k,
+                 * all of them survive and zeros (lowest indices first) fill the rest */
+                if (n_hi <= want) { path = PATH_ZERO; T = 0u; need = want - n_hi; }
+            } else if ((digit << SH0) >= L && ((digit + 1u) << SH0) <= H && room) {
+                path = PATH_BAND;
+            }
+            if (fine && (path == PATH_CAND || path == PATH_BAND)) { T = T18; need = need18; sh = SHS; }
+        }
+        t.T[b] = T;
+        t.need[b] = need;
+        t.sh[b] = sh;
+        t.fast[b] = path;
+        if (path != PATH_CAND) atomicAdd(t.nhard, 1u);
     }
 }
 
@@ -473,12 +626,13 @@ __device__ __forceinline__ void crefine_agg_body(const Tables &t, const Cand &c,
 template <int LEVEL>
 __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
                                              const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
-                                             int write_next, uint32_t *__restrict__ wT_out = nullptr)
+                                             uint32_t *__restrict__ wT_out = nullptr, int only_fb = 0)
 {
     constexpr int NB = LEVEL == 2 ? NB2 : NB1;
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
     __shared__ uint32_t tmp[WG];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    if (only_fb && t.fast[b]) return;          /* decided by k_select */
     const uint32_t want = t.need[b];
     if (want == 0) {
         /* empty bucket */
@@ -488,6 +642,7 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
     const uint32_t *hist = t.fast[b] ? hist_c : hist_f;
     DigitWalk<NB> w;
     w.load(hist + (uint64_t)b * NB, tmp);
+    if (only_fb) w.clear(const_cast<uint32_t *>(hist) + (uint64_t)b * NB);     /* left clean for the next call */
     if (w.total < want) {                  /* cannot happen: the level above counted them */
         if (tid == 0) err[0] = 1u;
         return;
@@ -501,14 +656,6 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
          * threshold itself (and, next, the last kept index among equal weights); the others a
          * bitmap */
         if (LEVEL == 2 && wT_out) wT_out[b] = t.fast[b] ? T : NONE;
-        if (LEVEL == 2 && write_next) {
-            /* history mode: next call's candidate bound sits a margin below this threshold */
-            const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
-            const uint32_t mg = t.margin[b];
-            /* elements with key >= T: the k survivors plus the equal ones left out */
-            const double ge_T = (double)t.k[b] - (double)(want - above) + (double)at;
-            t.L[b] = ((double)t.k[b] > 0.5 * cap_b || ge_T > 0.8 * cap_b) ? NONE : (T > mg ? T - mg : 0u);
-        }
     }
 }
 
@@ -566,11 +713,16 @@ __device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint
  * travel as one 64-bit word (neither total can reach 2^32: a bucket has fewer elements), and
  * every thread takes four consecutive units, so a round covers 1024 units with one scan. */
 __global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
-                                             uint32_t *__restrict__ tG, uint32_t *__restrict__ tE)
+                                             uint32_t *__restrict__ tG, uint32_t *__restrict__ tE, int only_fb = 0)
 {
     __shared__ uint64_t tmp[WG / 64];
     const uint32_t b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t mode = t.fast[b];
+    uint32_t mode = t.fast[b];
+    if (only_fb) {
+        /* gradient stage: only the buckets on the dense passes, whose counts are per segment too */
+        if (mode != PATH_DENSE) return;
+        mode = 1u;
+    }
     uint32_t *G = mode ? cG : tG, *E = mode ? cE : tE;
     const uint32_t t0 = mode ? t.span0[b] << t.segSh : t.tile0[b];
     const uint32_t t1 = mode ? t.span0[b + 1] << t.segSh : t.tile0[b + 1];

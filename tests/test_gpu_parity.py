@@ -13,15 +13,13 @@ from gpu_util import DEV, Case, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["auto", "history", "dense"])
+@pytest.fixture(autouse=True, params=["auto", "dense"])
 def path(request, monkeypatch):
-    """Every case runs three times: with the single-pass candidate path as shipped (candidate
-    bounds from a sample of the gradient; buckets fall back to the dense passes on their own
-    when they must), with the optional history mode (bounds from the previous call's thresholds
-    when there is one), and with every bucket forced through the dense passes.  The switches are
-    nsml_set_option settings applied to every context the test creates."""
+    """Every case runs twice: with the paths the library picks itself (what the streaming pass
+    stages comes from a sample of the gradient; buckets fall back to the dense passes on their
+    own when they must), and with every bucket forced through the dense passes.  The switches
+    are nsml_set_option settings applied to every context the test creates."""
     monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if request.param == "dense" else 0)
-    monkeypatch.setitem(nsml.Context.default_options, "history", 1 if request.param == "history" else 0)
     return request.param
 
 
@@ -174,6 +172,15 @@ def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
     c.step(0.02, 8)
     c.set_grad(_rand(n, 4243))
     c.step(0.004, 4)
+    # ratios beyond an eighth: a band of keys is staged and the survivors come from the dense
+    # accumulator; then a gradient that is mostly zeros, so that zeros must be sent (threshold key 0)
+    c.set_grad(_rand(n, 4244))
+    c.step(0.3, 8)
+    g2 = _rand(n, 4245)
+    g2[torch.rand(n, device=DEV, generator=torch.Generator(device=DEV).manual_seed(5)) < 0.7] = 0.0
+    c.set_residual(np.zeros(n, dtype=np.float32))
+    c.set_grad(g2)
+    c.step(0.45, 32)
 
 
 @pytest.mark.parametrize("span_tiles", [0, 16])

@@ -11,10 +11,9 @@ from gpu_util import DEV, compare_payload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["auto", "history", "dense"])
+@pytest.fixture(autouse=True, params=["auto", "dense"])
 def path(request, monkeypatch):
     monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if request.param == "dense" else 0)
-    monkeypatch.setitem(nsml.Context.default_options, "history", 1 if request.param == "history" else 0)
     return request.param
 
 

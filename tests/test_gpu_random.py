@@ -23,7 +23,7 @@ def _case(seed, pruned, monkeypatch):
         monkeypatch.setitem(nsml.Context.default_options, k, v)
     monkeypatch.setitem(nsml.Context.default_options, "agg", int(int(rs.randint(0, 2))))
     monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if rs.rand() < 0.15 else 0)
-    monkeypatch.setitem(nsml.Context.default_options, "history", 1 if rs.rand() < 0.3 else 0)
+    monkeypatch.setitem(nsml.Context.default_options, "rescan", 1 if rs.rand() < 0.25 else 0)
     B = int(rs.randint(1, 9))
     sizes = []
     for _ in range(B):
