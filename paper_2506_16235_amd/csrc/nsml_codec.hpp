@@ -9,22 +9,21 @@ namespace {
 
 /* ------------------------------------------------------------------ value coding */
 
-/* One workgroup per chunk of `chunk` consecutive survivors of one bucket: absmax, scale,
+/* A workgroup's work on one chunk of `chunk` consecutive survivors of a bucket whose survivors
+ * were written by k_hard's ordered pass (not PATH_CAND): absmax, scale,
  * codes, packing, and the coding error left in the residual.  Every floating-point step is a
  * single correctly rounded binary32 operation (divide, round-to-nearest-even, multiply,
  * subtract); nothing may be contracted into an fma. */
 template <int BITS>
-__global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const uint32_t *__restrict__ idx,
-                                              Tables t, float *__restrict__ r, void *__restrict__ val,
-                                              float *__restrict__ scales, int only_fb)
+__device__ __forceinline__ void quant_body(const float *__restrict__ v, const uint32_t *__restrict__ idx,
+                                           const Tables &t, float *__restrict__ r, void *__restrict__ val,
+                                           float *__restrict__ scales, const uint32_t *__restrict__ chunk_b,
+                                           uint64_t c)
 {
     __shared__ float red[WG / 64];
-    __shared__ uint32_t sh_b;
-    if (only_fb && t.nhard[0] == 0u) return;   /* every bucket was coded by k_encode */
     const uint32_t tid = threadIdx.x;
-    const uint64_t c = blockIdx.x;
-    const uint32_t b = find_bucket_wg<uint64_t>(t.C, t.B, c, &sh_b);
-    if (only_fb && t.fast[b] == PATH_CAND) return;          /* coded by k_encode */
+    const uint32_t b = chunk_b[c];
+    if (t.fast[b] == PATH_CAND) return;                     /* coded by k_encode */
     const uint64_t cb = c - t.C[b];
     const uint64_t j0 = cb * t.chunk;                         /* first survivor of the chunk, bucket-local */
     const uint32_t cnt = (uint32_t)min((uint64_t)t.chunk, (uint64_t)t.k[b] - j0);

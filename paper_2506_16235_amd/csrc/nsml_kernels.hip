@@ -616,11 +616,8 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     }
     LAUNCH(c, KID_PLAN, st, k_plan, B, t, h.h0, h.h0b, cd0, c->force_dense ? 0 : 1,
            (const double *)c->d_span_sq, c->d_l2sq);
-    LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, t);
-    const float *acc = residual;
     const uint32_t qgrid = (uint32_t)c->NC;
-    const uint32_t seg_grid = (n_ss + WG / 64 - 1) / (WG / 64);       /* one wavefront per staging segment ... */
-    const uint32_t hard_grid = seg_grid < 4096u ? seg_grid : 4096u;   /* ... in a grid that loops over them */
+    const uint32_t seg_grid = (n_ss + WG / 64 - 1) / (WG / 64);       /* one wavefront per staging segment */
     if (!c->force_dense) {
         /* buckets decided from their staged elements: undecided keys set apart, threshold and
          * survivor order per bucket, then the payload of the candidate-path buckets */
@@ -630,34 +627,31 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
                 (const uint32_t *)c->d_lcnt, (const uint32_t *)c->d_lkey, c->d_chunk_seg, c->d_flags,
                 c->force_rescan);
         {
+            /* the launch also carries the ordered write of the band / zero-threshold buckets */
             const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
+            const uint32_t wd = seg_grid < (uint32_t)(2 * c->n_cu) ? seg_grid : (uint32_t)(2 * c->n_cu);
             switch (bits) {
-            case 32: LAUNCH(c, KID_ENCODE, st, k_encode<32>, qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
-            case 16: LAUNCH(c, KID_ENCODE, st, k_encode<16>, qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
-            case 8:  LAUNCH(c, KID_ENCODE, st, k_encode<8>,  qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
-            default: LAUNCH(c, KID_ENCODE, st, k_encode<4>,  qgrid, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags); break;
+            case 32: LAUNCH(c, KID_ENCODE, st, k_encode<32>, qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
+            case 16: LAUNCH(c, KID_ENCODE, st, k_encode<16>, qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
+            case 8:  LAUNCH(c, KID_ENCODE, st, k_encode<8>,  qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
+            default: LAUNCH(c, KID_ENCODE, st, k_encode<4>,  qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
             }
         }
     }
-    /* buckets whose staged elements cannot decide them (usually none: these launches find an
-     * empty work list and leave): threshold by passes over the dense accumulator */
-    Cand cd = cd0;
-    LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), fgrid, acc, t, cd, h.c1, h.f1, 0u);
-    LAUNCH(c, KID_PICK1, st, k_pick<1>, B, t, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags, (uint32_t *)nullptr, 1);
-    LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), fgrid, acc, t, cd, h.c2, h.f2, 0u);
-    LAUNCH(c, KID_PICK2, st, k_pick<2>, B, t, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags, (uint32_t *)nullptr, 1);
-    LAUNCH(c, KID_COUNT, st, k_segcount_dense, hard_grid, acc, t, cd);
-    LAUNCH(c, KID_SCAN, st, k_scan, B, t, cd.G, cd.E, c->d_tG, c->d_tE, 1);
-    /* every bucket whose survivors come from the dense accumulator (band, zero threshold, dense
-     * passes): ordered write of indices and values, then the value coding */
-    const uint32_t dense_paths = (1u << PATH_DENSE) | (1u << PATH_BAND) | (1u << PATH_ZERO);
-    if (bits == 32) LAUNCH(c, KID_WRITE, st, k_write_dense<true>, hard_grid, residual, t, cd, idx, vdst, dense_paths);
-    else LAUNCH(c, KID_WRITE, st, k_write_dense<false>, hard_grid, residual, t, cd, idx, vdst, dense_paths);
-    switch (bits) {
-    case 32: break;        /* the ordered write left values and residual in their final state */
-    case 16: LAUNCH(c, KID_QUANT, st, k_quant<16>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, 1); break;
-    case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, 1); break;
-    default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, 1); break;
+    /* the buckets on the dense passes (usually none: the workgroups read one word and leave): a
+     * fixed grid, resident at once, that does all their steps with barriers between; then the
+     * value coding of every bucket whose survivors were written from the dense accumulator */
+    {
+        const uint32_t hgrid = (uint32_t)c->n_cu;
+        const uint32_t *cb_ = c->d_chunk_b;
+        if (bits == 32) LAUNCH(c, KID_HARD, st, k_hard<true>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, c->d_flags);
+        else LAUNCH(c, KID_HARD, st, k_hard<false>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, c->d_flags);
+        switch (bits) {
+        case 32: break;        /* the ordered write left values and residual in their final state */
+        case 16: LAUNCH(c, KID_QUANT, st, k_quant<16>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, cb_); break;
+        case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, cb_); break;
+        default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, cb_); break;
+        }
     }
     c->have_l2 = true;
     c->have_prune = pruned;

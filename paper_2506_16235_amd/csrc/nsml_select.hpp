@@ -71,7 +71,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, uint32_t *__restrict__
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const uint64_t nb = t.off[b + 1] - t.off[b];
     const uint32_t k = t.k[b];
-    if (b == 0 && tid == 0) t.nhard[0] = 0u;       /* counted anew by this call's plan */
+    if (b == 0 && tid < 4) t.nhard[tid] = 0u;      /* counted anew by this call's plan ([1]: the barrier of k_hard) */
     if (nb == 0 || force_dense) {
         if (tid == 0) { t.L[b] = NONE; t.H[b] = NONE; t.subLo[b] = NONE; }
         return;
@@ -453,13 +453,14 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, uint32_t *__restrict__ hi
         t.sh[b] = sh;
         t.fast[b] = path;
         if (path != PATH_CAND) atomicAdd(t.nhard, 1u);
+        if (path == PATH_DENSE) atomicAdd(t.nhard + 2, 1u);
     }
 }
 
 /* One workgroup: the list of spans that belong to fallback buckets.  (Kept as its own small
  * launch: doing it in the last workgroup of k_plan needs a device-scope fence in every
  * workgroup, which on this multi-die GPU writes back each L2 and costs more than a launch.) */
-__global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
+__device__ __forceinline__ void fb_plan_body(const Tables &t)
 {
     __shared__ uint32_t tmp[WG];
     const uint32_t tid = threadIdx.x;
@@ -476,6 +477,7 @@ __global__ __launch_bounds__(WG) void k_fb_plan(Tables t)
     }
     if (tid == 0) t.fspan0[t.B] = carry;
 }
+__global__ __launch_bounds__(WG) void k_fb_plan(Tables t) { fb_plan_body(t); }
 
 /* ------------------------------------------------------------------ candidate path */
 
@@ -624,14 +626,14 @@ __device__ __forceinline__ void crefine_agg_body(const Tables &t, const Cand &c,
  * fallback's, whichever path the bucket is on) to the digit holding the need-th entry and
  * append it to the prefix. */
 template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
-                                             const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
-                                             uint32_t *__restrict__ wT_out = nullptr, int only_fb = 0)
+__device__ __forceinline__ void pick_body(const Tables &t, const uint32_t *__restrict__ hist_c,
+                                          const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
+                                          uint32_t *__restrict__ wT_out, int only_fb, uint32_t b)
 {
     constexpr int NB = LEVEL == 2 ? NB2 : NB1;
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
     __shared__ uint32_t tmp[WG];
-    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x;
     if (only_fb && t.fast[b]) return;          /* decided by k_select */
     const uint32_t want = t.need[b];
     if (want == 0) {
@@ -657,6 +659,14 @@ __global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restric
          * bitmap */
         if (LEVEL == 2 && wT_out) wT_out[b] = t.fast[b] ? T : NONE;
     }
+}
+
+template <int LEVEL>
+__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
+                                             const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
+                                             uint32_t *__restrict__ wT_out = nullptr, int only_fb = 0)
+{
+    pick_body<LEVEL>(t, hist_c, hist_f, err, wT_out, only_fb, blockIdx.x);
 }
 
 /* Per segment: how many candidates exceed the threshold, how many equal it.  The counts of
@@ -712,11 +722,11 @@ __device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint
  * segments on the candidate path, its tiles on the fallback path).  Both counts of a unit
  * travel as one 64-bit word (neither total can reach 2^32: a bucket has fewer elements), and
  * every thread takes four consecutive units, so a round covers 1024 units with one scan. */
-__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
-                                             uint32_t *__restrict__ tG, uint32_t *__restrict__ tE, int only_fb = 0)
+__device__ __forceinline__ void scan_body(const Tables &t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
+                                          uint32_t *__restrict__ tG, uint32_t *__restrict__ tE, int only_fb, uint32_t b)
 {
     __shared__ uint64_t tmp[WG / 64];
-    const uint32_t b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t mode = t.fast[b];
     if (only_fb) {
         /* gradient stage: only the buckets on the dense passes, whose counts are per segment too */
@@ -755,6 +765,12 @@ __global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG
         }
         carry += total;
     }
+}
+
+__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
+                                             uint32_t *__restrict__ tG, uint32_t *__restrict__ tE, int only_fb = 0)
+{
+    scan_body(t, cG, cE, tG, tE, only_fb, blockIdx.x);
 }
 
 /* Per segment: copy the admitted candidates (key > T, or key == T and among the first e_b

@@ -600,7 +600,22 @@ __device__ __forceinline__ uint32_t gather_block(const Cand &c, uint32_t sblk, u
     const uint64_t below = (1ull << gl) - 1ull;
     const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << (GROUP % 64)) - 1ull);
     uint32_t got = 0;
-    for (uint32_t q = wave * SPR + sub; q < ((m + SLOTS - 1) / SLOTS) * SLOTS; q += SLOTS) {
+    /* the first batch of entries of a segment is fetched while the previous segment is worked on */
+    auto first_batch = [&](uint32_t q, float (&x)[CU], uint32_t (&li)[CU]) {
+        const uint32_t cnt = q < m ? mc[q] : 0u;
+        const uint64_t base = (uint64_t)(sblk + q) * c.cap;
+#pragma unroll
+        for (uint32_t u = 0; u < CU; ++u) {
+            const uint32_t i = u * GROUP + gl;
+            x[u] = i < cnt ? c.val[base + i] : 0.0f;
+            li[u] = i < cnt ? c.idx[base + i] : 0u;
+        }
+    };
+    const uint32_t qend = ((m + SLOTS - 1) / SLOTS) * SLOTS;
+    float xn[CU];
+    uint32_t lin[CU];
+    first_batch(wave * SPR + sub, xn, lin);
+    for (uint32_t q = wave * SPR + sub; q < qend; q += SLOTS) {
         const bool live = q < m;
         const uint32_t cnt = live ? mc[q] : 0u;
         uint32_t run_g = live ? mg[q] : 0u, run_e = live ? me[q] : 0u;
@@ -608,14 +623,19 @@ __device__ __forceinline__ uint32_t gather_block(const Cand &c, uint32_t sblk, u
 #pragma unroll
         for (int d = 32; d >= (int)GROUP; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
         const uint64_t base = (uint64_t)(sblk + q) * c.cap;
-        for (uint32_t i0 = 0; i0 < maxcnt; i0 += CU * GROUP) {
-            float x[CU];
-            uint32_t li[CU];
+        float x[CU];
+        uint32_t li[CU];
 #pragma unroll
-            for (uint32_t u = 0; u < CU; ++u) {
-                const uint32_t i = i0 + u * GROUP + gl;
-                x[u] = i < cnt ? c.val[base + i] : 0.0f;
-                li[u] = i < cnt ? c.idx[base + i] : 0u;
+        for (uint32_t u = 0; u < CU; ++u) { x[u] = xn[u]; li[u] = lin[u]; }
+        if (q + SLOTS < qend) first_batch(q + SLOTS, xn, lin);
+        for (uint32_t i0 = 0; i0 < maxcnt; i0 += CU * GROUP) {
+            if (i0 != 0) {
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t i = i0 + u * GROUP + gl;
+                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
+                    li[u] = i < cnt ? c.idx[base + i] : 0u;
+                }
             }
 #pragma unroll
             for (uint32_t u = 0; u < CU; ++u) {
@@ -679,12 +699,27 @@ __device__ __forceinline__ void gather_survivors(const Cand &c, uint32_t sA, uin
  * absmax, scale, codes, packing, indices, and the coding error left in the residual.  Every
  * floating-point step is a single correctly rounded binary32 operation.  A chunk longer than
  * ENC_BLK is gathered block by block, once for its absmax and once more for the codes. */
+template <bool DIRECT>
+__device__ __forceinline__ void write_dense_body(float *__restrict__ r, const Tables &t, const Cand &c,
+                                                 uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
+                                                 uint32_t which, uint32_t bid, uint32_t nblk);
+
 template <int BITS>
 __global__ __launch_bounds__(WG) void k_encode(Tables t, Cand c, const uint32_t *__restrict__ chunk_b,
                                                const uint32_t *__restrict__ chunk_seg, float *__restrict__ r,
                                                uint32_t *__restrict__ idx_out, void *__restrict__ val,
-                                               float *__restrict__ scales, uint32_t *__restrict__ err)
+                                               float *__restrict__ scales, uint32_t *__restrict__ err,
+                                               uint32_t n_chunks, float *__restrict__ vdst)
 {
+    if (blockIdx.x >= n_chunks) {
+        /* the last workgroups of the launch: ordered write for the buckets whose survivors come
+         * from the dense accumulator and whose threshold k_select_finish has left (band, zero
+         * threshold); usually there are none and they leave at once */
+        if (t.nhard[0] == 0u) return;
+        write_dense_body<BITS == 32>(r, t, c, idx_out, vdst, (1u << PATH_BAND) | (1u << PATH_ZERO),
+                                     blockIdx.x - n_chunks, gridDim.x - n_chunks);
+        return;
+    }
     __shared__ float sv[ENC_BLK];
     __shared__ uint32_t si[ENC_BLK];
     __shared__ uint32_t mc[WG], mg[WG], me[WG];
@@ -789,22 +824,21 @@ __global__ __launch_bounds__(WG) void k_encode(Tables t, Cand c, const uint32_t 
     }
 }
 
-/* ------------------------------------------------------------------ k_write_dense */
+/* ------------------------------------------------------------------ k_hard */
 
-/* Buckets whose survivors are taken from the dense accumulator (PATH_BAND, PATH_ZERO, and
- * PATH_DENSE once its own passes have left T, e and the per-segment prefixes): one wavefront
- * per staging segment walks the elements the segment covers, in index order, and writes the
+/* Ordered write for the buckets whose survivors are taken from the dense accumulator (PATH_BAND,
+ * PATH_ZERO, and PATH_DENSE once its own passes have left T, e and the per-segment prefixes):
+ * one wavefront per staging segment walks the elements the segment covers, in index order, and writes the
  * survivors' indices and values to their final slots.  Ranks inside a row of 64 lanes x 4
  * elements come from ballots; nothing crosses wavefronts.  which: bit p set = serve PATH p. */
 template <bool DIRECT>   /* DIRECT (32-bit values): v_out is the payload itself and the survivors' residual is zero */
-__global__ __launch_bounds__(WG) void k_write_dense(float *__restrict__ r, Tables t, Cand c,
-                                                    uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
-                                                    uint32_t which)
+__device__ __forceinline__ void write_dense_body(float *__restrict__ r, const Tables &t, const Cand &c,
+                                                 uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
+                                                 uint32_t which, uint32_t bid, uint32_t nblk)
 {
-    if (t.nhard[0] == 0u) return;                    /* every bucket was decided from its candidates */
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t n_seg = t.n_spans << t.segSh;
-    for (uint32_t ss = blockIdx.x * (WG / 64) + wave; ss < n_seg; ss += gridDim.x * (WG / 64)) {
+    for (uint32_t ss = bid * (WG / 64) + wave; ss < n_seg; ss += nblk * (WG / 64)) {
     const uint32_t span = ss >> t.segSh, wslot = ss & ((1u << t.segSh) - 1u);
     const uint32_t b = t.span_b[span];
     const uint32_t path = t.fast[b];
@@ -864,13 +898,13 @@ __global__ __launch_bounds__(WG) void k_write_dense(float *__restrict__ r, Table
 }
 
 /* PATH_DENSE buckets, after their own passes have found T and e: elements above and equal to T
- * per staging segment (one wavefront per segment), the counts k_scan turns into prefixes. */
-__global__ __launch_bounds__(WG) void k_segcount_dense(const float *__restrict__ r, Tables t, Cand c)
+ * per staging segment (one wavefront per segment), the counts the scan turns into prefixes. */
+__device__ __forceinline__ void segcount_dense_body(const float *__restrict__ r, const Tables &t, const Cand &c,
+                                                    uint32_t bid, uint32_t nblk)
 {
-    if (t.nhard[0] == 0u) return;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t n_seg = t.n_spans << t.segSh;
-    for (uint32_t ss = blockIdx.x * (WG / 64) + wave; ss < n_seg; ss += gridDim.x * (WG / 64)) {
+    for (uint32_t ss = bid * (WG / 64) + wave; ss < n_seg; ss += nblk * (WG / 64)) {
     const uint32_t span = ss >> t.segSh, wslot = ss & ((1u << t.segSh) - 1u);
     const uint32_t b = t.span_b[span];
     if (t.fast[b] != PATH_DENSE || t.k[b] == 0u) continue;
@@ -901,6 +935,74 @@ __global__ __launch_bounds__(WG) void k_segcount_dense(const float *__restrict__
     for (int d = 32; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
     if (lane == 0) { c.G[ss] = ng; c.E[ss] = ne; }
     }
+}
+
+/* The buckets whose staged elements could not decide them (PATH_DENSE: an unlucky sample, a
+ * staging segment that overflowed, a huge group of equal keys), in ONE launch of a fixed, small
+ * grid whose workgroups meet at barriers between the steps: list of their spans, level-1
+ * histogram over the dense accumulator, digit, level-2 histogram, digit, counts per segment,
+ * prefixes, ordered write.  In the usual case there is no such bucket: each workgroup reads one
+ * word and leaves, so the whole chain costs a single empty launch per call.
+ * A barrier is an arrival counter in memory: every wavefront waits for its own stores, one thread
+ * per workgroup then makes them visible device wide, counts the workgroup in and waits until all
+ * have arrived, and drops what the caches hold afterwards.  The grid is small enough to be
+ * resident at once; the wait is bounded by a clock all the same, and running out raises the
+ * consistency flag. */
+constexpr unsigned long long HARD_SPIN_TICKS = 500000000ull;      /* 5 s of the 100 MHz wall clock */
+
+__device__ __forceinline__ void grid_barrier(uint32_t *bar, uint32_t target, uint32_t *__restrict__ err)
+{
+    __builtin_amdgcn_s_waitcnt(0);                   /* this wavefront's stores have reached the L2 */
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();                             /* write the L2 back: visible to the other dies */
+        __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long t0 = wall_clock64();
+        while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(32);
+            if (wall_clock64() - t0 > HARD_SPIN_TICKS) { err[0] = 1u; break; }
+        }
+        __threadfence();                             /* and nothing stale is read afterwards */
+    }
+    __syncthreads();
+}
+
+template <bool DIRECT>
+__global__ __launch_bounds__(WG) void k_hard(float *__restrict__ r, Tables t, Cand c, uint32_t *__restrict__ f1,
+                                             uint32_t *__restrict__ f2, uint32_t *__restrict__ idx,
+                                             float *__restrict__ vdst, uint32_t *__restrict__ err)
+{
+    __shared__ uint32_t h[NB1];
+    if (t.nhard[2] == 0u) return;                    /* no bucket needs the dense passes */
+    uint32_t *bar = t.nhard + 1;
+    const uint32_t bid = blockIdx.x, nblk = gridDim.x;
+    uint32_t arrivals = 0;
+    if (bid == 0) fb_plan_body(t);
+    grid_barrier(bar, arrivals += nblk, err);
+    fb_refine_body<1>(r, t, f1, h, bid, nblk);
+    grid_barrier(bar, arrivals += nblk, err);
+    for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); pick_body<1>(t, f1, f1, err, nullptr, 1, b); }
+    grid_barrier(bar, arrivals += nblk, err);
+    fb_refine_body<2>(r, t, f2, h, bid, nblk);
+    grid_barrier(bar, arrivals += nblk, err);
+    for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); pick_body<2>(t, f2, f2, err, nullptr, 1, b); }
+    grid_barrier(bar, arrivals += nblk, err);
+    segcount_dense_body(r, t, c, bid, nblk);
+    grid_barrier(bar, arrivals += nblk, err);
+    for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); scan_body(t, c.G, c.E, nullptr, nullptr, 1, b); }
+    grid_barrier(bar, arrivals += nblk, err);
+    write_dense_body<DIRECT>(r, t, c, idx, vdst, 1u << PATH_DENSE, bid, nblk);
+}
+
+/* Value coding of the buckets whose survivors the ordered writes above left in idx / vdst
+ * (everything but PATH_CAND); one workgroup per chunk, leaving at once when there is none. */
+template <int BITS>
+__global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const uint32_t *__restrict__ idx, Tables t,
+                                              float *__restrict__ r, void *__restrict__ val,
+                                              float *__restrict__ scales, const uint32_t *__restrict__ chunk_b)
+{
+    if (t.nhard[0] == 0u) return;
+    quant_body<BITS>(v, idx, t, r, val, scales, chunk_b, blockIdx.x);
 }
 
 }  // namespace
