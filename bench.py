@@ -44,6 +44,7 @@ DEFAULTS = {          # workload -> (ratio, bits, distinct gradients kept in HBM
     "bert": (0.01, 8, 2),
     "resnet50": (0.05, 8, 4),
     "cfg1": (0.01, 8, 1),
+    "llama419m": (0.5, 8, 2),        # the first 16 Llama buckets: the high-ratio measurements
 }
 STREAMING = ("ef_emit", "decomp", "whist")      # the kernels that move whole gradients
 
@@ -71,6 +72,8 @@ def make_grads(workload, count, dev):
         t0 = time.time()
         if workload == "llama7b":
             g, off = W.llama7b_grad(s, dev)
+        elif workload == "llama419m":
+            g, off = W.llama_part_grad(s, dev)
         elif workload == "bert":
             g, off = W.bert_grad(s, dev)
         elif workload == "resnet50":
@@ -92,7 +95,7 @@ def cpu_baseline(workload, grads, off, ratio, bits, chunk):
     host_cpus = os.cpu_count() or 1
     cores = min(16, host_cpus)
     sizes = (off[1:] - off[:-1]).astype(np.int64)
-    if workload == "llama7b":
+    if workload in ("llama7b", "llama419m"):
         pick = list(range(min(4 * cores, len(sizes))))
         steps = 1
         what = f"first {len(pick)} of {len(sizes)} buckets (25 Mi elements each), 1 step"
@@ -116,7 +119,7 @@ def cpu_baseline(workload, grads, off, ratio, bits, chunk):
            "host_cpu_count": host_cpus, "thread_cap": 16,
            "kind": "oracle", "seconds": round(dt, 2),
            "sample": f"{what}; {gs[0].size} elements per step, compress+decompress, one bucket per thread"}
-    if workload != "llama7b":
+    if workload not in ("llama7b", "llama419m"):
         # the same on one thread (the three small configurations only), fewer steps
         steps1 = {"bert": 1, "resnet50": 4, "cfg1": 20}[workload]
         r = np.zeros_like(gs[0])

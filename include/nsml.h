@@ -275,6 +275,15 @@ int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
  * (fallback).  Both give identical results.  Synchronises the device.  NSML_EINTERNAL if the
  * call tripped a device-side consistency check (its outputs are then not valid). */
 int nsml_path_stats(nsml_ctx *ctx, uint32_t *fast_buckets, uint32_t *fallback_buckets);
+/* Diagnostics: the selection state of bucket b after the last nsml_compress of the context, eight
+ * words to out8 (host): how it was decided (0 dense passes, 1 candidates, 2 band, 3 zero
+ * threshold), why the dense passes were taken (bits: 1 the sample gave no usable guess, 2 a
+ * staging segment overflowed, 4 fewer staged elements than k, 8 no room for the undecided keys,
+ * 16 the threshold lies outside the staged band, 32 more non-zero elements than k in zero mode),
+ * the staged key range [L, H) (0xFFFFFFFF: none / no upper bound), the threshold key, the number
+ * of admitted elements equal to it, the bit position the threshold was known to before the
+ * finish, and k_b.  Synchronises the device.  NSML_EINVAL for a bucket out of range. */
+int nsml_bucket_state(nsml_ctx *ctx, uint32_t b, uint32_t *out8);
 /* The same for the weight-pruning stage of the last nsml_compress_pruned (zeros if the last
  * compress call had no weights): how many non-empty buckets got their pruning threshold from
  * the band of weights staged in one pass, and how many needed the dense ordered passes (a

@@ -74,6 +74,8 @@ _lib.nsml_profile_enable.argtypes = [_vp, _i32]
 _lib.nsml_profile_read.argtypes = [_vp, _vp, _vp]
 _lib.nsml_path_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
 _lib.nsml_path_stats.restype = _i32
+_lib.nsml_bucket_state.argtypes = [_vp, _u32, C.POINTER(_u32)]
+_lib.nsml_bucket_state.restype = _i32
 _lib.nsml_prune_stats.argtypes = [_vp, C.POINTER(_u32), C.POINTER(_u32)]
 _lib.nsml_prune_stats.restype = _i32
 _lib.nsml_decompress_accumulate.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _u32, _dbl, _i32, _vp, _vp]
@@ -322,6 +324,13 @@ class Context:
         a, b = _u32(), _u32()
         _check(_lib.nsml_path_stats(self._h, C.byref(a), C.byref(b)), "nsml_path_stats", self._h)
         return a.value, b.value
+
+    def bucket_state(self, b: int):
+        """-> dict with the selection state of bucket b after the last compress call (synchronises)."""
+        out = (_u32 * 8)()
+        _check(_lib.nsml_bucket_state(self._h, b, out), "nsml_bucket_state", self._h)
+        names = ("path", "why", "L", "H", "T", "need", "sh", "k")
+        return dict(zip(names, (int(x) for x in out)))
 
     def prune_stats(self):
         """-> (band buckets, dense buckets) of the weight stage of the last compress_pruned (synchronises)."""

@@ -9,6 +9,96 @@ namespace {
 
 /* ------------------------------------------------------------------ value coding */
 
+/* The same coding for chunks of at most 256 survivors, one wavefront per chunk and QUANT_PER_WAVE
+ * chunks per wavefront, all of whose values and indices are fetched before any is used (with a
+ * workgroup per small chunk the step is bound by the latency of its chain of dependent loads,
+ * not by bandwidth).  A lane takes up to two pairs of consecutive survivors of each chunk. */
+constexpr uint32_t QUANT_PER_WAVE = 4;
+template <int BITS>
+__device__ __forceinline__ void quant_wave(const float *__restrict__ v, const uint32_t *__restrict__ idx,
+                                           const Tables &t, float *__restrict__ r, void *__restrict__ val,
+                                           float *__restrict__ scales, const uint32_t *__restrict__ chunk_b,
+                                           uint64_t c0, uint32_t todo)
+{
+    constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+    const uint32_t lane = threadIdx.x & 63;
+    uint32_t bq[QUANT_PER_WAVE], cnt[QUANT_PER_WAVE];
+    uint64_t j0[QUANT_PER_WAVE], jg[QUANT_PER_WAVE], cbq[QUANT_PER_WAVE];
+#pragma unroll
+    for (uint32_t q = 0; q < QUANT_PER_WAVE; ++q) bq[q] = ((todo >> q) & 1u) ? chunk_b[c0 + q] : NONE;   /* bit q: chunk c0 + q is to be coded */
+#pragma unroll
+    for (uint32_t q = 0; q < QUANT_PER_WAVE; ++q) {
+        cnt[q] = 0; j0[q] = jg[q] = cbq[q] = 0;
+        if (bq[q] != NONE) {
+            cbq[q] = c0 + q - t.C[bq[q]];
+            j0[q] = cbq[q] * t.chunk;
+            cnt[q] = (uint32_t)min((uint64_t)t.chunk, (uint64_t)t.k[bq[q]] - j0[q]);
+            jg[q] = t.P[bq[q]] + j0[q];
+        }
+    }
+    float x[QUANT_PER_WAVE][2][2];
+    uint32_t li[QUANT_PER_WAVE][2][2];
+#pragma unroll
+    for (uint32_t q = 0; q < QUANT_PER_WAVE; ++q)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const uint32_t i = 2 * (lane + u * 64) + hh;
+                x[q][u][hh] = i < cnt[q] ? v[jg[q] + i] : 0.0f;
+                li[q][u][hh] = i < cnt[q] ? idx[jg[q] + i] : 0u;
+            }
+#pragma unroll
+    for (uint32_t q = 0; q < QUANT_PER_WAVE; ++q) {
+        if (cnt[q] == 0) continue;                             /* same for the whole wavefront */
+        const uint32_t b = bq[q];
+        const uint64_t lo = t.off[b];
+        uint8_t *vb = reinterpret_cast<uint8_t *>(val) + t.V[b];
+        float scale = 0.0f;
+        if (BITS <= 8) {
+            float m = fmaxf(fmaxf(fabsf(x[q][0][0]), fabsf(x[q][0][1])), fmaxf(fabsf(x[q][1][0]), fabsf(x[q][1][1])));
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+            scale = m == 0.0f ? 0.0f : __fdiv_rn(m, QMAX);
+            if (lane == 0) scales[t.S[b] + cbq[q]] = scale;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t i0 = 2 * (lane + u * 64);
+            if (i0 >= cnt[q]) continue;
+            const int have = (i0 + 1 < cnt[q]) ? 2 : 1;
+            float res[2] = {0.0f, 0.0f};
+            int qq[2] = {0, 0};
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                if (hh >= have) continue;
+                const float xv = x[q][u][hh];
+                float deq;
+                if (BITS == 32) {
+                    deq = xv;
+                } else if (BITS == 16) {
+                    const __half hv = __float2half_rn(xv);
+                    reinterpret_cast<__half *>(vb)[j0[q] + i0 + hh] = hv;
+                    deq = __half2float(hv);
+                } else {
+                    if (scale != 0.0f) {
+                        float tq = rintf(__fdiv_rn(xv, scale));
+                        tq = fminf(fmaxf(tq, -QMAX), QMAX);
+                        qq[hh] = (int)tq;
+                    }
+                    deq = __fmul_rn((float)qq[hh], scale);
+                    if (BITS == 8) reinterpret_cast<int8_t *>(vb)[j0[q] + i0 + hh] = (int8_t)qq[hh];
+                }
+                res[hh] = __fsub_rn(xv, deq);
+            }
+            if (BITS == 4) vb[(j0[q] + i0) >> 1] = (uint8_t)((qq[0] & 0xF) | ((qq[1] & 0xF) << 4));
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                if (hh < have) r[lo + li[q][u][hh]] = res[hh];
+        }
+    }
+}
+
 /* A workgroup's work on one chunk of `chunk` consecutive survivors of a bucket whose survivors
  * were written by k_hard's ordered pass (not PATH_CAND): absmax, scale,
  * codes, packing, and the coding error left in the residual.  Every floating-point step is a
@@ -116,7 +206,7 @@ __device__ __forceinline__ void quant_body(const float *__restrict__ v, const ui
 
 template <int BITS>
 __device__ __forceinline__ float decode(const uint8_t *__restrict__ vb, const float *__restrict__ sc,
-                                        uint64_t j, uint32_t chunk)
+                                        uint64_t j, uint32_t chunk, uint32_t chunkSh)
 {
     if (BITS == 32) return reinterpret_cast<const float *>(vb)[j];
     if (BITS == 16) return __half2float(reinterpret_cast<const __half *>(vb)[j]);
@@ -127,7 +217,8 @@ __device__ __forceinline__ float decode(const uint8_t *__restrict__ vb, const fl
         const int nib = (j & 1) ? (int)(byte >> 4) : (int)(byte & 0xFu);
         q = nib >= 8 ? nib - 16 : nib;
     }
-    return __fmul_rn((float)q, sc[j / chunk]);
+    /* the usual chunk lengths are powers of two: a shift instead of a 64-bit division */
+    return __fmul_rn((float)q, sc[chunkSh < 64u ? (j >> chunkSh) : j / chunk]);
 }
 
 /* Where each tile's survivors start in its bucket's ascending index list: ts[tile0[b] + b + i]
@@ -199,6 +290,30 @@ __global__ __launch_bounds__(WG) void k_tilestart(const uint32_t *__restrict__ i
     }
 }
 
+/* The same table by binary search, one thread per tile: cheaper than walking the whole index
+ * list once a tile holds many survivors (high ratios).  An index list that is not ascending (an
+ * invalid payload) gives entries that are wrong but still within [0, k_b]. */
+__global__ __launch_bounds__(WG) void k_tilestart_search(const uint32_t *__restrict__ idx, Tables t, uint32_t n_tiles,
+                                                         uint32_t *__restrict__ ts)
+{
+    const uint32_t g = blockIdx.x * WG + threadIdx.x;
+    if (g >= n_tiles) return;
+    const uint32_t b = find_bucket<uint32_t>(t.tile0, t.B, g);
+    const uint32_t i = g - t.tile0[b], tiles_b = t.tile0[b + 1] - t.tile0[b];
+    const uint32_t kb = t.k[b];
+    const uint32_t *ib = idx + t.P[b];
+    const uint64_t head = t.off[b] & 3ull;
+    const uint64_t edge = (uint64_t)i * TILE;           /* survivors with index + head below this come first */
+    uint32_t lo = 0, hi = kb;                           /* first j in [0, kb] with ib[j] + head >= edge */
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if ((uint64_t)ib[mid] + head < edge) lo = mid + 1; else hi = mid;
+    }
+    uint32_t *tsb = ts + t.tile0[b] + b;
+    tsb[i] = lo;
+    if (i + 1 == tiles_b) tsb[tiles_b] = kb;
+}
+
 /* Dense output for a span of tiles, the variant for gradients of up to a few hundred million
  * elements (256 threads): each tile is assembled in LDS (zeros, then the decoded
  * survivors that fall inside it, found through the tile-start table) and written out once with
@@ -230,7 +345,7 @@ __global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ 
         if (ti < s.ntiles) {
             const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
             const uint64_t j = (uint64_t)j0 + tid;
-            if (j < j1) { p_li = ib[j]; p_x = decode<BITS>(vb, sb, j, t.chunk); }
+            if (j < j1) { p_li = ib[j]; p_x = decode<BITS>(vb, sb, j, t.chunk, t.chunkSh); }
         }
     };
     fetch(0);
@@ -245,12 +360,23 @@ __global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ 
             const uint64_t slot = (uint64_t)p_li + shift;
             if (slot < TILE) tile[slot] = p_x;
         }
-        /* more than 256 survivors in the tile (ratio above 6 %) */
+        /* more than 256 survivors in the tile (ratio above 6 %): four per thread in flight */
         const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
-        for (uint64_t j = (uint64_t)j0 + WG + tid; j < j1; j += WG) {
-            const uint32_t li = ib[j];
-            const uint64_t slot = (uint64_t)li + shift;
-            if (li < nb && slot < TILE) tile[slot] = decode<BITS>(vb, sb, j, t.chunk);
+        for (uint64_t jb = (uint64_t)j0 + WG; jb < j1; jb += 4 * WG) {
+            uint32_t li4[4];
+            float x4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t j = jb + (uint64_t)u * WG + tid;
+                li4[u] = NONE;
+                x4[u] = 0.0f;
+                if (j < j1) { li4[u] = ib[j]; x4[u] = decode<BITS>(vb, sb, j, t.chunk, t.chunkSh); }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t slot = (uint64_t)li4[u] + shift;
+                if (li4[u] < nb && slot < TILE) tile[slot] = x4[u];
+            }
         }
         fetch(ti + 1);
         __syncthreads();
@@ -304,7 +430,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_decomp(const uint32_t *_
             const uint64_t j = (uint64_t)j0 + lane + 64u * u;
             p_li[u] = NONE;
             p_x[u] = 0.0f;
-            if (j < j1) { p_li[u] = ib[j]; p_x[u] = decode<BITS>(vb, sb, j, t.chunk); }
+            if (j < j1) { p_li[u] = ib[j]; p_x[u] = decode<BITS>(vb, sb, j, t.chunk, t.chunkSh); }
         }
         if (tb >= s.lo && tb + TILE <= s.hi) {
 #pragma unroll
@@ -338,7 +464,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_decomp(const uint32_t *_
         for (uint64_t j = (uint64_t)j0 + 64u * U + lane; j < j1; j += 64) {
             const uint32_t li = ib[j];
             const uint64_t slot = (uint64_t)li + shift;
-            if (li < nb && slot < TILE) dense[s.lo + li] = decode<BITS>(vb, sb, j, t.chunk);
+            if (li < nb && slot < TILE) dense[s.lo + li] = decode<BITS>(vb, sb, j, t.chunk, t.chunkSh);
         }
     }
 }
@@ -367,7 +493,7 @@ __global__ __launch_bounds__(WG) void k_decomp_acc(const uint32_t *__restrict__ 
         if (li >= nb) continue;                       /* invalid payload: never leave the bucket */
         const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[b];
         const float *sb = BITS <= 8 ? scales + t.S[b] : nullptr;
-        const float x = decode<BITS>(vb, sb, jj, t.chunk);
+        const float x = decode<BITS>(vb, sb, jj, t.chunk, t.chunkSh);
         dense[lo + li] = __fadd_rn(dense[lo + li], x);
     }
 }

@@ -23,6 +23,9 @@ constexpr uint32_t RUNS_PER_WG = 128;          /* sample runs (32 elements each)
 constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
 constexpr uint32_t AGG_GRID = 1024;            /* workgroups of the candidate refine that aggregates in LDS */
 
+/* Diagnostic: why the plan sent a bucket to the dense passes (bits; 0 when it did not). */
+enum Why : uint32_t { WHY_NO_GUESS = 1, WHY_OVERFLOW = 2, WHY_TOO_FEW = 4, WHY_NO_ROOM = 8, WHY_OUTSIDE_BAND = 16, WHY_NONZEROS = 32 };
+
 /* How a bucket's survivors are found once the streaming pass is done. */
 enum Path : uint32_t {
     PATH_DENSE = 0,   /* the staged elements cannot decide: every step over the dense accumulator */
@@ -68,6 +71,7 @@ struct Tables {
     uint32_t *subLo;         /* B   first of the SUB_DIGITS level-0 digits whose next 6 key bits the streaming pass
                               *     also counts (NONE: none) */
     uint32_t *sh;            /* B   T holds the key bits from this position up (19: the level-0 digit only; 13: six more) */
+    uint32_t *why;           /* B   diagnostic: why the plan did not take the staged elements (WHY_* bits, 0 if it did) */
     uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
     uint32_t *nhard;         /* 1   buckets of this call that are not on PATH_CAND (their kernels leave at once when 0) */
@@ -82,6 +86,7 @@ struct Tables {
     uint32_t spanT;          /* tiles per span */
     uint32_t segSh;          /* log2 of the staging segments per span (= wavefronts of the streaming pass) */
     uint32_t chunk;
+    uint32_t chunkSh;        /* log2(chunk) when chunk is a power of two, else NONE */
 };
 
 /* Candidate staging: segment ss = (span << segSh) + wavefront owns entries [ss * cap, ss * cap + cnt[ss]) */

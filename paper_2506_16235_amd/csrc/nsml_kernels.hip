@@ -78,7 +78,7 @@ struct nsml_ctx {
     uint4 *d_selw;         /* per workgroup of k_select_count: bucket, first and last segment */
     uint32_t *d_chunk_b;   /* per chunk of the payload: its bucket (fixed by layout, ratio, bits) */
     uint32_t *d_chunk_seg; /* per chunk: the staging segment that holds its first survivor */
-    uint32_t *d_H, *d_subLo, *d_sh;
+    uint32_t *d_H, *d_subLo, *d_sh, *d_why;
     uint32_t *d_lcnt, *d_lkey;   /* k_select_count: lists of undecided keys per workgroup */
     uint64_t max_chunks; uint32_t max_sel;
     uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
@@ -175,16 +175,24 @@ Hists hists_of(const nsml_ctx *c, uint32_t B)
     return h;
 }
 
+static uint32_t chunk_shift(uint32_t chunk)
+{
+    if (chunk == 0 || (chunk & (chunk - 1)) != 0) return NONE;
+    uint32_t sh = 0;
+    while ((1u << sh) != chunk) ++sh;
+    return sh;
+}
+
 Tables tables_of(const nsml_ctx *c)
 {
     Tables t;
     t.off = c->d_off; t.tile0 = c->d_tile0; t.span0 = c->d_span0; t.samp0 = c->d_samp0;
     t.span_b = c->d_span_b;
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
-    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.H = c->d_H; t.fast = c->d_fast; t.subLo = c->d_subLo; t.sh = c->d_sh;
+    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.H = c->d_H; t.fast = c->d_fast; t.subLo = c->d_subLo; t.sh = c->d_sh; t.why = c->d_why;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0; t.nhard = hists_of(c, c->B).nhard;
     t.kw = c->d_kw; t.w = nullptr; t.wT = nullptr; t.wcut = nullptr; t.pmask = nullptr;
-    t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk;
+    t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk; t.chunkSh = chunk_shift(c->chunk);
     return t;
 }
 
@@ -405,7 +413,7 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
-    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = nullptr;
+    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = nullptr;
     c->d_lcnt = c->d_lkey = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
@@ -447,7 +455,7 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_tile0, B1)); A(dev_alloc(c, &c->d_span0, B1)); A(dev_alloc(c, &c->d_samp0, B1));
     A(dev_alloc(c, &c->d_k, B1)); A(dev_alloc(c, &c->d_T, B1)); A(dev_alloc(c, &c->d_need, B1));
     A(dev_alloc(c, &c->d_L, B1)); A(dev_alloc(c, &c->d_fast, B1)); A(dev_alloc(c, &c->d_fspan0, B1));
-    A(dev_alloc(c, &c->d_sel0, B1)); A(dev_alloc(c, &c->d_H, B1)); A(dev_alloc(c, &c->d_subLo, B1)); A(dev_alloc(c, &c->d_sh, B1));
+    A(dev_alloc(c, &c->d_sel0, B1)); A(dev_alloc(c, &c->d_H, B1)); A(dev_alloc(c, &c->d_subLo, B1)); A(dev_alloc(c, &c->d_sh, B1)); A(dev_alloc(c, &c->d_why, B1));
     A(dev_alloc(c, &c->d_span_b, mt));
     A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
     A(dev_alloc(c, &c->d_tG, mt)); A(dev_alloc(c, &c->d_tE, mt));
@@ -509,7 +517,7 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
                     c->d_Tw, c->d_needw, c->d_wT, c->d_wfast, c->d_wcut,
-                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh};
+                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->h_flags) (void)hipHostFree(c->h_flags);
@@ -617,7 +625,6 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     LAUNCH(c, KID_PLAN, st, k_plan, B, t, h.h0, h.h0b, cd0, c->force_dense ? 0 : 1,
            (const double *)c->d_span_sq, c->d_l2sq);
     const uint32_t qgrid = (uint32_t)c->NC;
-    const uint32_t seg_grid = (n_ss + WG / 64 - 1) / (WG / 64);       /* one wavefront per staging segment */
     if (!c->force_dense) {
         /* buckets decided from their staged elements: undecided keys set apart, threshold and
          * survivor order per bucket, then the payload of the candidate-path buckets */
@@ -627,30 +634,41 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
                 (const uint32_t *)c->d_lcnt, (const uint32_t *)c->d_lkey, c->d_chunk_seg, c->d_flags,
                 c->force_rescan);
         {
-            /* the launch also carries the ordered write of the band / zero-threshold buckets */
             const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
-            const uint32_t wd = seg_grid < (uint32_t)(2 * c->n_cu) ? seg_grid : (uint32_t)(2 * c->n_cu);
+            const uint64_t nc64e = c->NC;
+            const uint32_t cpw = c->NC > (1ull << 18) ? 16u : 1u;     /* very many chunks: fewer, longer-lived workgroups */
+            const uint32_t egrid2 = (uint32_t)((c->NC + cpw - 1) / cpw);
             switch (bits) {
-            case 32: LAUNCH(c, KID_ENCODE, st, k_encode<32>, qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
-            case 16: LAUNCH(c, KID_ENCODE, st, k_encode<16>, qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
-            case 8:  LAUNCH(c, KID_ENCODE, st, k_encode<8>,  qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
-            default: LAUNCH(c, KID_ENCODE, st, k_encode<4>,  qgrid + wd, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, qgrid, vdst); break;
+            case 32: LAUNCH(c, KID_ENCODE, st, k_encode<32>, egrid2, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, nc64e, cpw); break;
+            case 16: LAUNCH(c, KID_ENCODE, st, k_encode<16>, egrid2, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, nc64e, cpw); break;
+            case 8:  LAUNCH(c, KID_ENCODE, st, k_encode<8>, egrid2, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, nc64e, cpw); break;
+            default: LAUNCH(c, KID_ENCODE, st, k_encode<4>, egrid2, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, nc64e, cpw); break;
             }
         }
     }
-    /* the buckets on the dense passes (usually none: the workgroups read one word and leave): a
-     * fixed grid, resident at once, that does all their steps with barriers between; then the
-     * value coding of every bucket whose survivors were written from the dense accumulator */
+    /* the buckets whose survivors come from the dense accumulator (usually none: the workgroups
+     * read one word and leave): a fixed grid, resident at once, that streams the band and
+     * zero-threshold buckets (ordered write and coding in one pass) and then does all the steps of
+     * the buckets on the dense passes with barriers between; then the value coding of what those
+     * left uncoded */
     {
-        const uint32_t hgrid = (uint32_t)c->n_cu;
-        const uint32_t *cb_ = c->d_chunk_b;
-        if (bits == 32) LAUNCH(c, KID_HARD, st, k_hard<true>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, c->d_flags);
-        else LAUNCH(c, KID_HARD, st, k_hard<false>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, c->d_flags);
+        const uint32_t hgrid = (uint32_t)(HARD_WG_PER_CU * c->n_cu), team = (uint32_t)c->n_cu;
+        const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
+        const int stream_coding = (bits != 32 && c->chunk <= DENC_MAX_CHUNK) ? 1 : 0;
+        switch (bits) {
+        case 32: LAUNCH(c, KID_HARD, st, k_hard<32>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
+        case 16: LAUNCH(c, KID_HARD, st, k_hard<16>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
+        case 8:  LAUNCH(c, KID_HARD, st, k_hard<8>,  hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
+        default: LAUNCH(c, KID_HARD, st, k_hard<4>,  hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
+        }
+        const uint32_t per_wg = (WG / 64) * QUANT_PER_WAVE;
+        const uint32_t ngrid = c->chunk <= QUANT_WAVE_CHUNK ? (qgrid + per_wg - 1) / per_wg : qgrid;
+        const uint64_t nc64 = c->NC;
         switch (bits) {
         case 32: break;        /* the ordered write left values and residual in their final state */
-        case 16: LAUNCH(c, KID_QUANT, st, k_quant<16>, qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, cb_); break;
-        case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, cb_); break;
-        default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  qgrid, (const float *)vdst, (const uint32_t *)idx, t, residual, val, scales, cb_); break;
+        case 16: LAUNCH(c, KID_QUANT, st, k_quant<16>, ngrid, (const float *)vdst, (const uint32_t *)idx, t, cd0, residual, val, scales, cb_, cs_, nc64, stream_coding); break;
+        case 8:  LAUNCH(c, KID_QUANT, st, k_quant<8>,  ngrid, (const float *)vdst, (const uint32_t *)idx, t, cd0, residual, val, scales, cb_, cs_, nc64, stream_coding); break;
+        default: LAUNCH(c, KID_QUANT, st, k_quant<4>,  ngrid, (const float *)vdst, (const uint32_t *)idx, t, cd0, residual, val, scales, cb_, cs_, nc64, stream_coding); break;
         }
     }
     c->have_l2 = true;
@@ -677,11 +695,14 @@ int nsml_compress_pruned(nsml_ctx *c, const float *grad, float *residual, const 
 
 /* The launches of one decompress: tile-start table, then the dense output.  c may be NULL
  * (the entry point without a context): then nothing is profiled and no error code is kept. */
-static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint64_t K, uint32_t n_spans,
+static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint64_t K, uint32_t n_spans, uint32_t n_tiles,
                              uint32_t *d_ts, int nt_dense, int variant, const uint32_t *idx, const void *val,
                              const float *scales, int bits, float *dense_out)
 {
-    if (K >= (4ull << 20)) {
+    const bool crowded = K >= 64ull * n_tiles;           /* many survivors per tile */
+    if (crowded) {
+        LAUNCH(c, KID_TILESTART, st, k_tilestart_search, (n_tiles + WG - 1) / WG, idx, t, n_tiles, d_ts);
+    } else if (K >= (4ull << 20)) {
         const uint64_t want = (K + (uint64_t)WG * 8 - 1) / ((uint64_t)WG * 8);
         LAUNCH(c, KID_TILESTART, st, k_tilestart<8>, (uint32_t)(want < 16384 ? want : 16384), idx, t, K, d_ts);
     } else {
@@ -689,8 +710,8 @@ static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint6
         LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, K, d_ts);
     }
     const uint32_t *ts = d_ts;
-    if (variant > 0 || (variant < 0 && t.spanT >= MAX_SPAN_TILES)) {
-        /* the largest gradients: one wavefront per tile, direct stores (plain unless asked otherwise) */
+    if (variant > 0 || (variant < 0 && t.spanT >= MAX_SPAN_TILES && !crowded)) {
+        /* the largest gradients at low ratios: one wavefront per tile, direct stores (plain unless asked otherwise) */
         const uint32_t dblock = 64u * t.spanT;
         if (nt_dense > 0) {
             switch (bits) {
@@ -742,7 +763,7 @@ int nsml_decompress(nsml_ctx *c, const uint32_t *idx, const void *val, const flo
     if (rc) return rc;
     rc = ensure_tables(c, ratio, bits, st);
     if (rc) return rc;
-    return launch_decompress(c, st, tables_of(c), c->K, c->n_spans, c->d_ts, c->nt_dense, c->decomp_variant, idx, val, scales,
+    return launch_decompress(c, st, tables_of(c), c->K, c->n_spans, c->n_tiles, c->d_ts, c->nt_dense, c->decomp_variant, idx, val, scales,
                              bits, dense_out);
 }
 
@@ -862,12 +883,12 @@ int nsml_decompress_static(const uint32_t *idx, const void *val, const float *sc
     memset(&t, 0, sizeof t);
     t.off = m.off; t.tile0 = m.tile0; t.span0 = m.span0; t.span_b = m.span_b;
     t.k = m.k; t.kw = m.kw; t.P = m.P; t.V = m.V; t.S = m.S; t.C = m.C;
-    t.B = B; t.n_spans = (uint32_t)ns; t.spanT = spanT; t.segSh = 2; t.chunk = chunk;
+    t.B = B; t.n_spans = (uint32_t)ns; t.spanT = spanT; t.segSh = 2; t.chunk = chunk; t.chunkSh = chunk_shift(chunk);
     LAUNCH(none, KID_SETUP, st, k_static_layout, 1, so, B, spanT, m.off, m.tile0, m.span0);
     LAUNCH(none, KID_SETUP, st, k_setup, 1, t, ratio, bits);
     LAUNCH(none, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)m.span0, B,
            (uint32_t)ns, m.span_b);
-    return launch_decompress(none, st, t, K, (uint32_t)ns, m.ts, -1, -1, idx, val, scales, bits, dense_out);
+    return launch_decompress(none, st, t, K, (uint32_t)ns, (uint32_t)nt, m.ts, -1, -1, idx, val, scales, bits, dense_out);
 }
 
 int nsml_decompress_accumulate(nsml_ctx *c, const uint32_t *idx, const void *val, const float *scales,
@@ -956,6 +977,17 @@ int nsml_path_stats(nsml_ctx *c, uint32_t *fast_buckets, uint32_t *fallback_buck
         if (f[b]) *fast_buckets += 1; else *fallback_buckets += 1;
     }
     return *(volatile uint32_t *)&c->h_flags[0] ? NSML_EINTERNAL : NSML_OK;
+}
+
+int nsml_bucket_state(nsml_ctx *c, uint32_t b, uint32_t *out8)
+{
+    if (!c || !out8 || b >= c->B) return NSML_EINVAL;
+    DeviceGuard guard(c->device);
+    NSML_HIP(c, hipDeviceSynchronize());
+    const uint32_t *src[8] = {c->d_fast, c->d_why, c->d_L, c->d_H, c->d_T, c->d_need, c->d_sh, c->d_k};
+    for (int i = 0; i < 8; ++i)
+        NSML_HIP(c, hipMemcpy(out8 + i, src[i] + b, sizeof(uint32_t), hipMemcpyDeviceToHost));
+    return NSML_OK;
 }
 
 int nsml_prune_stats(nsml_ctx *c, uint32_t *band_buckets, uint32_t *dense_buckets)

@@ -117,10 +117,13 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, uint32_t *__restrict__
         const uint32_t dig_up = res[3], dig_dn = res[6];
         if (dig_up == 0u) {
             L = 1u; H = 1u;
-        } else if (dig_dn != 0u) {
-            const double in_band = (double)(res[7] + res[8]) - (double)res[4];
+        } else {
+            /* a pessimistic rank among the zeros (digit 0) while the optimistic one is not: the band
+             * starts at key 1, zeros are only counted, and the plan decides between a zero
+             * threshold and one inside the band */
+            const double in_band = (double)res[7] + (dig_dn != 0u ? (double)res[8] : 0.0) - (double)res[4];
             const double est = in_band * pop / (double)m;
-            if (est <= 0.8 * cap_b) { L = dig_dn << SH0; H = (dig_up + 1u) << SH0; }
+            if (est <= 0.8 * cap_b) { L = dig_dn != 0u ? dig_dn << SH0 : 1u; H = (dig_up + 1u) << SH0; }
         }
     }
     t.L[b] = L;
@@ -433,21 +436,31 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, uint32_t *__restrict__ hi
             }
         }
         if (tid != 0) return;
-        if (have_cand && L != NONE && !ovf) {
+        uint32_t why = 0u;
+        if (!have_cand || L == NONE) why = WHY_NO_GUESS;
+        else if (ovf) why = WHY_OVERFLOW;
+        else {
             const uint64_t cap_b = (uint64_t)((t.span0[b + 1] - t.span0[b]) << t.segSh) * c.cap;
             if (fine) at = at18;
             const bool room = (uint64_t)at * 2u <= cap_b - (uint64_t)n_cand;     /* for the undecided keys in the tails */
             if (H == NONE) {
                 if (n_cand >= want && room) path = PATH_CAND;
+                else why = n_cand < want ? WHY_TOO_FEW : WHY_NO_ROOM;
             } else if (L == H) {
                 /* n_hi = non-zero keys among the selectable elements: if they are no more than k,
                  * all of them survive and zeros (lowest indices first) fill the rest */
                 if (n_hi <= want) { path = PATH_ZERO; T = 0u; need = want - n_hi; }
-            } else if ((digit << SH0) >= L && ((digit + 1u) << SH0) <= H && room) {
-                path = PATH_BAND;
-            }
+                else why = WHY_NONZEROS;
+            } else if (L == 1u && n_hi + n_cand <= want) {
+                /* the band starts at key 1 and everything non-zero is still not enough: zero threshold */
+                path = PATH_ZERO; T = 0u; need = want - (n_hi + n_cand);
+            } else if ((digit << SH0) >= L && ((digit + 1u) << SH0) <= H) {
+                if (room) path = PATH_BAND;
+                else why = WHY_NO_ROOM;
+            } else why = WHY_OUTSIDE_BAND;
             if (fine && (path == PATH_CAND || path == PATH_BAND)) { T = T18; need = need18; sh = SHS; }
         }
+        t.why[b] = why;
         t.T[b] = T;
         t.need[b] = need;
         t.sh[b] = sh;

@@ -101,6 +101,20 @@ __device__ __forceinline__ uint32_t wg_search_le(uint32_t lo, uint32_t hi, uint6
     return lo;
 }
 
+/* Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel moves: shifts by 1, 2,
+ * 4, 8 lanes inside each row of 16 (lanes shifted in from outside a row read 0), then lane 15 of
+ * rows 0 and 2 added to rows 1 and 3, then lane 31 added to rows 2 and 3. */
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);
+    return v;
+}
+
 /* ------------------------------------------------------------------ k_select_count */
 
 constexpr uint32_t SELC_WAVES = WG / 64;
@@ -569,9 +583,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_finish(Tables t, Cand c,
     FinShared sm;
     sm.pool = pool; sm.h2 = h2; sm.tmp = tmp; sm.res = res;
     if (path == PATH_ZERO) {
-        /* the streaming pass counted non-zero (G) and zero (E) keys per segment */
+        /* the streaming pass counted non-zero (G) and zero (E) keys per segment; when a band from
+         * key 1 up was staged as well, G holds the keys above the band and the staged ones add to it */
+        const bool mixed = t.L[b] != t.H[b];
         finish_prefixes(t, c, b, seg_lo, seg_hi, 0u, need0, kb, chunk_seg, tmp, err,
-                        [&](uint32_t, uint32_t s, uint32_t &, uint32_t &q) { if (s < seg_hi) q += c.E[s]; });
+                        [&](uint32_t, uint32_t s, uint32_t &g, uint32_t &q) {
+                            if (s < seg_hi) { q += c.E[s]; if (mixed) g += c.cnt[s]; }
+                        });
         return;
     }
     const uint32_t nun = u1 - u0;
@@ -699,27 +717,13 @@ __device__ __forceinline__ void gather_survivors(const Cand &c, uint32_t sA, uin
  * absmax, scale, codes, packing, indices, and the coding error left in the residual.  Every
  * floating-point step is a single correctly rounded binary32 operation.  A chunk longer than
  * ENC_BLK is gathered block by block, once for its absmax and once more for the codes. */
-template <bool DIRECT>
-__device__ __forceinline__ void write_dense_body(float *__restrict__ r, const Tables &t, const Cand &c,
-                                                 uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
-                                                 uint32_t which, uint32_t bid, uint32_t nblk);
-
 template <int BITS>
 __global__ __launch_bounds__(WG) void k_encode(Tables t, Cand c, const uint32_t *__restrict__ chunk_b,
                                                const uint32_t *__restrict__ chunk_seg, float *__restrict__ r,
                                                uint32_t *__restrict__ idx_out, void *__restrict__ val,
                                                float *__restrict__ scales, uint32_t *__restrict__ err,
-                                               uint32_t n_chunks, float *__restrict__ vdst)
+                                               uint64_t n_chunks, uint32_t cpw)
 {
-    if (blockIdx.x >= n_chunks) {
-        /* the last workgroups of the launch: ordered write for the buckets whose survivors come
-         * from the dense accumulator and whose threshold k_select_finish has left (band, zero
-         * threshold); usually there are none and they leave at once */
-        if (t.nhard[0] == 0u) return;
-        write_dense_body<BITS == 32>(r, t, c, idx_out, vdst, (1u << PATH_BAND) | (1u << PATH_ZERO),
-                                     blockIdx.x - n_chunks, gridDim.x - n_chunks);
-        return;
-    }
     __shared__ float sv[ENC_BLK];
     __shared__ uint32_t si[ENC_BLK];
     __shared__ uint32_t mc[WG], mg[WG], me[WG];
@@ -727,10 +731,17 @@ __global__ __launch_bounds__(WG) void k_encode(Tables t, Cand c, const uint32_t 
     __shared__ uint32_t sh, filled, mxc;
     constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
     const uint32_t tid = threadIdx.x;
-    const uint64_t cid = blockIdx.x;
+    /* a workgroup takes cpw consecutive chunks (one, unless the payload has very many) */
+    const uint64_t cend = min(n_chunks, ((uint64_t)blockIdx.x + 1) * cpw);
+    if (cpw > 1) {
+        /* all of them in one bucket that is not coded here: nothing to do */
+        const uint32_t bf = chunk_b[(uint64_t)blockIdx.x * cpw], bl = chunk_b[cend - 1];
+        if (bf == bl && t.fast[bf] != PATH_CAND) return;
+    }
+    for (uint64_t cid = (uint64_t)blockIdx.x * cpw; cid < cend; ++cid) {
     const uint32_t b = chunk_b[cid];
     const uint32_t sFirst = chunk_seg[cid];          /* meaningful for PATH_CAND buckets only */
-    if (t.fast[b] != PATH_CAND) return;
+    if (t.fast[b] != PATH_CAND) continue;
     const uint64_t cb = cid - t.C[b];
     const uint64_t j0c = cb * t.chunk;                         /* first survivor of the chunk, bucket-local */
     const uint32_t cnt_c = (uint32_t)min((uint64_t)t.chunk, (uint64_t)t.k[b] - j0c);
@@ -822,6 +833,7 @@ __global__ __launch_bounds__(WG) void k_encode(Tables t, Cand c, const uint32_t 
                 if (hh < have) r[lo + li[hh]] = res[hh];
         }
     }
+    }
 }
 
 /* ------------------------------------------------------------------ k_hard */
@@ -851,16 +863,30 @@ __device__ __forceinline__ void write_dense_body(float *__restrict__ r, const Ta
     const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t per = (t.spanT * 4u) >> t.segSh;
     const uint32_t wt0 = wslot * per, wt1 = min(s.ntiles * 4u, wt0 + per);
+    /* the next wave-tile (64 lanes x 4 rows x 4 elements) is fetched while this one is written */
+    float xn[4][4];
+    uint32_t mn[4];
+    auto fetch = [&](uint32_t wt) {
+        const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+            mn[u] = load_quad(r, gi, s.lo, s.hi, xn[u]);
+            if (t.w) mn[u] &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+        }
+    };
+    if (wt0 < wt1) fetch(wt0);
     for (uint32_t wt = wt0; wt < wt1; ++wt) {
         const uint64_t wb = s.base + (uint64_t)wt * WTILE;
         float x[4][4];
         uint32_t m[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
-            m[u] = load_quad(r, gi, s.lo, s.hi, x[u]);
-            if (t.w) m[u] &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+            m[u] = mn[u];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[u][j] = xn[u][j];
         }
+        if (wt + 1 < wt1) fetch(wt + 1);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
@@ -967,15 +993,290 @@ __device__ __forceinline__ void grid_barrier(uint32_t *bar, uint32_t target, uin
     __syncthreads();
 }
 
-template <bool DIRECT>
-__global__ __launch_bounds__(WG) void k_hard(float *__restrict__ r, Tables t, Cand c, uint32_t *__restrict__ f1,
-                                             uint32_t *__restrict__ f2, uint32_t *__restrict__ idx,
-                                             float *__restrict__ vdst, uint32_t *__restrict__ err)
+/* Ordered write and value coding in one pass, for the buckets whose survivors are taken from the
+ * dense accumulator and whose threshold is known (PATH_BAND, PATH_ZERO), with chunks of at most
+ * DENC_MAX_CHUNK survivors.  Survivors are dense here (ratios from an eighth up, or an
+ * embedding whose few non-zero rows all survive), so the work is laid out by elements: a
+ * workgroup streams a unit of DENC_SPANS consecutive spans, 4096 elements at a time (one
+ * wave-tile per wavefront); ranks come from ballots and a prefix over the four wavefronts; the
+ * survivors are put into LDS in rank order behind the ones still waiting for their chunk to
+ * fill up; every chunk that is complete is coded from LDS by one wavefront (absmax, scale,
+ * codes, indices, and the coding error scattered into the accumulator lines the workgroup has
+ * just read, which are still in the cache).  A chunk that reaches across the unit's ends (or a
+ * bucket's spans of another unit) is written uncoded to idx / v_out, and k_quant codes exactly
+ * those afterwards (same test, see chunk_coded_by_stream).  16-bit values need no chunk and are
+ * all coded here. */
+constexpr uint32_t DENC_SPANS = 4;
+constexpr uint32_t DENC_MAX_CHUNK = 256;
+constexpr uint32_t DENC_CAP = TILE + DENC_MAX_CHUNK;
+
+template <int BITS>
+__device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const Tables &t, const Cand &c,
+                                                  uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
+                                                  void *__restrict__ val, float *__restrict__ scales,
+                                                  float *sv, uint32_t *si, uint32_t *wtot, uint32_t *__restrict__ err,
+                                                  uint32_t bid, uint32_t nblk)
 {
-    __shared__ uint32_t h[NB1];
-    if (t.nhard[2] == 0u) return;                    /* no bucket needs the dense passes */
+    constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t chunk = t.chunk;
+    const uint32_t n_units = (t.n_spans + DENC_SPANS - 1) / DENC_SPANS;
+    for (uint32_t unit = bid; unit < n_units; unit += nblk) {
+        uint32_t cur_b = NONE;
+        /* state of the stream: one bucket's consecutive spans inside the unit */
+        uint32_t T = 0, e_b = 0, kb = 0, run_g = 0, run_e = 0, carry = 0, Rbase = 0;
+        uint64_t Pb = 0, lo = 0;
+        uint8_t *vb = nullptr;
+        uint64_t Sb = 0;
+        bool head = false;
+        /* what is left in LDS when a stream ends belongs to a chunk that goes on elsewhere */
+        auto flush = [&]() {
+            for (uint32_t i = tid; i < carry; i += WG) {
+                idx_out[Pb + Rbase + i] = si[i];
+                v_out[Pb + Rbase + i] = sv[i];
+            }
+            carry = 0;
+            __syncthreads();
+        };
+        const uint32_t sp1 = min(t.n_spans, (unit + 1) * DENC_SPANS);
+        for (uint32_t span = unit * DENC_SPANS; span < sp1; ++span) {
+            const uint32_t b = t.span_b[span];
+            const uint32_t path = t.fast[b];
+            if ((path != PATH_BAND && path != PATH_ZERO) || t.k[b] == 0u) {
+                if (cur_b != NONE) { flush(); cur_b = NONE; }
+                continue;
+            }
+            const SpanGeo s = span_geo_b(t, b, span - t.span0[b]);
+            if (b != cur_b) {
+                if (cur_b != NONE) flush();
+                cur_b = b;
+                T = t.T[b]; e_b = t.need[b]; kb = t.k[b]; Pb = t.P[b]; lo = s.lo;
+                vb = reinterpret_cast<uint8_t *>(val) + t.V[b];
+                Sb = t.S[b];
+                const uint32_t ss0 = span << t.segSh;
+                run_g = c.G[ss0]; run_e = c.E[ss0];
+                Rbase = run_g + min(e_b, run_e);
+                carry = 0;
+                head = BITS <= 8 && (Rbase % chunk) != 0u;
+            }
+            else if (tid == 0 && (run_g != c.G[span << t.segSh] || run_e != c.E[span << t.segSh]))
+                err[0] = 1u;                         /* the prefixes and the elements disagree */
+            const uint32_t wT = t.w ? t.wT[b] : 0u, wcut = t.w ? t.wcut[b] : 0u;
+            const uint32_t nwt = s.ntiles * 4u;
+            /* the next 4096 elements are fetched while the survivors of these are coded */
+            float xn[4][4];
+            uint32_t mn[4];
+            auto fetch = [&](uint32_t wt_base) {
+                const uint32_t wt = wt_base + wave;
+                const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                    mn[u] = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xn[u][j] = 0.0f;
+                    if (wt < nwt) {
+                        mn[u] = load_quad(r, gi, s.lo, s.hi, xn[u]);
+                        if (t.w) mn[u] &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+                    }
+                }
+            };
+            fetch(0);
+            for (uint32_t wt_base = 0; wt_base < nwt; wt_base += WG / 64) {
+                const uint32_t wt = wt_base + wave;
+                const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+                float x[4][4];
+                uint32_t fg[4], fe[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    fg[u] = fe[u] = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        x[u][j] = xn[u][j];
+                        const uint32_t key = keyof(x[u][j]);
+                        if ((mn[u] >> j) & 1u) { fg[u] |= (key > T ? 1u : 0u) << j; fe[u] |= (key == T ? 1u : 0u) << j; }
+                    }
+                }
+                /* ranks: a lane's elements of a row are consecutive, so the elements before one are
+                 * those of the lower lanes of its row, of the earlier rows and of the earlier
+                 * wavefronts.  Counts of elements above T (low half) and equal to T (high half)
+                 * travel in one word; 4096 elements cannot carry from one half into the other. */
+                uint32_t ex[4], wsum = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t cnt = (uint32_t)__popc(fg[u]) | ((uint32_t)__popc(fe[u]) << 16);
+                    const uint32_t incl = wave_incl_scan(cnt);
+                    ex[u] = wsum + incl - cnt;
+                    wsum += __builtin_amdgcn_readlane(incl, 63);
+                }
+                if (lane == 0) wtot[wave] = wsum;
+                __syncthreads();
+                uint32_t woff = 0, all = 0;
+#pragma unroll
+                for (uint32_t w = 0; w < WG / 64; ++w) {
+                    if (w < wave) woff += wtot[w];
+                    all += wtot[w];
+                }
+                const uint32_t all_g = all & 0xFFFFu, all_e = all >> 16;
+                const uint32_t Rnext = run_g + min(e_b, run_e);               /* rank of the next survivor = Rbase + carry */
+                const uint32_t nsurv = (run_g + all_g + min(e_b, run_e + all_e)) - Rnext;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                    const uint32_t before = woff + ex[u];
+                    uint32_t pg = run_g + (before & 0xFFFFu), pe = run_e + (before >> 16);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const bool isg = (fg[u] >> j) & 1u, ise = (fe[u] >> j) & 1u;
+                        if (isg || (ise && pe < e_b)) {
+                            const uint32_t slot = carry + (pg + min(e_b, pe) - Rnext);
+                            sv[slot] = x[u][j];
+                            si[slot] = (uint32_t)(gi + j - s.lo);
+                        }
+                        pg += isg ? 1u : 0u;
+                        pe += ise ? 1u : 0u;
+                    }
+                }
+                run_g += all_g;
+                run_e += all_e;
+                __syncthreads();
+                if (wt_base + WG / 64 < nwt) fetch(wt_base + WG / 64);
+                /* consume what is complete */
+                const uint32_t total = carry + nsurv;
+                uint32_t p = 0;
+                if (BITS == 16) {
+                    for (uint32_t i = tid; i < total; i += WG) {
+                        const float xv = sv[i];
+                        const uint32_t li = si[i];
+                        const __half hv = __float2half_rn(xv);
+                        reinterpret_cast<__half *>(vb)[Rbase + i] = hv;
+                        idx_out[Pb + Rbase + i] = li;
+                        r[lo + li] = __fsub_rn(xv, __half2float(hv));
+                    }
+                    p = total;
+                } else {
+                    if (head) {
+                        /* up to the next chunk boundary: part of a chunk that began before this stream */
+                        const uint32_t to_edge = chunk - (Rbase % chunk);
+                        const uint32_t nh = min(total, to_edge);
+                        for (uint32_t i = tid; i < nh; i += WG) {
+                            idx_out[Pb + Rbase + i] = si[i];
+                            v_out[Pb + Rbase + i] = sv[i];
+                        }
+                        p = nh;
+                        if (nh == to_edge) head = false;
+                    }
+                    if (!head) {
+                        const uint32_t avail = total - p;
+                        const uint32_t nfull = avail / chunk, rem = avail - nfull * chunk;
+                        const uint32_t ncode = nfull + ((rem != 0u && Rbase + total == kb) ? 1u : 0u);   /* the bucket's last chunk may be short */
+                        for (uint32_t q = wave; q < ncode; q += WG / 64) {
+                            const uint32_t base = p + q * chunk;
+                            const uint32_t cnt = min(chunk, total - base);
+                            const uint32_t rank0 = Rbase + base;
+                            float xv[2][2];
+                            uint32_t li[2][2];
+#pragma unroll
+                            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                                for (int hh = 0; hh < 2; ++hh) {
+                                    const uint32_t i = 2 * (lane + u * 64) + hh;
+                                    xv[u][hh] = i < cnt ? sv[base + i] : 0.0f;
+                                    li[u][hh] = i < cnt ? si[base + i] : 0u;
+                                }
+                            float mx = fmaxf(fmaxf(fabsf(xv[0][0]), fabsf(xv[0][1])), fmaxf(fabsf(xv[1][0]), fabsf(xv[1][1])));
+#pragma unroll
+                            for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+                            const float scale = mx == 0.0f ? 0.0f : __fdiv_rn(mx, QMAX);
+                            if (lane == 0) scales[Sb + rank0 / chunk] = scale;
+#pragma unroll
+                            for (int u = 0; u < 2; ++u) {
+                                const uint32_t i0 = 2 * (lane + u * 64);
+                                if (i0 >= cnt) continue;
+                                const int have = (i0 + 1 < cnt) ? 2 : 1;
+                                int qq[2] = {0, 0};
+                                float res[2] = {0.0f, 0.0f};
+#pragma unroll
+                                for (int hh = 0; hh < 2; ++hh) {
+                                    if (hh >= have) continue;
+                                    if (scale != 0.0f) {
+                                        float tq = rintf(__fdiv_rn(xv[u][hh], scale));
+                                        tq = fminf(fmaxf(tq, -QMAX), QMAX);
+                                        qq[hh] = (int)tq;
+                                    }
+                                    res[hh] = __fsub_rn(xv[u][hh], __fmul_rn((float)qq[hh], scale));
+                                    if (BITS == 8) reinterpret_cast<int8_t *>(vb)[rank0 + i0 + hh] = (int8_t)qq[hh];
+                                    idx_out[Pb + rank0 + i0 + hh] = li[u][hh];
+                                }
+                                if (BITS == 4) vb[(rank0 + i0) >> 1] = (uint8_t)((qq[0] & 0xF) | ((qq[1] & 0xF) << 4));
+#pragma unroll
+                                for (int hh = 0; hh < 2; ++hh)
+                                    if (hh < have) r[lo + li[u][hh]] = res[hh];
+                            }
+                        }
+                        p += min(avail, ncode * chunk);
+                    }
+                }
+                __syncthreads();
+                /* the rest waits at the front for the next elements */
+                const uint32_t left = total - p;
+                float keep_v = 0.0f;
+                uint32_t keep_i = 0;
+                if (tid < left) { keep_v = sv[p + tid]; keep_i = si[p + tid]; }
+                __syncthreads();
+                if (tid < left) { sv[tid] = keep_v; si[tid] = keep_i; }
+                Rbase += p;
+                carry = left;
+            }
+        }
+        if (cur_b != NONE) flush();
+        __syncthreads();
+    }
+}
+
+/* Whether chunk cb (bucket-local) of a PATH_BAND / PATH_ZERO bucket b was coded by
+ * dense_encode_body: its first survivor lies in segment s, and all of its survivors lie in the
+ * spans of b inside the unit of DENC_SPANS spans that holds s. */
+__device__ __forceinline__ bool chunk_coded_by_stream(const Tables &t, const Cand &c, uint32_t b, uint64_t cb, uint32_t s)
+{
+    const uint32_t kb = t.k[b], e_b = t.need[b];
+    const uint64_t end = min((cb + 1) * (uint64_t)t.chunk, (uint64_t)kb);
+    const uint32_t next_span = ((s >> t.segSh) / DENC_SPANS + 1u) * DENC_SPANS;
+    uint64_t r1 = kb;
+    if (next_span < t.span0[b + 1]) {
+        const uint32_t sn = next_span << t.segSh;
+        r1 = (uint64_t)c.G[sn] + min(e_b, c.E[sn]);
+    }
+    return end <= r1;
+}
+
+constexpr uint32_t HARD_WG_PER_CU = 4;      /* workgroups of k_hard per compute unit (its LDS allows no more) */
+constexpr uint32_t HARD_LDS = 2 * DENC_CAP + 2 * (WG / 64);    /* words; also holds the level-1 histogram */
+
+template <int BITS>
+__global__ __launch_bounds__(WG, HARD_WG_PER_CU) void k_hard(float *__restrict__ r, Tables t, Cand c, uint32_t *__restrict__ f1,
+                                             uint32_t *__restrict__ f2, uint32_t *__restrict__ idx,
+                                             float *__restrict__ vdst, void *__restrict__ val,
+                                             float *__restrict__ scales, uint32_t *__restrict__ err, int stream_coding, uint32_t team)
+{
+    static_assert(HARD_LDS >= NB1, "the pool must hold the level-1 histogram");
+    __shared__ uint32_t pool[HARD_LDS];
+    if (t.nhard[0] == 0u) return;                    /* every bucket was decided and coded from its staged elements */
+    const uint32_t bid = blockIdx.x;
+    uint32_t nblk = gridDim.x;
+    /* band and zero-threshold buckets: survivors from the dense accumulator, threshold known */
+    if (BITS != 32 && stream_coding)
+        dense_encode_body<(BITS == 32 ? 16 : BITS)>(r, t, c, idx, vdst, val, scales, reinterpret_cast<float *>(pool),
+                                                     pool + DENC_CAP, pool + 2 * DENC_CAP, err, bid, nblk);
+    else
+        write_dense_body<BITS == 32>(r, t, c, idx, vdst, (1u << PATH_BAND) | (1u << PATH_ZERO), bid, nblk);
+    /* the dense passes: the first `team` workgroups only (they are dispatched first and fit the
+     * device together whatever the others do, so their barriers cannot starve) */
+    if (t.nhard[2] == 0u || bid >= team) return;
+    __syncthreads();
+    nblk = team;
+    uint32_t *h = pool;
     uint32_t *bar = t.nhard + 1;
-    const uint32_t bid = blockIdx.x, nblk = gridDim.x;
     uint32_t arrivals = 0;
     if (bid == 0) fb_plan_body(t);
     grid_barrier(bar, arrivals += nblk, err);
@@ -991,18 +1292,47 @@ __global__ __launch_bounds__(WG) void k_hard(float *__restrict__ r, Tables t, Ca
     grid_barrier(bar, arrivals += nblk, err);
     for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); scan_body(t, c.G, c.E, nullptr, nullptr, 1, b); }
     grid_barrier(bar, arrivals += nblk, err);
-    write_dense_body<DIRECT>(r, t, c, idx, vdst, 1u << PATH_DENSE, bid, nblk);
+    write_dense_body<BITS == 32>(r, t, c, idx, vdst, 1u << PATH_DENSE, bid, nblk);
 }
 
-/* Value coding of the buckets whose survivors the ordered writes above left in idx / vdst
- * (everything but PATH_CAND); one workgroup per chunk, leaving at once when there is none. */
+/* Value coding of the survivors the ordered writes above left uncoded in idx / vdst: every chunk
+ * of a PATH_DENSE bucket, and of the band / zero-threshold buckets the chunks that the one-pass
+ * coding could not complete (all of them when it was not used).  Leaves at once when every
+ * bucket was coded from its staged elements.  Chunks of up to 256 survivors: a wavefront per
+ * chunk, QUANT_PER_WAVE chunks per wavefront; longer chunks: a workgroup each. */
+constexpr uint32_t QUANT_WAVE_CHUNK = 256;
 template <int BITS>
 __global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const uint32_t *__restrict__ idx, Tables t,
-                                              float *__restrict__ r, void *__restrict__ val,
-                                              float *__restrict__ scales, const uint32_t *__restrict__ chunk_b)
+                                              Cand c, float *__restrict__ r, void *__restrict__ val,
+                                              float *__restrict__ scales, const uint32_t *__restrict__ chunk_b,
+                                              const uint32_t *__restrict__ chunk_seg, uint64_t n_chunks, int stream_coding)
 {
     if (t.nhard[0] == 0u) return;
-    quant_body<BITS>(v, idx, t, r, val, scales, chunk_b, blockIdx.x);
+    if (t.chunk <= QUANT_WAVE_CHUNK) {
+        /* which of the workgroup's chunks are still to be coded: one lane per chunk */
+        constexpr uint32_t PER_WG = (WG / 64) * QUANT_PER_WAVE;
+        __shared__ uint32_t todo_sh;
+        const uint64_t cw = (uint64_t)blockIdx.x * PER_WG;
+        if (threadIdx.x < 64) {
+            const uint64_t cid = cw + threadIdx.x;
+            bool todo = false;
+            if (threadIdx.x < PER_WG && cid < n_chunks) {
+                const uint32_t b = chunk_b[cid];
+                const uint32_t path = t.fast[b];
+                todo = path != PATH_CAND;
+                if (todo && stream_coding && path != PATH_DENSE)
+                    todo = BITS <= 8 && !chunk_coded_by_stream(t, c, b, cid - t.C[b], chunk_seg[cid]);
+            }
+            const uint64_t bal = __ballot(todo);
+            if (threadIdx.x == 0) todo_sh = (uint32_t)bal;
+        }
+        __syncthreads();
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const uint32_t mine = (todo_sh >> (wave * QUANT_PER_WAVE)) & ((1u << QUANT_PER_WAVE) - 1u);
+        if (mine) quant_wave<BITS>(v, idx, t, r, val, scales, chunk_b, cw + wave * QUANT_PER_WAVE, mine);
+    } else {
+        quant_body<BITS>(v, idx, t, r, val, scales, chunk_b, blockIdx.x);
+    }
 }
 
 }  // namespace

@@ -178,6 +178,16 @@ def llama7b_grad(step: int, device="cpu", out: torch.Tensor | None = None,
     return g, off
 
 
+def llama_part_grad(step: int, device="cpu", nbuckets: int = 16, bucket: int = LLAMA_BUCKET):
+    """The first `nbuckets` buckets of the Llama-7B-shaped gradient as a gradient of its own
+    (16 buckets: 419,430,400 elements), the mid-size case the high-ratio measurements use."""
+    off = llama7b_bucket_offsets(bucket)[:nbuckets + 1]
+    g = torch.empty(int(off[-1]), device=device, dtype=torch.float32)
+    for b in range(nbuckets):
+        g[int(off[b]):int(off[b + 1])] = llama7b_bucket_values(step, b, device, bucket)
+    return g, off
+
+
 def llama7b_bucket_values(step: int, b: int, device="cpu", bucket: int = LLAMA_BUCKET):
     """The values of one Llama bucket, standalone (same bits as llama7b_grad writes)."""
     off = llama7b_bucket_offsets(bucket)

@@ -52,6 +52,29 @@ def test_ragged_unaligned_buckets(bits):
         c.step(ratio, bits)
 
 
+@pytest.mark.parametrize("chunk", [8, 64, 256, 264])
+@pytest.mark.parametrize("bits", [4, 8, 16])
+def test_high_ratios_with_small_chunks(bits, chunk):
+    """Ratios from an eighth up: the survivors are written and coded from the dense accumulator
+    in one pass when a chunk has at most 256 of them (264: the two-pass variant).  Buckets from a
+    few elements to many spans, unaligned starts, an empty one; the third step runs on the
+    residual of the first two, the last one on a gradient with 70 % exact zeros."""
+    sizes = [5, 70_000, 0, 1_000_003, 257, 4096, 300_001, 9, 2_500_000]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    c = Case(_rand(n, 900 + bits + chunk), off, chunk=chunk)
+    for step, ratio in enumerate((0.5, 0.2, 1.0, 0.13)):
+        c.set_grad(_rand(n, 950 + 10 * step + bits))
+        c.step(ratio, bits)
+    g = _rand(n, 990 + bits)
+    z = torch.rand(n, generator=torch.Generator(device=DEV).manual_seed(5), device=DEV)
+    g[z < 0.7] = 0.0
+    c.set_grad(g)
+    c.set_residual(np.zeros(n, dtype=np.float32))
+    c.step(0.45, bits)
+    c.step(0.3, bits)
+
+
 @pytest.mark.parametrize("ratio,bits", [(0.1, 8), (0.01, 4), (0.5, 32), (1.0, 32), (1.0, 4)])
 def test_heavy_ties_and_zeros(ratio, bits):
     """Magnitudes drawn from a handful of values, 60 % exact zeros of both signs: the threshold
@@ -148,6 +171,32 @@ def test_bert_shaped_scaled(ratio, bits):
             g[int(off[b]):int(off[b + 1])] = W._laplace(nb, 1e-4, gen, DEV)
     c = Case(g, off)
     c.step(ratio, bits)
+
+
+@pytest.mark.parametrize("delta", [-5000, -1, 0, 1, 5000])
+def test_threshold_at_the_boundary_between_zeros_and_values(path, delta):
+    """A bucket of 2 M elements with k + delta non-zero ones (k = 200,000): the sample cannot tell
+    whether the k-th largest magnitude is a zero, so a band from the smallest non-zero key up is
+    staged and the exact counts decide.  Two steps, the second with the residual of the first."""
+    n0, n1 = 2_000_000, 70_001
+    ratio = 0.1
+    k = int(np.floor(ratio * n0))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242 + delta)
+    g = torch.zeros(n0 + n1, device=DEV)
+    pos = torch.randperm(n0, generator=gen, device=DEV)[: k + delta]
+    v = W._laplace(k + delta, 1e-4, gen, DEV)
+    v[v == 0] = 1e-4
+    g[pos] = v
+    g[n0:] = W._laplace(n1, 1e-4, gen, DEV)
+    off = np.array([0, n0, n0 + n1], dtype=np.uint64)
+    c = Case(g, off, chunk=256)
+    c.step(ratio, 8)
+    st = c.ctx.bucket_state(0)
+    say("zero boundary", delta, path, st)
+    if path == "auto":
+        assert st["path"] == (3 if delta <= 0 else 2), st       # zero threshold / band, not the dense passes
+    c.step(ratio, 4)
 
 
 @pytest.mark.parametrize("span_tiles,seg_waves,group", [(1, 4, 16), (2, 8, 64), (4, 16, 16), (8, 8, 16),
