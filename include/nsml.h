@@ -162,9 +162,6 @@ int nsml_destroy(nsml_ctx *ctx);
  *   "span_tiles"   tiles of 4096 elements per workgroup of the streaming kernels: 1..16, 0 = by
  *                  gradient size
  *   "seg_waves"    wavefronts per workgroup of the streaming pass (4, 8 or 16), 0 = by span size
- *   "group"        lanes per staging segment in the kernels that walk staged entries (4, 16 or
- *                  64), 0 = by ratio
- *   "agg"          weight stage: level-1 histogram aggregated in LDS: 1 always, 0 never, -1 by size
  *   "force_dense"  1: decide every bucket by the dense passes over the accumulator (the path a
  *                  bucket takes when its candidates cannot decide it), 0: default
  *   "nt"           bit mask of non-temporal hints in the streaming pass (1 grad loads, 2 residual
@@ -173,6 +170,13 @@ int nsml_destroy(nsml_ctx *ctx);
  *   "rescan"       diagnostic: 1 makes the threshold search read the undecided keys from the
  *                  staged entries again (the path taken when a staging segment has no room left
  *                  for its copy of them), 0: default
+ *   "whistory"     pruning step: 1 (default) stages a narrow band of weight magnitudes around the
+ *                  threshold the previous call on this context found for the bucket (weights move
+ *                  little between steps; a band that misses costs a repeat of the weight pass, the
+ *                  result is the same), 0: the band always comes from a sample of the weights
+ *   "wband_miss"   diagnostic: 1 places the band of weight magnitudes that the pruning step stages
+ *                  beside the threshold, so that every bucket takes the repeat of the weight pass
+ *                  (the path of a band that missed), 0: default
  *   "trip_check"   diagnostic: 1 raises the flag a failed device-side consistency check raises,
  *                  so the error reporting of the next call can be exercised without a failure */
 int nsml_set_option(nsml_ctx *ctx, const char *name, int value);

@@ -35,16 +35,16 @@ enum Path : uint32_t {
 };
 
 enum KernelId {
-    KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN, KID_FB_PLAN,
-    KID_REFINE1, KID_PICK1, KID_REFINE2, KID_PICK2, KID_COUNT, KID_SCAN, KID_WRITE,
-    KID_QUANT, KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC, KID_WHIST, KID_WPLAN, KID_WMASK,
-    KID_SELECT, KID_FINISH, KID_ENCODE, KID_HARD, KID_N
+    KID_SETUP = 0, KID_SPANMAP, KID_CLEAR, KID_SAMPLE, KID_PREDICT, KID_EF_EMIT, KID_PLAN,
+    KID_SELECT, KID_FINISH, KID_ENCODE, KID_HARD, KID_QUANT,
+    KID_TILESTART, KID_DECOMP, KID_DECOMP_ACC,
+    KID_WHIST, KID_WPLAN, KID_WMASK, KID_WHARD, KID_N
 };
 const char *const kKernelNames[KID_N] = {
-    "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan", "fb_plan",
-    "refine1", "pick1", "refine2", "pick2", "count", "scan", "write",
-    "quant", "tilestart", "decomp", "decomp_acc", "whist", "wplan", "wmask",
-    "select_count", "select_finish", "encode", "hard"
+    "setup", "spanmap", "clear", "sample", "predict", "ef_emit", "plan",
+    "select_count", "select_finish", "encode", "hard", "quant",
+    "tilestart", "decomp", "decomp_acc",
+    "whist", "wplan", "wmask", "whard"
 };
 static_assert(KID_N <= NSML_MAX_KERNELS, "raise NSML_MAX_KERNELS");
 

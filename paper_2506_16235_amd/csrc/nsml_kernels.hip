@@ -78,7 +78,7 @@ struct nsml_ctx {
     uint4 *d_selw;         /* per workgroup of k_select_count: bucket, first and last segment */
     uint32_t *d_chunk_b;   /* per chunk of the payload: its bucket (fixed by layout, ratio, bits) */
     uint32_t *d_chunk_seg; /* per chunk: the staging segment that holds its first survivor */
-    uint32_t *d_H, *d_subLo, *d_sh, *d_why;
+    uint32_t *d_H, *d_subLo, *d_sh, *d_why, *d_wredo, *d_wnone, *d_wprevT, *d_wprevHw, *d_wnband;
     uint32_t *d_lcnt, *d_lkey;   /* k_select_count: lists of undecided keys per workgroup */
     uint64_t max_chunks; uint32_t max_sel;
     uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
@@ -110,13 +110,13 @@ struct nsml_ctx {
     void *pinned; size_t pinned_bytes;
     int span_override;
     int seg_override;      /* wavefronts per workgroup of the streaming pass (0: by span size) */
-    int group_override;    /* lanes per staging segment in the candidate kernels (0: by ratio) */
-    int agg_override;      /* level-1 candidate histogram aggregated in LDS: 1 always, 0 never, -1 by size */
     int force_dense;
     bool zero_clean; uint32_t zero_B;   /* the per-call histograms and flags were left zeroed (for this many buckets) */
     int persist;           /* workgroups per compute unit of the streaming pass (0: one workgroup per span) */
     int decomp_variant;    /* decompress: 1 direct stores, 0 tiles assembled in LDS, -1 by gradient size */
     int n_cu;
+    int whistory;          /* the weight band follows the threshold of the last call (1, default) or always comes from a sample (0) */
+    int wband_miss;        /* diagnostic: the weight band is placed beside the threshold, so every bucket takes the repeat */
     int force_rescan;      /* diagnostic: k_select_finish filters the staged entries again instead of using the tails */
     int nt_mode;
     int nt_dense;          /* non-temporal stores for the dense output of decompress: 1, 0, or -1 = by variant */
@@ -346,6 +346,7 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
     if (nsel)
         LAUNCH(c, KID_SPANMAP, st, k_selmap, (uint32_t)((nsel + WG - 1) / WG), (const uint32_t *)c->d_sel0,
                (const uint32_t *)c->d_span0, B, (uint32_t)nsel, segSh, c->d_selw);
+    NSML_HIP(c, hipMemsetAsync(c->d_wprevT, 0xFF, sizeof(uint32_t) * B1, st));     /* other buckets: nothing remembered */
     NSML_HIP(c, hipStreamSynchronize(st));
 
     c->h_off.assign(off, off + B + 1);
@@ -413,7 +414,7 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
-    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = nullptr;
+    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = c->d_wredo = c->d_wnone = c->d_wprevT = c->d_wprevHw = c->d_wnband = nullptr;
     c->d_lcnt = c->d_lkey = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
@@ -422,10 +423,10 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->have_prune = false;
     c->max_ratio = max_ratio;
     /* tuning switches: the measured defaults (see nsml_set_option) */
-    c->span_override = 0; c->seg_override = 0; c->segSh = 2; c->agg_override = -1; c->group_override = 0;
+    c->span_override = 0; c->seg_override = 0; c->segSh = 2;
     c->zero_clean = false; c->zero_B = 0;
     c->persist = 0; c->decomp_variant = -1; c->n_cu = 256;
-    c->force_dense = 0; c->force_rescan = 0; c->nt_mode = 7; c->nt_dense = -1;
+    c->force_dense = 0; c->force_rescan = 0; c->wband_miss = 0; c->whistory = 1; c->nt_mode = 7; c->nt_dense = -1;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
@@ -484,6 +485,14 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
     A(dev_alloc(c, &c->d_wT, B1)); A(dev_alloc(c, &c->d_wfast, B1)); A(dev_alloc(c, &c->d_wcut, B1));
     A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1));
+    A(dev_alloc(c, &c->d_wredo, B1)); A(dev_alloc(c, &c->d_wnone, B1));
+    A(dev_alloc(c, &c->d_wprevT, B1)); A(dev_alloc(c, &c->d_wprevHw, B1)); A(dev_alloc(c, &c->d_wnband, B1));
+    if (rc == NSML_OK) {
+        hipError_t e = hipMemset(c->d_wnone, 0xFF, sizeof(uint32_t) * B1);      /* NONE for every bucket */
+        if (e == hipSuccess) e = hipMemset(c->d_wredo, 0, sizeof(uint32_t) * B1);
+        if (e == hipSuccess) e = hipMemset(c->d_wprevT, 0xFF, sizeof(uint32_t) * B1);   /* nothing remembered */
+        if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
+    }
     if (rc == NSML_OK) {
         c->pinned_bytes = B1 * 24;
         hipError_t e = hipHostMalloc(&c->pinned, c->pinned_bytes, hipHostMallocDefault);
@@ -517,7 +526,7 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
                     c->d_Tw, c->d_needw, c->d_wT, c->d_wfast, c->d_wcut,
-                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why};
+                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why, c->d_wredo, c->d_wnone, c->d_wprevT, c->d_wprevHw, c->d_wnband};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->h_flags) (void)hipHostFree(c->h_flags);
@@ -558,7 +567,6 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
     float *vdst = bits == 32 ? static_cast<float *>(val) : c->d_v;
     const uint32_t n_ss = c->n_spans << c->segSh;
     const uint32_t eblock = 64u << c->segSh;
-    const uint32_t fgrid = c->n_spans < SIDE_GRID ? c->n_spans : SIDE_GRID;
     uint32_t egrid = c->n_spans;         /* streaming pass: one workgroup per span, or a fixed number per compute unit */
     if (c->persist > 0 && (uint32_t)(c->persist * c->n_cu) < egrid) egrid = (uint32_t)(c->persist * c->n_cu);
 
@@ -567,34 +575,36 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
          * had to take the dense passes), on its own set of tables */
         Tables tw = t;
         tw.k = c->d_kw; tw.T = c->d_Tw; tw.need = c->d_needw; tw.fast = c->d_wfast;
-        Cand cdw = cd0;
-        const uint32_t n_chunks_w = (n_ss + 63) / 64;
-        while (cdw.splitSh < 6u && ((uint64_t)n_chunks_w << cdw.splitSh) < 4ull * SIDE_GRID) ++cdw.splitSh;
-        const uint64_t wwaves = (uint64_t)n_chunks_w << cdw.splitSh;
-        const uint32_t cgw = c->force_dense ? 0u : (uint32_t)((wwaves + 3) / 4 < SIDE_GRID ? (wwaves + 3) / 4 : SIDE_GRID);
+        const Cand cdw = cd0;
         LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
         if (!c->force_dense)
             LAUNCH(c, KID_SAMPLE, st, k_sample<false>, c->n_samp, weights, (const float *)nullptr, tw, h.hs);
         LAUNCH(c, KID_WPLAN, st, k_wpredict, B, tw, (const uint32_t *)h.hs, c->d_wLo, c->d_wHi, c->force_dense,
-               c->d_flags + 1);
+               c->wband_miss, c->whistory ? (const uint32_t *)c->d_wprevT : (const uint32_t *)nullptr,
+               (const uint32_t *)c->d_wprevHw);
         LAUNCHB(c, KID_WHIST, st, k_whist, c->n_spans, eblock, weights, tw, h.h0, cdw,
-                (const uint32_t *)c->d_wLo, (const uint32_t *)c->d_wHi);
-        LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, (const uint32_t *)h.h0, (const uint32_t *)c->d_wLo,
-               (const uint32_t *)c->d_wHi);
-        LAUNCH(c, KID_FB_PLAN, st, k_fb_plan, 1, tw);
-        if (cgw && (c->agg_override > 0 || (c->agg_override < 0 && n_chunks_w >= 8u * SIDE_GRID)))
-            LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64, true>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
-        else
-            LAUNCH(c, KID_REFINE1, st, (k_refine<1, 64>), cgw + fgrid, weights, tw, cdw, h.c1, h.f1, cgw);
-        LAUNCH(c, KID_PICK1, st, k_pick<1>, B, tw, (const uint32_t *)h.c1, (const uint32_t *)h.f1, c->d_flags + 1);
-        LAUNCH(c, KID_REFINE2, st, (k_refine<2, 64>), cgw + fgrid, weights, tw, cdw, h.c2, h.f2, cgw);
-        LAUNCH(c, KID_PICK2, st, k_pick<2>, B, tw, (const uint32_t *)h.c2, (const uint32_t *)h.f2, c->d_flags + 1, c->d_wT);
-        LAUNCH(c, KID_COUNT, st, k_count<64>, cgw + fgrid, weights, tw, cdw, c->d_tG, c->d_tE, cgw);
-        LAUNCH(c, KID_SCAN, st, k_scan, B, tw, cdw.G, cdw.E, c->d_tG, c->d_tE);
-        LAUNCH(c, KID_WMASK, st, k_wfinish<64>, cgw + fgrid, weights, tw, cdw, (const uint32_t *)c->d_tG,
-               (const uint32_t *)c->d_tE, c->d_wcut, c->d_pmask, cgw);
+                (const uint32_t *)c->d_wLo, (const uint32_t *)c->d_wHi, c->d_pmask, (const uint32_t *)c->d_wredo, 0);
+        LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, h.h0, cdw, (const uint32_t *)c->d_wLo,
+               (const uint32_t *)c->d_wHi, c->d_wredo, c->d_wnband, 0);
+        /* the buckets whose band missed the threshold (rare): the pass again, exact histogram */
+        LAUNCHB(c, KID_WHIST, st, k_whist, c->n_spans, eblock, weights, tw, h.h0, cdw,
+                (const uint32_t *)c->d_wLo, (const uint32_t *)c->d_wHi, c->d_pmask, (const uint32_t *)c->d_wredo, 1);
+        LAUNCH(c, KID_WPLAN, st, k_wplan, B, tw, h.h0, cdw, (const uint32_t *)c->d_wLo,
+               (const uint32_t *)c->d_wHi, c->d_wredo, c->d_wnband, 1);
+        /* buckets decided from their band: undecided keys, threshold key and tie count, the pruned
+         * band elements' bits; buckets on the dense passes: everything in one resident launch */
+        if (!c->force_dense) {
+            LAUNCH(c, KID_SELECT, st, k_select_count, c->n_sel, tw, cdw, (const uint4 *)c->d_selw, h.tail_ovf, c->d_lcnt, c->d_lkey);
+            LAUNCHB(c, KID_FINISH, st, k_select_finish, B, SEL_THREADS, tw, cdw, (const uint32_t *)c->d_sel0, h.tail_ovf,
+                    (const uint32_t *)c->d_lcnt, (const uint32_t *)c->d_lkey, (uint32_t *)nullptr, c->d_flags + 1,
+                    c->force_rescan);
+            LAUNCH(c, KID_WMASK, st, k_wfix, (n_ss + 15) / 16, tw, cdw, c->d_pmask);
+        }
+        LAUNCH(c, KID_WHARD, st, k_whard, (uint32_t)c->n_cu, weights, tw, cdw, h.f1, h.f2, c->d_pmask, c->d_flags + 1);
+        LAUNCH(c, KID_WPLAN, st, k_wremember, (B + WG - 1) / WG, tw, (const uint32_t *)c->d_Tw, (const uint32_t *)c->d_wLo,
+               (const uint32_t *)c->d_wHi, (const uint32_t *)c->d_wnband, c->d_wprevT, c->d_wprevHw);
         t.w = weights;
-        t.wT = c->d_wT;
+        t.wT = c->d_wnone;
         t.wcut = c->d_wcut;
         t.pmask = c->d_pmask;
     }
@@ -1032,12 +1042,6 @@ int nsml_set_option(nsml_ctx *c, const char *name, int value)
         c->seg_override = value;
         c->B = 0;
         c->tables_valid = false;
-    } else if (is("group")) {
-        if (value != 0 && value != 4 && value != 16 && value != 64) return NSML_EINVAL;
-        c->group_override = value;
-    } else if (is("agg")) {
-        if (value < -1 || value > 1) return NSML_EINVAL;
-        c->agg_override = value;
     } else if (is("force_dense")) {
         if (value != 0 && value != 1) return NSML_EINVAL;
         c->force_dense = value;
@@ -1056,6 +1060,12 @@ int nsml_set_option(nsml_ctx *c, const char *name, int value)
     } else if (is("rescan")) {
         if (value != 0 && value != 1) return NSML_EINVAL;
         c->force_rescan = value;
+    } else if (is("whistory")) {
+        if (value != 0 && value != 1) return NSML_EINVAL;
+        c->whistory = value;
+    } else if (is("wband_miss")) {
+        if (value != 0 && value != 1) return NSML_EINVAL;
+        c->wband_miss = value;
     } else if (is("trip_check")) {
         if (value != 1) return NSML_EINVAL;
         *(volatile uint32_t *)&c->h_flags[0] = 1u;

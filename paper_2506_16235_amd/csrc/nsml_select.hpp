@@ -490,154 +490,9 @@ __device__ __forceinline__ void fb_plan_body(const Tables &t)
     }
     if (tid == 0) t.fspan0[t.B] = carry;
 }
-__global__ __launch_bounds__(WG) void k_fb_plan(Tables t) { fb_plan_body(t); }
-
-/* ------------------------------------------------------------------ candidate path */
-
-/* The candidate kernels walk the staging segments, 64 consecutive ones per wavefront at a
- * time.  Lane l first fetches what describes segment 64 * chunk + l (bucket, entry count,
- * threshold): one round of look-ups for 64 segments.  Then the wavefront goes through them
- * 64 / GROUP at a time, GROUP lanes per segment, taking each description from the lane that
- * holds it.  GROUP is 4 or 16 when segments are short (low ratios), 64 otherwise.  Entries are
- * fetched four per lane before any is used, so a segment costs about one memory round trip.
- * When there are fewer chunks than wavefronts, 2^splitSh wavefronts share a chunk and take
- * every 2^splitSh-th round of it. */
-struct SegMeta {
-    uint32_t ss, b, cnt;
-    uint32_t T;          /* the bucket's threshold key / prefix so far */
-    bool in_range, active;
-};
-
-__device__ __forceinline__ SegMeta seg_meta(const Tables &t, const Cand &c, uint32_t chunk)
-{
-    SegMeta m;
-    m.ss = chunk * 64 + (threadIdx.x & 63);
-    m.in_range = m.ss < (t.n_spans << t.segSh);
-    /* independent loads first (segment -> bucket, entry count), then the bucket's state */
-    m.b = m.in_range ? t.span_b[m.ss >> t.segSh] : 0u;
-    const uint32_t cnt = m.in_range ? c.cnt[m.ss] : 0u;
-    m.T = t.T[m.b];
-    m.active = m.in_range && t.fast[m.b] != 0u;
-    m.cnt = m.active ? cnt : 0u;
-    return m;
-}
-
-__device__ __forceinline__ uint32_t seg_chunks(const Tables &t) { return ((t.n_spans << t.segSh) + 63u) / 64u; }
 
 constexpr uint32_t CU = 4;   /* entries a lane fetches ahead */
 
-/* Next-digit histogram over the candidates that carry the prefix found so far (LEVEL 1:
- * 12-bit prefix, digit = key bits 18..7; LEVEL 2: 24-bit prefix, digit = bits 6..0).  The
- * matching entries are few, so they go straight to global atomics. */
-template <int LEVEL, uint32_t GROUP>
-__device__ __forceinline__ void crefine_body(const Tables &t, const Cand &c, uint32_t *__restrict__ hist,
-                                             uint32_t bid, uint32_t nblk)
-{
-    constexpr int NB = LEVEL == 1 ? NB1 : NB2;
-    constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
-    constexpr int DSH = LEVEL == 1 ? SH1 : 0;
-    constexpr uint32_t SPR = 64 / GROUP;             /* segments per round */
-    const uint32_t lane = threadIdx.x & 63, sub = lane / GROUP, gl = lane % GROUP;
-    const uint32_t n_chunks = seg_chunks(t);
-    const uint32_t split = 1u << c.splitSh;
-    for (uint32_t v = bid * 4 + (threadIdx.x >> 6); v < (n_chunks << c.splitSh); v += nblk * 4) {
-        const uint32_t chunk = v >> c.splitSh;
-        const SegMeta m = seg_meta(t, c, chunk);
-        if (__ballot(m.cnt != 0u) == 0ull) continue;
-        for (uint32_t rd = v & (split - 1u); rd < GROUP; rd += split) {
-            const uint32_t src = rd * SPR + sub;
-            const uint32_t cnt = __shfl(m.cnt, src, 64);
-            if (__ballot(cnt != 0u) == 0ull) continue;
-            const uint32_t prefix = __shfl(m.T, src, 64), b = __shfl(m.b, src, 64);
-            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
-            for (uint32_t i0 = gl; i0 < cnt; i0 += CU * GROUP) {
-                float x[CU];
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t i = i0 + u * GROUP;
-                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t key = keyof(x[u]);
-                    if (i0 + u * GROUP < cnt && (key >> PSH) == prefix)
-                        atomicAdd(&hist[(uint64_t)b * NB + ((key >> DSH) & (NB - 1))], 1u);
-                }
-            }
-        }
-    }
-}
-
-/* The same histogram when a large share of the staged elements carries the prefix (the weight
- * stage: a whole level-0 digit of the weights): a workgroup walks a contiguous range of
- * chunks, which almost always lies inside one bucket, counts in LDS and adds its histogram to
- * the bucket's once.  Groups of chunks that straddle two buckets count straight into global
- * memory.  h: NB words of LDS. */
-template <int LEVEL, uint32_t GROUP>
-__device__ __forceinline__ void crefine_agg_body(const Tables &t, const Cand &c, uint32_t *__restrict__ hist,
-                                                 uint32_t *h, uint32_t bid, uint32_t nblk)
-{
-    constexpr int NB = LEVEL == 1 ? NB1 : NB2;
-    constexpr int PSH = LEVEL == 1 ? SH0 : SH1;
-    constexpr int DSH = LEVEL == 1 ? SH1 : 0;
-    constexpr uint32_t SPR = 64 / GROUP;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sub = lane / GROUP, gl = lane % GROUP;
-    const uint32_t n_segs = t.n_spans << t.segSh;
-    const uint32_t n_chunks = seg_chunks(t);
-    const uint32_t per = (n_chunks + nblk - 1) / nblk;
-    const uint32_t start = min(n_chunks, bid * per), end = min(n_chunks, start + per);
-    for (int i = tid; i < NB; i += WG) h[i] = 0;
-    __syncthreads();
-    uint32_t cur_b = NONE;               /* bucket whose counts sit in LDS (same in every thread) */
-    for (uint32_t g0 = start; g0 < end; g0 += 4) {
-        /* the segments of this group of up to four chunks: one bucket or several? */
-        const uint32_t seg_a = g0 * 64, seg_z = min(n_segs, min(end, g0 + 4) * 64) - 1u;
-        const uint32_t b_a = t.span_b[seg_a >> t.segSh], b_z = t.span_b[seg_z >> t.segSh];
-        const bool one = b_a == b_z;
-        if (one && b_a != cur_b) {
-            __syncthreads();
-            if (cur_b != NONE) hist_flush(h, hist + (uint64_t)cur_b * NB, NB);
-            __syncthreads();
-            for (int i = tid; i < NB; i += WG) h[i] = 0;
-            __syncthreads();
-            cur_b = b_a;
-        }
-        const uint32_t chunk = g0 + wave;
-        if (chunk >= end) continue;
-        const SegMeta m = seg_meta(t, c, chunk);
-        if (__ballot(m.cnt != 0u) == 0ull) continue;
-        for (uint32_t rd = 0; rd < GROUP; ++rd) {
-            const uint32_t src = rd * SPR + sub;
-            const uint32_t cnt = __shfl(m.cnt, src, 64);
-            if (__ballot(cnt != 0u) == 0ull) continue;
-            const uint32_t prefix = __shfl(m.T, src, 64), b = __shfl(m.b, src, 64);
-            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
-            for (uint32_t i0 = gl; i0 < cnt; i0 += CU * GROUP) {
-                float x[CU];
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t i = i0 + u * GROUP;
-                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t key = keyof(x[u]);
-                    if (i0 + u * GROUP < cnt && (key >> PSH) == prefix) {
-                        const uint32_t d = (key >> DSH) & (NB - 1);
-                        if (one) atomicAdd(&h[d], 1u);
-                        else atomicAdd(&hist[(uint64_t)b * NB + d], 1u);
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
-    if (cur_b != NONE) hist_flush(h, hist + (uint64_t)cur_b * NB, NB);
-}
-
-/* Per bucket, levels 1 and 2: walk the level's histogram (the candidates' one or the dense
- * fallback's, whichever path the bucket is on) to the digit holding the need-th entry and
- * append it to the prefix. */
 template <int LEVEL>
 __device__ __forceinline__ void pick_body(const Tables &t, const uint32_t *__restrict__ hist_c,
                                           const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
@@ -671,63 +526,6 @@ __device__ __forceinline__ void pick_body(const Tables &t, const uint32_t *__res
          * threshold itself (and, next, the last kept index among equal weights); the others a
          * bitmap */
         if (LEVEL == 2 && wT_out) wT_out[b] = t.fast[b] ? T : NONE;
-    }
-}
-
-template <int LEVEL>
-__global__ __launch_bounds__(WG) void k_pick(Tables t, const uint32_t *__restrict__ hist_c,
-                                             const uint32_t *__restrict__ hist_f, uint32_t *__restrict__ err,
-                                             uint32_t *__restrict__ wT_out = nullptr, int only_fb = 0)
-{
-    pick_body<LEVEL>(t, hist_c, hist_f, err, wT_out, only_fb, blockIdx.x);
-}
-
-/* Per segment: how many candidates exceed the threshold, how many equal it.  The counts of
- * a chunk's 64 segments are gathered back into the lanes that described them and stored
- * side by side. */
-template <uint32_t GROUP>
-__device__ __forceinline__ void ccount_body(const Tables &t, const Cand &c, uint32_t bid, uint32_t nblk)
-{
-    constexpr uint32_t SPR = 64 / GROUP;
-    const uint32_t lane = threadIdx.x & 63, sub = lane / GROUP, gl = lane % GROUP;
-    const uint32_t n_chunks = seg_chunks(t);
-    const uint32_t split = 1u << c.splitSh;
-    for (uint32_t v = bid * 4 + (threadIdx.x >> 6); v < (n_chunks << c.splitSh); v += nblk * 4) {
-        const uint32_t chunk = v >> c.splitSh, part = v & (split - 1u);
-        const SegMeta m = seg_meta(t, c, chunk);
-        if (__ballot(m.active) == 0ull) continue;
-        uint32_t my_g = 0, my_e = 0;             /* results for segment 64 * chunk + lane */
-        for (uint32_t rd = part; rd < GROUP; rd += split) {
-            const uint32_t src = rd * SPR + sub;
-            const uint32_t cnt = __shfl(m.cnt, src, 64);
-            if (__ballot(cnt != 0u) == 0ull) continue;
-            const uint32_t T = __shfl(m.T, src, 64);
-            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
-            uint32_t ng = 0, ne = 0;
-            for (uint32_t i0 = gl; i0 < cnt; i0 += CU * GROUP) {
-                float x[CU];
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t i = i0 + u * GROUP;
-                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t key = keyof(x[u]);
-                    const bool in = i0 + u * GROUP < cnt;
-                    ng += (in && key > T) ? 1u : 0u;
-                    ne += (in && key == T) ? 1u : 0u;
-                }
-            }
-#pragma unroll
-            for (int d = GROUP / 2; d >= 1; d >>= 1) { ng += __shfl_xor(ng, d, 64); ne += __shfl_xor(ne, d, 64); }
-            /* segment rd * SPR + j was counted by the group of lanes starting at j * GROUP */
-            const uint32_t from = (lane % SPR) * GROUP;
-            const uint32_t got_g = __shfl(ng, from, 64), got_e = __shfl(ne, from, 64);
-            if (lane / SPR == rd) { my_g = got_g; my_e = got_e; }
-        }
-        /* this wavefront took the rounds congruent to `part` */
-        if (m.active && ((lane / SPR) & (split - 1u)) == part) { c.G[m.ss] = my_g; c.E[m.ss] = my_e; }
     }
 }
 
@@ -777,79 +575,6 @@ __device__ __forceinline__ void scan_body(const Tables &t, uint32_t *__restrict_
             run += v[j];
         }
         carry += total;
-    }
-}
-
-__global__ __launch_bounds__(WG) void k_scan(Tables t, uint32_t *__restrict__ cG, uint32_t *__restrict__ cE,
-                                             uint32_t *__restrict__ tG, uint32_t *__restrict__ tE, int only_fb = 0)
-{
-    scan_body(t, cG, cE, tG, tE, only_fb, blockIdx.x);
-}
-
-/* Per segment: copy the admitted candidates (key > T, or key == T and among the first e_b
- * equal ones of the bucket in index order) to their final slots. */
-template <uint32_t GROUP, bool CUT = false>   /* CUT (weight stage): only record, per bucket in idx_out[b],
-                                               * the index of the last admitted entry equal to the threshold */
-__device__ __forceinline__ void cwrite_body(const Tables &t, const Cand &c, uint32_t *__restrict__ idx_out,
-                                            float *__restrict__ v_out, uint32_t bid, uint32_t nblk)
-{
-    constexpr uint32_t SPR = 64 / GROUP;
-    const uint32_t lane = threadIdx.x & 63, sub = lane / GROUP, gl = lane % GROUP;
-    const uint32_t shift = sub * GROUP;
-    const uint64_t below = (1ull << gl) - 1ull;
-    const uint64_t gmask = GROUP == 64 ? ~0ull : ((1ull << (GROUP % 64)) - 1ull);
-    const uint32_t n_chunks = seg_chunks(t);
-    const uint32_t split = 1u << c.splitSh;
-    for (uint32_t v = bid * 4 + (threadIdx.x >> 6); v < (n_chunks << c.splitSh); v += nblk * 4) {
-        const uint32_t chunk = v >> c.splitSh;
-        const SegMeta m = seg_meta(t, c, chunk);
-        if (__ballot(m.cnt != 0u) == 0ull) continue;
-        const uint32_t m_g = m.in_range ? c.G[m.ss] : 0u, m_e = m.in_range ? c.E[m.ss] : 0u;
-        const uint32_t m_need = t.need[m.b];
-        const uint64_t m_P = t.P[m.b];
-        for (uint32_t rd = v & (split - 1u); rd < GROUP; rd += split) {
-            const uint32_t src = rd * SPR + sub;
-            const uint32_t cnt = __shfl(m.cnt, src, 64);
-            /* the groups of the wavefront advance together: ballots need every lane */
-            uint32_t maxcnt = cnt;
-#pragma unroll
-            for (int d = 32; d >= (int)GROUP; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
-            if (maxcnt == 0u) continue;
-            const uint32_t T = __shfl(m.T, src, 64), e_b = __shfl(m_need, src, 64);
-            uint32_t run_g = __shfl(m_g, src, 64), run_e = __shfl(m_e, src, 64);
-            const uint64_t Pb = ((uint64_t)__shfl((uint32_t)(m_P >> 32), src, 64) << 32) |
-                                (uint64_t)__shfl((uint32_t)m_P, src, 64);
-            const uint32_t bkt = __shfl(m.b, src, 64);
-            const uint64_t base = (uint64_t)(chunk * 64 + src) * c.cap;
-            for (uint32_t i0 = 0; i0 < maxcnt; i0 += CU * GROUP) {
-                float x[CU];
-                uint32_t li[CU];
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t i = i0 + u * GROUP + gl;
-                    x[u] = i < cnt ? c.val[base + i] : 0.0f;
-                    li[u] = i < cnt ? c.idx[base + i] : 0u;
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < CU; ++u) {
-                    const uint32_t key = keyof(x[u]);
-                    const bool in = i0 + u * GROUP + gl < cnt;
-                    const bool isg = in && key > T, ise = in && key == T;
-                    const uint64_t bg = (__ballot(isg) >> shift) & gmask;
-                    const uint64_t be = (__ballot(ise) >> shift) & gmask;
-                    const uint32_t pg = run_g + __popcll(bg & below), pe = run_e + __popcll(be & below);
-                    if (CUT) {
-                        if (ise && pe + 1u == e_b) idx_out[bkt] = li[u];
-                    } else if (isg || (ise && pe < e_b)) {
-                        const uint64_t pos = Pb + pg + min(e_b, pe);
-                        idx_out[pos] = li[u];
-                        v_out[pos] = x[u];
-                    }
-                    run_g += __popcll(bg);
-                    run_e += __popcll(be);
-                }
-            }
-        }
     }
 }
 
@@ -908,178 +633,6 @@ __device__ __forceinline__ void fb_refine_body(const float *__restrict__ r, cons
         hist_flush(h, hist + (uint64_t)b * NB, NB);
         __syncthreads();
     }
-}
-
-/* Per tile of a fallback bucket: how many keys exceed the threshold, how many equal it. */
-__device__ __forceinline__ void fb_count_body(const float *__restrict__ r, const Tables &t,
-                                              uint32_t *__restrict__ tG, uint32_t *__restrict__ tE,
-                                              uint32_t (*cnt)[2], uint32_t bid, uint32_t nblk)
-{
-    const uint32_t tid = threadIdx.x;
-    const uint32_t total = t.fspan0[t.B];
-    for (uint32_t fs = bid; fs < total; fs += nblk) {
-        const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
-        const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
-        const uint32_t T = t.T[b];
-        if (tid < MAX_SPAN_TILES * 2) (&cnt[0][0])[tid] = 0;
-        __syncthreads();
-        for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-            const uint64_t tb = s.base + (uint64_t)ti * TILE;
-            uint32_t ng = 0, ne = 0;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-                float x[4];
-                uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-                if (t.w) m &= ~pruned_quad(t, t.wT[b], t.wcut[b], s.tile_g + ti, u * WG + tid, gi, s.lo, s.hi);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t key = keyof(x[j]);
-                    const bool ok = (m >> j) & 1u;
-                    ng += (ok && key > T) ? 1u : 0u;
-                    ne += (ok && key == T) ? 1u : 0u;
-                }
-            }
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) {
-                ng += __shfl_xor(ng, d, 64);
-                ne += __shfl_xor(ne, d, 64);
-            }
-            if ((tid & 63) == 0) { atomicAdd(&cnt[ti][0], ng); atomicAdd(&cnt[ti][1], ne); }
-        }
-        __syncthreads();
-        if (tid < s.ntiles) { tG[s.tile_g + tid] = cnt[tid][0]; tE[s.tile_g + tid] = cnt[tid][1]; }
-        __syncthreads();
-    }
-}
-
-/* Per tile of a fallback bucket: write the survivors to their final slots, in ascending
- * index order.  Inside a tile, thread t owns the quads (u*256 + t)*4, u = 0..3. */
-template <bool MASKOUT>
-__device__ __forceinline__ void fb_write_body(const float *__restrict__ r, const Tables &t,
-                                              const uint32_t *__restrict__ tG,
-                                              const uint32_t *__restrict__ tE,
-                                              uint32_t *__restrict__ idx_out,
-                                              float *__restrict__ v_out, uint32_t (*tot)[2],
-                                              uint32_t *bitmap, uint32_t *__restrict__ mask_out,
-                                              uint32_t bid, uint32_t nblk)
-{
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint64_t lt = (1ull << lane) - 1ull;
-    const uint32_t total = t.fspan0[t.B];
-    for (uint32_t fs = bid; fs < total; fs += nblk) {
-        const uint32_t b = find_bucket<uint32_t>(t.fspan0, t.B, fs);
-        const SpanGeo s = span_geo_b(t, b, fs - t.fspan0[b]);
-        const uint32_t T = t.T[b], e_b = t.need[b];
-        const uint64_t Pb = t.P[b];
-        for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
-            const uint64_t tb = s.base + (uint64_t)ti * TILE;
-            const uint32_t gpre = tG[s.tile_g + ti], epre = tE[s.tile_g + ti];
-            float x[4][4];
-            uint32_t fg[4], fe[4], gb[4], eb[4], vm[4] = {0, 0, 0, 0};
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-                uint32_t m = load_quad(r, gi, s.lo, s.hi, x[u]);
-                if (!MASKOUT && t.w) m &= ~pruned_quad(t, t.wT[b], t.wcut[b], s.tile_g + ti, u * WG + tid, gi, s.lo, s.hi);
-                fg[u] = fe[u] = 0;
-                if (MASKOUT) {
-                    vm[u] = m;
-                    if (u == 0 && tid < TILE / 32) bitmap[tid] = 0u;
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t key = keyof(x[u][j]);
-                    if (((m >> j) & 1u) && key > T) fg[u] |= 1u << j;
-                    if (((m >> j) & 1u) && key == T) fe[u] |= 1u << j;
-                }
-                uint32_t cg = 0, ce = 0, wg = 0, we = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint64_t bg = __ballot((fg[u] >> j) & 1u);
-                    const uint64_t be = __ballot((fe[u] >> j) & 1u);
-                    cg += __popcll(bg & lt); wg += __popcll(bg);
-                    ce += __popcll(be & lt); we += __popcll(be);
-                }
-                gb[u] = cg; eb[u] = ce;
-                if (lane == 0) { tot[u * 4 + wave][0] = wg; tot[u * 4 + wave][1] = we; }
-            }
-            __syncthreads();
-            uint32_t run_g = 0, run_e = 0;
-            int sl = 0;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int mine = u * 4 + (int)wave;
-                for (; sl < mine; ++sl) { run_g += tot[sl][0]; run_e += tot[sl][1]; }
-                uint32_t pg = gpre + run_g + gb[u];
-                uint32_t pe = epre + run_e + eb[u];
-                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
-                uint32_t kept = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const bool isg = (fg[u] >> j) & 1u, ise = (fe[u] >> j) & 1u;
-                    if (isg || (ise && pe < e_b)) {
-                        if (MASKOUT) {
-                            kept |= 1u << j;
-                        } else {
-                            const uint64_t pos = Pb + pg + min(e_b, pe);
-                            idx_out[pos] = (uint32_t)(gi + j - s.lo);
-                            v_out[pos] = x[u][j];
-                        }
-                    }
-                    pg += isg ? 1u : 0u;
-                    pe += ise ? 1u : 0u;
-                }
-                if (MASKOUT) {
-                    /* pruned = inside the bucket and not kept; 8 quads share a bitmap word */
-                    const uint32_t q = u * WG + tid;
-                    const uint32_t bits = vm[u] & ~kept;
-                    if (bits) atomicOr(&bitmap[q >> 3], bits << ((q & 7u) * 4u));
-                }
-            }
-            __syncthreads();
-            if (MASKOUT && tid < TILE / 32) mask_out[(uint64_t)(s.tile_g + ti) * (TILE / 32) + tid] = bitmap[tid];
-        }
-    }
-}
-
-/* ------------------------------------------------------------------ merged stages */
-
-/* Each selection stage is one launch: the first cgrid workgroups walk the candidate segments,
- * the others walk the dense spans of the fallback buckets (usually none: they read the empty
- * list and leave). */
-template <int LEVEL, uint32_t GROUP, bool AGG = false>
-__global__ __launch_bounds__(WG) void k_refine(const float *__restrict__ r, Tables t, Cand c,
-                                               uint32_t *__restrict__ hist_c, uint32_t *__restrict__ hist_f,
-                                               uint32_t cgrid)
-{
-    __shared__ uint32_t h[LEVEL == 1 ? NB1 : NB2];
-    if (blockIdx.x < cgrid) {
-        if (AGG) crefine_agg_body<LEVEL, GROUP>(t, c, hist_c, h, blockIdx.x, cgrid);
-        else crefine_body<LEVEL, GROUP>(t, c, hist_c, blockIdx.x, cgrid);
-    } else fb_refine_body<LEVEL>(r, t, hist_f, h, blockIdx.x - cgrid, gridDim.x - cgrid);
-}
-
-template <uint32_t GROUP>
-__global__ __launch_bounds__(WG) void k_count(const float *__restrict__ r, Tables t, Cand c,
-                                              uint32_t *__restrict__ tG, uint32_t *__restrict__ tE,
-                                              uint32_t cgrid)
-{
-    __shared__ uint32_t cnt[MAX_SPAN_TILES][2];
-    if (blockIdx.x < cgrid) ccount_body<GROUP>(t, c, blockIdx.x, cgrid);
-    else fb_count_body(r, t, tG, tE, cnt, blockIdx.x - cgrid, gridDim.x - cgrid);
-}
-
-template <uint32_t GROUP>
-__global__ __launch_bounds__(WG) void k_write(const float *__restrict__ r, Tables t, Cand c,
-                                              const uint32_t *__restrict__ tG, const uint32_t *__restrict__ tE,
-                                              uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
-                                              uint32_t cgrid)
-{
-    __shared__ uint32_t tot[16][2];      /* slot = u * 4 + wavefront */
-    if (blockIdx.x < cgrid) cwrite_body<GROUP>(t, c, idx_out, v_out, blockIdx.x, cgrid);
-    else fb_write_body<false>(r, t, tG, tE, idx_out, v_out, tot, nullptr, nullptr, blockIdx.x - cgrid,
-                              gridDim.x - cgrid);
 }
 
 }  // namespace

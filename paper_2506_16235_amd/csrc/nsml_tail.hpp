@@ -338,7 +338,8 @@ __device__ __forceinline__ void finish_prefixes(const Tables &t, const Cand &c, 
             /* survivors of this segment have ranks [r0, r1): the chunks that start among them */
             const uint64_t r0 = (uint64_t)Gp + min(e_b, Ep);
             const uint64_t r1 = (uint64_t)Gp + g + min((uint64_t)e_b, (uint64_t)Ep + q);
-            for (uint64_t cb = (r0 + chunk - 1) / chunk; cb * chunk < r1; ++cb) chunk_seg[Cb + cb] = s;
+            if (chunk_seg)                           /* not for the weight stage: its ranks are no payload positions */
+                for (uint64_t cb = (r0 + chunk - 1) / chunk; cb * chunk < r1; ++cb) chunk_seg[Cb + cb] = s;
         }
         run += tt;
     }
@@ -1333,6 +1334,136 @@ __global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const
     } else {
         quant_body<BITS>(v, idx, t, r, val, scales, chunk_b, blockIdx.x);
     }
+}
+
+/* ------------------------------------------------------------------ weight stage: the bitmap */
+
+/* The staged band elements of a bucket decided from its band that are pruned get their bit in the
+ * bitmap (k_whist left 0 for the whole band): below the threshold key, or equal to it and not
+ * among the first e equal ones in index order (k_select_finish left T, e and, per segment, the
+ * number of equal keys before it).  Sixteen lanes per staging segment, four segments per
+ * wavefront. */
+__global__ __launch_bounds__(WG) void k_wfix(Tables t, Cand c, uint32_t *__restrict__ pmask)
+{
+    const uint32_t lane = threadIdx.x & 63, sub = lane >> 4, gl = lane & 15u;
+    const uint32_t n_seg = t.n_spans << t.segSh;
+    const uint32_t ss = (blockIdx.x * (WG / 64) + (threadIdx.x >> 6)) * 4u + sub;
+    uint32_t cnt = 0, T = 0, e_b = 0, run_e = 0, b = 0, head = 0;
+    if (ss < n_seg) {
+        b = t.span_b[ss >> t.segSh];
+        if (t.fast[b] == PATH_BAND && t.k[b] != 0u) {
+            cnt = c.cnt[ss];
+            T = t.T[b]; e_b = t.need[b]; run_e = c.E[ss];
+            head = (uint32_t)(t.off[b] & 3ull);
+        }
+    }
+    uint32_t maxcnt = cnt;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
+    const uint64_t base = (uint64_t)ss * c.cap;
+    for (uint32_t i0 = 0; i0 < maxcnt; i0 += 16) {
+        const uint32_t i = i0 + gl;
+        const bool in = i < cnt;
+        const uint32_t key = in ? keyof(c.val[base + i]) : 0u;
+        const uint32_t li = in ? c.idx[base + i] : 0u;
+        const bool ise = in && key == T;
+        const uint32_t be = (uint32_t)(__ballot(ise) >> (sub * 16u)) & 0xFFFFu;
+        const uint32_t pe = run_e + __popc(be & ((1u << gl) - 1u));
+        if (in && (key < T || (ise && pe >= e_b))) {
+            const uint64_t e = (uint64_t)li + head;          /* position counted from the bucket's first tile */
+            const uint32_t tile = t.tile0[b] + (uint32_t)(e / TILE);
+            const uint32_t inq = (uint32_t)(e % TILE);
+            atomicOr(&pmask[(uint64_t)tile * (TILE / 32) + (inq >> 5)], 1u << (inq & 31u));
+        }
+        run_e += __popc(be);
+    }
+}
+
+/* Bitmap of a bucket that went through the dense passes (T, e and the per-segment prefixes are
+ * known): one wavefront per staging segment walks the weights it covers in index order; a weight
+ * is kept when its key exceeds T or equals it among the first e such, everything else gets its
+ * bit.  Every word of the bucket's tiles is written. */
+__device__ __forceinline__ void mask_dense_body(const float *__restrict__ w, const Tables &t, const Cand &c,
+                                                uint32_t *__restrict__ pmask, uint32_t bid, uint32_t nblk)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t n_seg = t.n_spans << t.segSh;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    for (uint32_t ss = bid * (WG / 64) + wave; ss < n_seg; ss += nblk * (WG / 64)) {
+        const uint32_t span = ss >> t.segSh, wslot = ss & ((1u << t.segSh) - 1u);
+        const uint32_t b = t.span_b[span];
+        if (t.fast[b] != PATH_DENSE || t.k[b] == 0u) continue;
+        const SpanGeo s = span_geo_b(t, b, span - t.span0[b]);
+        const uint32_t T = t.T[b], e_b = t.need[b];
+        uint32_t run_e = c.E[ss];
+        const uint32_t per = (t.spanT * 4u) >> t.segSh;
+        const uint32_t wt0 = wslot * per, wt1 = min(s.ntiles * 4u, wt0 + per);
+        for (uint32_t wt = wt0; wt < wt1; ++wt) {
+            const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                float x[4];
+                const uint32_t m = load_quad(w, gi, s.lo, s.hi, x);
+                uint32_t fe = 0, bits = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t key = keyof(x[j]);
+                    if ((m >> j) & 1u) { fe |= (key == T ? 1u : 0u) << j; bits |= (key < T ? 1u : 0u) << j; }
+                }
+                uint32_t pe = run_e, te = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint64_t be = __ballot((fe >> j) & 1u);
+                    pe += __popcll(be & lt);
+                    te += __popcll(be);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool ise = (fe >> j) & 1u;
+                    if (ise && pe >= e_b) bits |= 1u << j;
+                    pe += ise ? 1u : 0u;
+                }
+                run_e += te;
+                uint32_t word = bits << ((lane & 7u) * 4u);
+                word |= __shfl_xor(word, 1, 64);
+                word |= __shfl_xor(word, 2, 64);
+                word |= __shfl_xor(word, 4, 64);
+                if ((lane & 7u) == 0u)
+                    pmask[(uint64_t)(s.tile_g + (wt >> 2)) * (TILE / 32) + (wt & 3u) * (WG / 8) + u * 8 + (lane >> 3)] = word;
+            }
+        }
+    }
+}
+
+/* The weight buckets on the dense passes (no usable band, or a band that missed twice over), in
+ * one launch of a small resident grid with barriers between the steps, like k_hard: spans,
+ * level-1 histogram of |w|, digit, level-2 histogram, digit, counts per segment, prefixes,
+ * bitmap.  Leaves at once when there is no such bucket. */
+__global__ __launch_bounds__(WG) void k_whard(const float *__restrict__ w, Tables t, Cand c, uint32_t *__restrict__ f1,
+                                              uint32_t *__restrict__ f2, uint32_t *__restrict__ pmask,
+                                              uint32_t *__restrict__ err)
+{
+    __shared__ uint32_t h[NB1];
+    if (t.nhard[2] == 0u) return;
+    const uint32_t bid = blockIdx.x, nblk = gridDim.x;
+    uint32_t *bar = t.nhard + 1;
+    uint32_t arrivals = 0;
+    if (bid == 0) fb_plan_body(t);
+    grid_barrier(bar, arrivals += nblk, err);
+    fb_refine_body<1>(w, t, f1, h, bid, nblk);
+    grid_barrier(bar, arrivals += nblk, err);
+    for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); pick_body<1>(t, f1, f1, err, nullptr, 1, b); }
+    grid_barrier(bar, arrivals += nblk, err);
+    fb_refine_body<2>(w, t, f2, h, bid, nblk);
+    grid_barrier(bar, arrivals += nblk, err);
+    for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); pick_body<2>(t, f2, f2, err, nullptr, 1, b); }
+    grid_barrier(bar, arrivals += nblk, err);
+    segcount_dense_body(w, t, c, bid, nblk);
+    grid_barrier(bar, arrivals += nblk, err);
+    for (uint32_t b = bid; b < t.B; b += nblk) { __syncthreads(); scan_body(t, c.G, c.E, nullptr, nullptr, 1, b); }
+    grid_barrier(bar, arrivals += nblk, err);
+    mask_dense_body(w, t, c, pmask, bid, nblk);
 }
 
 }  // namespace

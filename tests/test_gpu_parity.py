@@ -199,22 +199,18 @@ def test_threshold_at_the_boundary_between_zeros_and_values(path, delta):
     c.step(ratio, 4)
 
 
-@pytest.mark.parametrize("span_tiles,seg_waves,group", [(1, 4, 16), (2, 8, 64), (4, 16, 16), (8, 8, 16),
-                                                        (16, 4, 64), (16, 8, 16), (16, 16, 16), (16, 16, 64), (16, 16, 4), (2, 4, 4)])
-def test_streaming_geometries(monkeypatch, span_tiles, seg_waves, group):
-    # the level-1 histogram of the candidates aggregated in LDS (the rule from ~2 G elements up)
-    monkeypatch.setitem(nsml.Context.default_options, "agg", 1 if (span_tiles + seg_waves + group) % 8 == 4 or group == 4 else 0)
-    """The library picks tiles per workgroup, wavefronts per workgroup and lanes per staging
-    segment from the size of the gradient; the large-gradient shapes are forced here on a
+@pytest.mark.parametrize("span_tiles,seg_waves", [(1, 4), (2, 8), (4, 16), (8, 8), (16, 4), (16, 8), (16, 16), (2, 4)])
+def test_streaming_geometries(monkeypatch, span_tiles, seg_waves):
+    """The library picks tiles per workgroup and wavefronts per workgroup from the size of the
+    gradient; the large-gradient shapes are forced here on a
     gradient the oracle sorts in a second: ragged buckets, last spans with fewer tiles than
     wavefronts, ties at the threshold, two error-feedback steps."""
     monkeypatch.setitem(nsml.Context.default_options, "span_tiles", int(span_tiles))
     monkeypatch.setitem(nsml.Context.default_options, "seg_waves", int(seg_waves))
-    monkeypatch.setitem(nsml.Context.default_options, "group", int(group))
     sizes = [200_003, 65_536 * 3 + 1, 4_099, 0, 333_333, 70_001]
     off = W.offsets_of(sizes)
     n = int(off[-1])
-    say("geometry", span_tiles, seg_waves, group, n)
+    say("geometry", span_tiles, seg_waves, n)
     g = _rand(n, 4242)
     g[5_000:9_000] = torch.round(g[5_000:9_000] * 2e3) / 2e3          # plateaus of equal magnitudes
     c = Case(g, off, chunk=512)

@@ -18,10 +18,10 @@ def _case(seed, pruned, monkeypatch):
     rs = np.random.RandomState(seed)
     st = int(rs.choice([0, 1, 2, 4, 8, 16]))
     sw = int(rs.choice([0, 4, 8, 16]))
-    grp = int(rs.choice([0, 4, 16, 64]))
-    for k, v in (("span_tiles", st), ("seg_waves", sw), ("group", grp)):
+    rs.choice([0, 4, 16, 64])                 # (keeps the stream of the later draws as it was)
+    for k, v in (("span_tiles", st), ("seg_waves", sw)):
         monkeypatch.setitem(nsml.Context.default_options, k, v)
-    monkeypatch.setitem(nsml.Context.default_options, "agg", int(int(rs.randint(0, 2))))
+    rs.randint(0, 2)                          # (keeps the stream of the later draws as it was)
     monkeypatch.setitem(nsml.Context.default_options, "force_dense", 1 if rs.rand() < 0.15 else 0)
     monkeypatch.setitem(nsml.Context.default_options, "rescan", 1 if rs.rand() < 0.25 else 0)
     B = int(rs.randint(1, 9))
@@ -40,7 +40,7 @@ def _case(seed, pruned, monkeypatch):
     gen = torch.Generator(device=DEV)
     gen.manual_seed(seed)
     say("random case", seed, "pruned" if pruned else "plain", sizes, "chunk", chunk, "bits", bits, "dist", dist,
-        "geometry", st, sw, grp)
+        "geometry", st, sw)
 
     def grad():
         g = torch.randn(n, generator=gen, device=DEV) * 1e-3
