@@ -202,7 +202,9 @@ class Job:
         return prof, wall
 
     def floor_bytes(self):
-        return 16.0 * self.n + 2.0 * self.payload
+        """What one step must move at least: grad and residual read, accumulator written, dense
+        output written, the payload written and read; with pruning also the weights read once."""
+        return (20.0 if self.weights is not None else 16.0) * self.n + 2.0 * self.payload
 
     def summary(self, ms_per_step, prof, steps):
         per_step = {k: ms / steps for k, (c, ms) in prof.items() if c >= steps}
@@ -223,7 +225,8 @@ def other_workloads(chunk, dev):
     """The remaining benchmark configurations, a few steps each (bounded: about 10 s)."""
     out = {}
     plan = [("bert", [(0.1, 8), (0.1, 4), (0.01, 8), (0.01, 4), (0.001, 8), (0.001, 4)], 30, 5),
-            ("resnet50", [(0.05, 8)], 50, 5), ("cfg1", [(0.01, 8)], 100, 10)]
+            ("resnet50", [(0.05, 8)], 50, 5), ("cfg1", [(0.01, 8)], 100, 10),
+            ("llama419m", [(0.5, 8), (1.0, 8), (0.13, 8)], 10, 3)]
     import torch
     for workload, combos, steps, warm in plan:
         grads, off = make_grads(workload, DEFAULTS[workload][2], dev)
@@ -411,7 +414,18 @@ def main():
         out["cpu_baseline"] = cpu_baseline(args.workload, grads, off, ratio, bits, chunk)
     if not args.no_other_workloads and args.workload == "llama7b" and not args.prune and not args.graph:
         job.ctx.close()
-        del job, grads
+        del job
+        torch.cuda.empty_cache()
+        # the same step preceded by the weight-magnitude pruning of Algorithm 2 Step 2
+        pj = Job(args.workload, grads, off, ratio, bits, chunk, prune=True)
+        pms = pj.timed(4, 2)
+        pprof, _ = pj.profiled(4)
+        band, wdense = pj.ctx.prune_stats()
+        out["pruned_variant"] = pj.summary(pms, pprof, 4)
+        out["pruned_variant"]["weight_buckets"] = {"from_band": band, "dense_passes": wdense}
+        log(f"[bench] pruned variant: {pms:.3f} ms/step")
+        pj.ctx.close()
+        del pj, grads
         torch.cuda.empty_cache()
         out["other_workloads"] = other_workloads(chunk, dev)
     print(json.dumps(out), flush=True)

@@ -138,9 +138,9 @@ typedef struct nsml_ctx nsml_ctx;
 
 /* Allocate a context and its device workspace on GPU `device` for gradients of up to max_n
  * elements in up to max_buckets buckets, quantized in chunks of `chunk` survivors (2048 in
- * the benchmark configurations; a positive multiple of 8).  Workspace: about 6.2 bytes per
- * element of max_n (survivor values, candidate staging, a pruning bitmap for the rare bucket
- * that needs one) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
+ * the benchmark configurations; a positive multiple of 8).  Workspace: about 6.3 bytes per
+ * element of max_n (4 for survivor values at ratio 1, 2 for the staging segments, 0.3 for the
+ * lists of undecided keys, the pruning bitmap and the per-tile tables) plus 200 KiB per bucket.  NSML_EHIP if the device or its memory is not
  * available (there is no CPU fallback).
  * A context serialises nothing itself: its calls share the workspace and the cached tables, so
  * they must not overlap, neither from several host threads nor on different streams (use one
@@ -149,7 +149,7 @@ typedef struct nsml_ctx nsml_ctx;
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 /* As nsml_create for callers that never exceed a ratio: the buffer of survivor values is sized
  * for max_ratio in (0, 1] instead of 1 (nsml_create is nsml_create_ex with max_ratio = 1), which
- * brings the workspace to about 2.2 + 4 * max_ratio bytes per element.  A compress call with a
+ * brings the workspace to about 2.3 + 4 * max_ratio bytes per element.  A compress call with a
  * larger ratio returns NSML_ECAP. */
 int nsml_create_ex(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk,
                    double max_ratio);
@@ -162,8 +162,12 @@ int nsml_destroy(nsml_ctx *ctx);
  *   "span_tiles"   tiles of 4096 elements per workgroup of the streaming kernels: 1..16, 0 = by
  *                  gradient size
  *   "seg_waves"    wavefronts per workgroup of the streaming pass (4, 8 or 16), 0 = by span size
+ *   "persist"      workgroups per compute unit of the streaming pass, each taking a contiguous
+ *                  share of the spans: 1..8, 0 (default) = one workgroup per span
+ *   "decomp_variant"  decompress: 1 = one wavefront per tile with direct stores, 0 = tiles assembled
+ *                  in LDS, -1 (default) = by gradient size and survivors per tile
  *   "force_dense"  1: decide every bucket by the dense passes over the accumulator (the path a
- *                  bucket takes when its candidates cannot decide it), 0: default
+ *                  bucket takes when its staged elements cannot decide it), 0: default
  *   "nt"           bit mask of non-temporal hints in the streaming pass (1 grad loads, 2 residual
  *                  loads, 4 accumulator stores); default 7
  *   "nt_dense"     non-temporal stores of the dense output of decompress: 1, 0, -1 = by variant

@@ -20,8 +20,6 @@ constexpr uint32_t NONE = 0xFFFFFFFFu;
 constexpr uint32_t SAMPLE_ALL_BELOW = 262144;  /* buckets smaller than this are sampled in full */
 constexpr uint32_t SAMPLE_STRIDE = 64;         /* larger ones: 32 elements out of every 2048 */
 constexpr uint32_t RUNS_PER_WG = 128;          /* sample runs (32 elements each) per workgroup */
-constexpr uint32_t SIDE_GRID = 2048;           /* workgroups of the kernels that walk work lists */
-constexpr uint32_t AGG_GRID = 1024;            /* workgroups of the candidate refine that aggregates in LDS */
 
 /* Diagnostic: why the plan sent a bucket to the dense passes (bits; 0 when it did not). */
 enum Why : uint32_t { WHY_NO_GUESS = 1, WHY_OVERFLOW = 2, WHY_TOO_FEW = 4, WHY_NO_ROOM = 8, WHY_OUTSIDE_BAND = 16, WHY_NONZEROS = 32 };
@@ -76,11 +74,7 @@ struct Tables {
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */
     uint32_t *nhard;         /* 1   buckets of this call that are not on PATH_CAND (their kernels leave at once when 0) */
     uint32_t *kw;            /* B   parameters the pruning step keeps (only with weights) */
-    const float *w;          /* weights when Algorithm 2 Step 2 is on, else NULL */
-    const uint32_t *wT;      /* B   with weights: threshold key of |w|; NONE: the bucket's mask is in the bitmap */
-    const uint32_t *wcut;    /* B   with weights: among parameters with key(w) == wT, those up to this
-                              *     bucket-local index are kept (kept: key > wT, or key == wT and index <= wcut) */
-    const uint32_t *pmask;   /* pruning bitmap, 128 words per tile, bit = pruned (buckets with wT = NONE) */
+    const uint32_t *pmask;   /* with Algorithm 2 Step 2: the pruning bitmap, 128 words per tile, bit = pruned; else NULL */
     uint32_t B;
     uint32_t n_spans;
     uint32_t spanT;          /* tiles per span */
@@ -97,7 +91,6 @@ struct Cand {
     uint32_t *G;     /* per segment: #(key > T), later its exclusive prefix inside the bucket */
     uint32_t *E;     /* per segment: #(key == T), later its exclusive prefix */
     uint32_t cap;    /* entries per segment: a quarter of the elements it covers */
-    uint32_t splitSh; /* log2 of the wavefronts that share a chunk of 64 segments in the candidate kernels */
 };
 
 typedef float f4 __attribute__((ext_vector_type(4)));   /* one aligned 16-byte access */
@@ -190,25 +183,6 @@ __device__ __forceinline__ uint32_t load_quad(const float *__restrict__ p, uint6
         if (gi + j >= lo && gi + j < hi) { x[j] = p[gi + j]; m |= 1u << j; }
     }
     return m;
-}
-
-/* The four pruning bits (1 = pruned) of the quad at aligned element index gi, which is quad
- * `quad` of tile `tile_abs`, in a bucket [lo, hi) whose weight threshold is wT and whose last
- * kept index among the weights equal to the threshold is cut. */
-__device__ __forceinline__ uint32_t pruned_quad(const Tables &t, uint32_t wT, uint32_t cut, uint32_t tile_abs,
-                                                uint32_t quad, uint64_t gi, uint64_t lo, uint64_t hi)
-{
-    if (wT == 0xFFFFFFFFu) return pruned_bits(t.pmask, tile_abs, quad);
-    float x[4];
-    load_quad(t.w, gi, lo, hi, x);
-    const uint32_t li = (uint32_t)(gi - lo);        /* meaningless below lo: those lanes are masked anyway */
-    uint32_t bits = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t key = __float_as_uint(x[j]) & 0x7FFFFFFFu;
-        bits |= ((key < wT || (key == wT && li + j > cut)) ? 1u : 0u) << j;
-    }
-    return bits;
 }
 
 /* ------------------------------------------------------------------ setup / clear */

@@ -4,41 +4,56 @@
  * One compress call = error-feedback accumulation, exact top-k by magnitude per bucket
  * (Sec. 4.2 Step 3 / Algorithm 2 Step 3), value coding and payload packing; one decompress
  * call = payload -> dense gradient.  Nothing here is a dense contraction: every kernel is a
- * streaming pass bound by HBM bandwidth, so the work is organised around coalesced 16-byte
- * accesses, LDS histograms and 64-lane ballots, not MFMA.
+ * streaming pass bound by HBM bandwidth (or, for the small ones, by launch and dependent-load
+ * latency), so the work is organised around coalesced 16-byte accesses, LDS histograms, 64-lane
+ * ballots and as few dependent launches as possible, not MFMA.
  *
  * Selection is an exact radix select on the 31-bit magnitude key (binary32 pattern with the
  * sign cleared), digits of 12 + 12 + 7 bits, arranged so that the gradient is read ONCE:
  *
  *   sample    level-0 histogram of a 1/64 sample of grad + residual (small buckets: all of it)
- *   predict   per bucket: a level-0 digit whose lower edge L_b is, with a wide margin, below
- *             the k-th largest key
- *   ef_emit   acc = grad + residual (written over residual), exact level-0 histogram, and
- *             every element with key >= L_b appended, in index order, to a per-wavefront
- *             staging segment ("candidates")                                  12 B/element
- *   plan      per bucket: exact level-0 digit b0 of the k-th key; the candidates (exactly
- *             the elements with key >= L_b) decide the bucket iff there are at least k of
- *             them and no staging segment overflowed
- *   refine1/2, pick1/2   remaining digits from the candidates only -> threshold key T_b and
- *             e_b = how many elements equal to T_b are admitted (lowest indices first)
- *   count, scan, write   survivors to their final, index-ordered slots
- *   fallback  buckets whose candidates cannot decide (huge groups of equal keys, ratio near
- *             1, an unlucky sample) take the same steps over the dense accumulator instead,
- *             in the last workgroups of the same launches: four more reads of that bucket
- *             only.  Results are identical.
- *   quant     per chunk of survivors: absmax scale, codes, packing, residual update
- *   tilestart, decomp    payload -> dense, each output line written once, tile staged in LDS
+ *   predict   per bucket, what the streaming pass stages: everything from a key L_b up that lies,
+ *             with a wide margin, below the k-th largest ("candidates", ratios up to an eighth);
+ *             a band [L_b, H_b) of keys around the k-th largest (larger ratios); nothing, when
+ *             the k-th largest is a zero (sparse embeddings, ratio 1)
+ *   ef_emit   acc = grad + residual (written over residual), exact level-0 histogram, a finer
+ *             histogram of the four level-0 digits around the expected threshold, and the staged
+ *             elements appended, in index order, to per-wavefront segments       12 B/element
+ *   plan      per bucket: exact level-0 digit of the k-th key (18 bits of it when the finer
+ *             histogram covers it) and the path: PATH_CAND, PATH_BAND, PATH_ZERO when the staged
+ *             elements and the counts can decide it, else PATH_DENSE
+ *   select_count, select_finish   the staged entries against those bits: counts per segment, the
+ *             few undecided keys set aside, then per bucket (one workgroup of 1024 threads) the
+ *             remaining bits in LDS -> threshold key T_b, e_b = how many elements equal to T_b
+ *             are admitted (lowest indices first), and every segment's place in the survivor order
+ *   encode    PATH_CAND: one workgroup per chunk of survivors gathers them from the segments and
+ *             codes them (absmax scale, codes, packing, indices, coding error into the residual)
+ *   hard      usually one empty launch.  PATH_BAND / PATH_ZERO: survivors taken from the dense
+ *             accumulator and coded in one streaming pass; PATH_DENSE (an unlucky sample, a
+ *             staging segment that overflowed, huge groups of equal keys): all radix steps over
+ *             the dense accumulator, in a small resident grid with barriers between the steps
+ *   quant     codes what hard left uncoded (chunks that straddle its work units; PATH_DENSE)
+ *   tilestart, decomp    payload -> dense, each output line written once
+ * Every path gives the same bytes.
+ *
+ * With weights (Algorithm 2 Step 2) a weight pass comes first: sample of |w| -> band around the
+ * threshold of the kept set (from the second call on: around the threshold the call before
+ * found) -> one pass over w that stages the band, counts what lies above it and writes the
+ * pruning bitmap for everything outside the band -> threshold and ties from the band with the
+ * same select_count / select_finish -> bitmap bits of the band; the gradient kernels then read
+ * one bit per element instead of the weight.
  *
  * Geometry: a bucket [lo, hi) is cut into tiles of 4096 elements starting at lo rounded down
  * to a multiple of 4, so every 16-byte access is aligned; elements of an edge tile outside
  * [lo, hi) are masked.  A workgroup owns a span of up to 16 consecutive tiles of one bucket.
- * Workgroups have 256 threads, except in the streaming pass, which runs one wavefront per
- * tile (512 or 1024 threads) on spans of 8 and 16 tiles.
+ * Workgroups have 256 threads, except in the streaming passes, which run one wavefront per
+ * staging segment (256 to 1024 threads), and in select_finish.
  *
  * One translation unit: the device code lives in nsml_device_common.hpp (tables, geometry,
- * histogram helpers), nsml_select.hpp (sample .. write), nsml_prune.hpp (weight stage) and
- * nsml_codec.hpp (value coding, decompress); this file holds the context, the launch
- * sequences and the C-ABI entry points.
+ * histogram helpers), nsml_select.hpp (sample .. plan, the radix steps over the dense
+ * accumulator), nsml_prune.hpp (weight pass), nsml_codec.hpp (value coding of leftover chunks,
+ * decompress) and nsml_tail.hpp (select_count .. quant, the bitmap kernels); this file holds
+ * the context, the launch sequences and the C-ABI entry points.
  */
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -78,18 +93,17 @@ struct nsml_ctx {
     uint4 *d_selw;         /* per workgroup of k_select_count: bucket, first and last segment */
     uint32_t *d_chunk_b;   /* per chunk of the payload: its bucket (fixed by layout, ratio, bits) */
     uint32_t *d_chunk_seg; /* per chunk: the staging segment that holds its first survivor */
-    uint32_t *d_H, *d_subLo, *d_sh, *d_why, *d_wredo, *d_wnone, *d_wprevT, *d_wprevHw, *d_wnband;
+    uint32_t *d_H, *d_subLo, *d_sh, *d_why, *d_wredo, *d_wprevT, *d_wprevHw, *d_wnband;
     uint32_t *d_lcnt, *d_lkey;   /* k_select_count: lists of undecided keys per workgroup */
     uint64_t max_chunks; uint32_t max_sel;
     uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
-    uint32_t *d_tG, *d_tE; /* per tile (fallback path) */
     uint32_t *d_ccnt, *d_cG, *d_cE, *d_cidx;   /* candidate staging */
     float *d_cval;
     float *d_v;            /* survivor values in final order (not used for bits == 32) */
     uint32_t *d_ts;        /* decompress: where each tile's survivors start */
     uint32_t *d_pmask;     /* pruning bitmap, 128 words per tile */
     uint32_t *d_kw, *d_Tw, *d_needw;              /* pruning stage: kept counts, threshold search state */
-    uint32_t *d_wT, *d_wcut, *d_wfast;            /* pruning stage: threshold key and cut index per bucket; path taken */
+    uint32_t *d_wfast;                            /* pruning stage: how each bucket was decided */
     uint32_t *d_wLo, *d_wHi;                      /* pruning stage: band of keys staged per bucket */
     uint32_t *h_flags;     /* pinned, mapped: [0] consistency flag of the selection, [1] of the pruning stage */
     uint32_t *d_flags;     /* the same two words as the kernels see them */
@@ -191,7 +205,7 @@ Tables tables_of(const nsml_ctx *c)
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
     t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.H = c->d_H; t.fast = c->d_fast; t.subLo = c->d_subLo; t.sh = c->d_sh; t.why = c->d_why;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0; t.nhard = hists_of(c, c->B).nhard;
-    t.kw = c->d_kw; t.w = nullptr; t.wT = nullptr; t.wcut = nullptr; t.pmask = nullptr;
+    t.kw = c->d_kw; t.pmask = nullptr;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk; t.chunkSh = chunk_shift(c->chunk);
     return t;
 }
@@ -201,7 +215,6 @@ Cand cand_of(const nsml_ctx *c)
     Cand k;
     k.idx = c->d_cidx; k.val = c->d_cval; k.cnt = c->d_ccnt; k.G = c->d_cG; k.E = c->d_cE;
     k.cap = (c->spanT * (TILE / 4)) >> c->segSh;
-    k.splitSh = 0;
     return k;
 }
 
@@ -413,12 +426,12 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->prof = false; c->pinned = nullptr; c->pinned_bytes = 0;
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
-    c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = c->d_tG = c->d_tE = nullptr;
-    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = c->d_wredo = c->d_wnone = c->d_wprevT = c->d_wprevHw = c->d_wnband = nullptr;
+    c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = nullptr;
+    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = c->d_wredo = c->d_wprevT = c->d_wprevHw = c->d_wnband = nullptr;
     c->d_lcnt = c->d_lkey = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
-    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wT = c->d_wfast = c->d_wcut = c->d_wLo = c->d_wHi = nullptr;
+    c->d_pmask = c->d_kw = c->d_Tw = c->d_needw = c->d_wfast = c->d_wLo = c->d_wHi = nullptr;
     c->h_flags = c->d_flags = nullptr;
     c->have_prune = false;
     c->max_ratio = max_ratio;
@@ -459,7 +472,6 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_sel0, B1)); A(dev_alloc(c, &c->d_H, B1)); A(dev_alloc(c, &c->d_subLo, B1)); A(dev_alloc(c, &c->d_sh, B1)); A(dev_alloc(c, &c->d_why, B1));
     A(dev_alloc(c, &c->d_span_b, mt));
     A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
-    A(dev_alloc(c, &c->d_tG, mt)); A(dev_alloc(c, &c->d_tE, mt));
     /* segments: at most 4 per tile-sized span, or one per tile plus a partly filled span per bucket */
     const uint64_t msg = 4 * mt + (uint64_t)MAX_SEG_WAVES * B1;
     A(dev_alloc(c, &c->d_ccnt, msg)); A(dev_alloc(c, &c->d_cG, msg)); A(dev_alloc(c, &c->d_cE, msg));
@@ -483,13 +495,12 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_span_sq, mt)); A(dev_alloc(c, &c->d_l2sq, B1));
     A(dev_alloc(c, &c->d_pmask, mt * (TILE / 32)));
     A(dev_alloc(c, &c->d_kw, B1)); A(dev_alloc(c, &c->d_Tw, B1)); A(dev_alloc(c, &c->d_needw, B1));
-    A(dev_alloc(c, &c->d_wT, B1)); A(dev_alloc(c, &c->d_wfast, B1)); A(dev_alloc(c, &c->d_wcut, B1));
+    A(dev_alloc(c, &c->d_wfast, B1));
     A(dev_alloc(c, &c->d_wLo, B1)); A(dev_alloc(c, &c->d_wHi, B1));
-    A(dev_alloc(c, &c->d_wredo, B1)); A(dev_alloc(c, &c->d_wnone, B1));
+    A(dev_alloc(c, &c->d_wredo, B1));
     A(dev_alloc(c, &c->d_wprevT, B1)); A(dev_alloc(c, &c->d_wprevHw, B1)); A(dev_alloc(c, &c->d_wnband, B1));
     if (rc == NSML_OK) {
-        hipError_t e = hipMemset(c->d_wnone, 0xFF, sizeof(uint32_t) * B1);      /* NONE for every bucket */
-        if (e == hipSuccess) e = hipMemset(c->d_wredo, 0, sizeof(uint32_t) * B1);
+        hipError_t e = hipMemset(c->d_wredo, 0, sizeof(uint32_t) * B1);
         if (e == hipSuccess) e = hipMemset(c->d_wprevT, 0xFF, sizeof(uint32_t) * B1);   /* nothing remembered */
         if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
     }
@@ -523,10 +534,10 @@ int nsml_destroy(nsml_ctx *c)
     (void)hipDeviceSynchronize();
     void *ptrs[] = {c->d_off, c->d_P, c->d_V, c->d_S, c->d_C, c->d_tile0, c->d_span0, c->d_samp0,
                     c->d_span_b, c->d_k, c->d_T, c->d_need, c->d_L, c->d_fast, c->d_fspan0,
-                    c->d_zero, c->d_tG, c->d_tE, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
+                    c->d_zero, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
-                    c->d_Tw, c->d_needw, c->d_wT, c->d_wfast, c->d_wcut,
-                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why, c->d_wredo, c->d_wnone, c->d_wprevT, c->d_wprevHw, c->d_wnband};
+                    c->d_Tw, c->d_needw, c->d_wfast,
+                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why, c->d_wredo, c->d_wprevT, c->d_wprevHw, c->d_wnband};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->h_flags) (void)hipHostFree(c->h_flags);
@@ -603,9 +614,6 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         LAUNCH(c, KID_WHARD, st, k_whard, (uint32_t)c->n_cu, weights, tw, cdw, h.f1, h.f2, c->d_pmask, c->d_flags + 1);
         LAUNCH(c, KID_WPLAN, st, k_wremember, (B + WG - 1) / WG, tw, (const uint32_t *)c->d_Tw, (const uint32_t *)c->d_wLo,
                (const uint32_t *)c->d_wHi, (const uint32_t *)c->d_wnband, c->d_wprevT, c->d_wprevHw);
-        t.w = weights;
-        t.wT = c->d_wnone;
-        t.wcut = c->d_wcut;
         t.pmask = c->d_pmask;
     }
 

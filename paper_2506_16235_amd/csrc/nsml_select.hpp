@@ -35,10 +35,9 @@ __global__ __launch_bounds__(WG) void k_sample(const float *__restrict__ g, cons
             float x[4], y[4];
             uint32_t m = load_quad(g, gi, lo, hi, x);
             if (SUM) load_quad(r, gi, lo, hi, y);
-            if (SUM && t.w) {
+            if (SUM && t.pmask) {
                 const uint64_t rel = gi - a0;
-                m &= ~pruned_quad(t, t.wT[b], t.wcut[b], t.tile0[b] + (uint32_t)(rel / TILE),
-                                  (uint32_t)(rel % TILE) / 4, gi, lo, hi);
+                m &= ~pruned_bits(t.pmask, t.tile0[b] + (uint32_t)(rel / TILE), (uint32_t)(rel % TILE) / 4);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -92,7 +91,7 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, uint32_t *__restrict__
     const bool exact = nb < SAMPLE_ALL_BELOW;
     /* the sample was drawn from the parameters that can be selected: all of them, or the
      * ones the pruning step kept */
-    const double pop = t.w ? (double)t.kw[b] : (double)nb;
+    const double pop = t.pmask ? (double)t.kw[b] : (double)nb;
     const double ks = (double)k * (double)m / pop;
     const double dev = exact ? 0.0 : 4.0 * sqrt(ks) + 4.0;
     const double want_d = exact ? (double)k : ceil(ks + dev);
@@ -260,8 +259,6 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     const uint32_t L = EMIT ? t.L[s.b] : NONE;
     const uint32_t H = EMIT ? t.H[s.b] : NONE;           /* NONE: no upper bound */
     uint32_t n_hi = 0, n_lo = 0;                          /* band mode: elements above / below the band */
-    const uint32_t wT = PRUNE ? t.wT[s.b] : 0u;          /* NONE: this bucket's mask is in the bitmap */
-    const uint32_t wcut = PRUNE ? t.wcut[s.b] : 0u;
     const uint32_t ss = (span << t.segSh) + wave;
     const uint64_t cbase = (uint64_t)ss * c.cap;
     uint32_t wcount = 0;
@@ -273,37 +270,30 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     for (uint32_t wt = wt0; wt < wt1; ++wt) {
         const uint64_t wb = s.base + (uint64_t)wt * WTILE;
         if (wb >= s.lo && wb + WTILE <= s.hi) {
-            f4 gv[4], rv[4], wv[4];
+            {
+            constexpr int ROWS = 4, hb2 = 0;         /* rows of 1 KiB in flight per operand */
+            f4 gv[ROWS], rv[ROWS];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
-                gv[u] = (NT & 1) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi))
+            for (int v = 0; v < ROWS; ++v) {
+                const uint64_t gi = wb + (uint64_t)((hb2 + v) * 64 + lane) * 4;
+                gv[v] = (NT & 1) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi))
                                  : *reinterpret_cast<const f4 *>(g + gi);
-                rv[u] = (NT & 2) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r + gi))
+                rv[v] = (NT & 2) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r + gi))
                                  : *reinterpret_cast<const f4 *>(r + gi);
-                if (PRUNE && wT != NONE) wv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(t.w + gi));
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int v = 0; v < ROWS; ++v) {
+                const int u = hb2 + v;
                 const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
                 float a[4];
-                a[0] = __fadd_rn(gv[u].x, rv[u].x); a[1] = __fadd_rn(gv[u].y, rv[u].y);
-                a[2] = __fadd_rn(gv[u].z, rv[u].z); a[3] = __fadd_rn(gv[u].w, rv[u].w);
-                sq += (double)(__fmaf_rn(gv[u].x, gv[u].x, __fmul_rn(gv[u].y, gv[u].y)) +
-                               __fmaf_rn(gv[u].z, gv[u].z, __fmul_rn(gv[u].w, gv[u].w)));
+                a[0] = __fadd_rn(gv[v].x, rv[v].x); a[1] = __fadd_rn(gv[v].y, rv[v].y);
+                a[2] = __fadd_rn(gv[v].z, rv[v].z); a[3] = __fadd_rn(gv[v].w, rv[v].w);
+                sq += (double)(__fmaf_rn(gv[v].x, gv[v].x, __fmul_rn(gv[v].y, gv[v].y)) +
+                               __fmaf_rn(gv[v].z, gv[v].z, __fmul_rn(gv[v].w, gv[v].w)));
                 uint32_t cm = 0xFu;
-                if (PRUNE) {
-                    if (wT != NONE) {
-                        const uint32_t li = (uint32_t)(gi - s.lo);
-                        const uint32_t kx = keyof(wv[u].x), ky = keyof(wv[u].y), kz = keyof(wv[u].z), kq = keyof(wv[u].w);
-                        cm = ((kx > wT || (kx == wT && li <= wcut)) ? 1u : 0u) |
-                             ((ky > wT || (ky == wT && li + 1 <= wcut)) ? 2u : 0u) |
-                             ((kz > wT || (kz == wT && li + 2 <= wcut)) ? 4u : 0u) |
-                             ((kq > wT || (kq == wT && li + 3 <= wcut)) ? 8u : 0u);
-                    } else
-                        cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
-                }
+                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
                 ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, hb, subLo, L, H, c, cbase, wcount, n_hi, n_lo);
+            }
             }
         } else {
 #pragma unroll
@@ -315,7 +305,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
 #pragma unroll
                 for (int j = 0; j < 4; ++j) { a[j] = __fadd_rn(x[j], y[j]); sq += (double)__fmul_rn(x[j], x[j]); }
                 uint32_t cm = m;
-                if (PRUNE) cm &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
                 ef_row<false, EMIT, NT, PRUNE>(r, gi, a, m, cm, (uint32_t)(gi - s.lo), h, hb, subLo, L, H, c, cbase, wcount, n_hi, n_lo);
             }
         }
@@ -606,7 +596,7 @@ __device__ __forceinline__ void fb_refine_body(const float *__restrict__ r, cons
                 const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
                 float x[4];
                 uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-                if (t.w) m &= ~pruned_quad(t, t.wT[b], t.wcut[b], s.tile_g + ti, u * WG + tid, gi, s.lo, s.hi);
+                if (t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + ti, u * WG + tid);
                 uint32_t d[4];
                 uint32_t hit = 0;
 #pragma unroll

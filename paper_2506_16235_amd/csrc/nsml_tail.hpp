@@ -859,7 +859,6 @@ __device__ __forceinline__ void write_dense_body(float *__restrict__ r, const Ta
     const SpanGeo s = span_geo_b(t, b, span - t.span0[b]);
     const uint32_t T = t.T[b], e_b = t.need[b];
     const uint64_t Pb = t.P[b];
-    const uint32_t wT = t.w ? t.wT[b] : 0u, wcut = t.w ? t.wcut[b] : 0u;
     uint32_t run_g = c.G[ss], run_e = c.E[ss];
     const uint64_t lt = (1ull << lane) - 1ull;
     const uint32_t per = (t.spanT * 4u) >> t.segSh;
@@ -873,7 +872,7 @@ __device__ __forceinline__ void write_dense_body(float *__restrict__ r, const Ta
         for (int u = 0; u < 4; ++u) {
             const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
             mn[u] = load_quad(r, gi, s.lo, s.hi, xn[u]);
-            if (t.w) mn[u] &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+            if (t.pmask) mn[u] &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
         }
     };
     if (wt0 < wt1) fetch(wt0);
@@ -937,7 +936,6 @@ __device__ __forceinline__ void segcount_dense_body(const float *__restrict__ r,
     if (t.fast[b] != PATH_DENSE || t.k[b] == 0u) continue;
     const SpanGeo s = span_geo_b(t, b, span - t.span0[b]);
     const uint32_t T = t.T[b];
-    const uint32_t wT = t.w ? t.wT[b] : 0u, wcut = t.w ? t.wcut[b] : 0u;
     const uint32_t per = (t.spanT * 4u) >> t.segSh;
     const uint32_t wt0 = wslot * per, wt1 = min(s.ntiles * 4u, wt0 + per);
     uint32_t ng = 0, ne = 0;
@@ -948,7 +946,7 @@ __device__ __forceinline__ void segcount_dense_body(const float *__restrict__ r,
             const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
             float x[4];
             uint32_t m = load_quad(r, gi, s.lo, s.hi, x);
-            if (t.w) m &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+            if (t.pmask) m &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t key = keyof(x[j]);
@@ -1062,8 +1060,7 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
             }
             else if (tid == 0 && (run_g != c.G[span << t.segSh] || run_e != c.E[span << t.segSh]))
                 err[0] = 1u;                         /* the prefixes and the elements disagree */
-            const uint32_t wT = t.w ? t.wT[b] : 0u, wcut = t.w ? t.wcut[b] : 0u;
-            const uint32_t nwt = s.ntiles * 4u;
+                    const uint32_t nwt = s.ntiles * 4u;
             /* the next 4096 elements are fetched while the survivors of these are coded */
             float xn[4][4];
             uint32_t mn[4];
@@ -1078,7 +1075,7 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
                     for (int j = 0; j < 4; ++j) xn[u][j] = 0.0f;
                     if (wt < nwt) {
                         mn[u] = load_quad(r, gi, s.lo, s.hi, xn[u]);
-                        if (t.w) mn[u] &= ~pruned_quad(t, wT, wcut, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane, gi, s.lo, s.hi);
+                        if (t.pmask) mn[u] &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
                     }
                 }
             };
