@@ -9,7 +9,7 @@ namespace {
 
 /* ------------------------------------------------------------------ value coding */
 
-/* The same coding for chunks of at most 256 survivors, one wavefront per chunk and QUANT_PER_WAVE
+/* The coding of quant_body (below) for chunks of at most 256 survivors, one wavefront per chunk and QUANT_PER_WAVE
  * chunks per wavefront, all of whose values and indices are fetched before any is used (with a
  * workgroup per small chunk the step is bound by the latency of its chain of dependent loads,
  * not by bandwidth).  A lane takes up to two pairs of consecutive survivors of each chunk. */

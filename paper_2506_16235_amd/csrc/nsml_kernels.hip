@@ -654,7 +654,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         {
             const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
             const uint64_t nc64e = c->NC;
-            const uint32_t cpw = c->NC > (1ull << 18) ? 16u : 1u;     /* very many chunks: fewer, longer-lived workgroups */
+            const uint32_t cpw = c->NC > (1ull << 14) ? 16u : 1u;     /* very many chunks: fewer, longer-lived workgroups */
             const uint32_t egrid2 = (uint32_t)((c->NC + cpw - 1) / cpw);
             switch (bits) {
             case 32: LAUNCH(c, KID_ENCODE, st, k_encode<32>, egrid2, t, cd0, cb_, cs_, residual, idx, val, scales, c->d_flags, nc64e, cpw); break;
@@ -670,17 +670,21 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
      * the buckets on the dense passes with barriers between; then the value coding of what those
      * left uncoded */
     {
-        const uint32_t hgrid = (uint32_t)(HARD_WG_PER_CU * c->n_cu), team = (uint32_t)c->n_cu;
+        const bool big = c->chunk > DENC_SMALL_CHUNK;
+        const uint32_t hgrid = (uint32_t)(hard_wg_per_cu(big) * c->n_cu), team = hgrid;
         const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
-        const int stream_coding = (bits != 32 && c->chunk <= DENC_MAX_CHUNK) ? 1 : 0;
+        const int stream_coding = c->chunk <= DENC_MAX_CHUNK ? 1 : 0;
+#define NSML_HARD(BITS_, BIG_) LAUNCH(c, KID_HARD, st, (k_hard<BITS_, BIG_>), hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team)
         switch (bits) {
-        case 32: LAUNCH(c, KID_HARD, st, k_hard<32>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
-        case 16: LAUNCH(c, KID_HARD, st, k_hard<16>, hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
-        case 8:  LAUNCH(c, KID_HARD, st, k_hard<8>,  hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
-        default: LAUNCH(c, KID_HARD, st, k_hard<4>,  hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team); break;
+        case 32: NSML_HARD(32, false); break;
+        case 16: if (big) NSML_HARD(16, true); else NSML_HARD(16, false); break;
+        case 8:  if (big) NSML_HARD(8, true); else NSML_HARD(8, false); break;
+        default: if (big) NSML_HARD(4, true); else NSML_HARD(4, false); break;
         }
+#undef NSML_HARD
         const uint32_t per_wg = (WG / 64) * QUANT_PER_WAVE;
-        const uint32_t ngrid = c->chunk <= QUANT_WAVE_CHUNK ? (qgrid + per_wg - 1) / per_wg : qgrid;
+        const uint32_t ngrid = c->chunk <= QUANT_WAVE_CHUNK ? (qgrid + per_wg - 1) / per_wg
+                                                            : (qgrid + QUANT_BIG_PER_WG - 1) / QUANT_BIG_PER_WG;
         const uint64_t nc64 = c->NC;
         switch (bits) {
         case 32: break;        /* the ordered write left values and residual in their final state */

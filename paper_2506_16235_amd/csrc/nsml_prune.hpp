@@ -12,15 +12,17 @@ namespace {
 /* Algorithm 2 Step 2 on the GPU: the kept parameters of a bucket are its n_b - floor(0.5 (1 -
  * ratio) n_b) largest |weight| (ties: lower index kept).  The kept set is more than half of
  * the bucket, so "candidates above a bound" would be most of it; instead the threshold is
- * bracketed: a sample of |w| gives a band of level-0 digits that holds the kw-th largest key
- * with a wide margin, one pass over the weights builds the exact level-0 histogram and stages
- * the elements inside the band, and the remaining digits, the threshold key T and the index
- * of the last kept element among those equal to T come from the staged elements alone.  The
- * gradient kernels then decide "kept" from the weight itself as they stream it (key > T, or
- * key == T and index <= cut).  A bucket whose band missed or overflowed (a sample that was
- * unlucky, a huge group of equal weights) takes the dense ordered passes instead, which leave
- * a bitmap (1 = pruned).  Either way pruned parameters are neither counted nor emitted, and
- * their accumulated gradient is still written to the residual: pruning is not permanent. */
+ * bracketed by a band of keys [lo, hi) that holds the kw-th largest key: from a sample of |w|
+ * with a wide margin, or, from the second call on, a narrow one around the threshold the call
+ * before found (weights move little between steps).  One pass over the weights stages the
+ * elements inside the band, counts those above it and writes the pruning bitmap (1 = pruned)
+ * for everything outside it; the threshold key T and the number e of admitted elements equal to
+ * T come from the staged elements alone (k_select_count / k_select_finish), and k_wfix sets the
+ * bits of the band elements that turn out pruned.  A bucket whose band missed or overflowed
+ * repeats the pass with an exact histogram and takes the dense ordered passes (k_whard), which
+ * write its bitmap.  The gradient kernels read one bit per parameter.  Pruned parameters are
+ * neither counted nor emitted, and their accumulated gradient is still written to the residual:
+ * pruning is not permanent. */
 
 /* Per bucket: the band of keys [lo, hi) to stage, from the sample histogram of |w|. */
 __global__ __launch_bounds__(WG) void k_wpredict(Tables t, const uint32_t *__restrict__ hist_s,

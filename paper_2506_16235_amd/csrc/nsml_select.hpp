@@ -1,6 +1,6 @@
 /*
- * libnsml device code, part 2: the selection path: sample, candidate bound, the streaming pass, the candidate
- * and dense-fallback stages of the radix select.
+ * libnsml device code, part 2: the head of the selection: sample, what to stage, the streaming
+ * pass, the plan, and the radix steps over the dense accumulator that the fallback uses.
  * Included by nsml_kernels.hip (one translation unit); not a public header.
  */
 #ifndef NSML_SELECT_HPP
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
  * every element of that digit: in candidate mode they are exactly the elements with key >= L_b,
  * so they do iff there are at least k of them; in band mode iff the digit lies inside the band;
  * in both only if no staging segment overflowed and the undecided keys of the digit are few
- * enough to fit the free part of the staging area (k_select parks them there).  In zero mode
+ * enough to fit the free part of the staging area (k_select_count parks them there).  In zero mode
  * the counts settle everything: fewer non-zero elements than k means threshold key 0. */
 __global__ __launch_bounds__(WG) void k_plan(Tables t, uint32_t *__restrict__ hist0, uint32_t *__restrict__ hist0b,
                                              Cand c, int have_cand,
@@ -492,7 +492,7 @@ __device__ __forceinline__ void pick_body(const Tables &t, const uint32_t *__res
     constexpr int BITS = LEVEL == 2 ? 7 : 12;
     __shared__ uint32_t tmp[WG];
     const uint32_t tid = threadIdx.x;
-    if (only_fb && t.fast[b]) return;          /* decided by k_select */
+    if (only_fb && t.fast[b]) return;          /* decided from its staged elements */
     const uint32_t want = t.need[b];
     if (want == 0) {
         /* empty bucket */

@@ -3,26 +3,30 @@
  * Included by nsml_kernels.hip (one translation unit); not a public header.
  *
  * What the tail knows when it starts (left by the streaming pass and the plan): for every
- * bucket the level-0 digit b0 of its k-th largest key and how many of the keys inside that
- * digit are still wanted; for every staging segment its entries (index, value) in index order.
- * Entries above digit b0 are survivors, entries below it are not, the ones inside it are the
- * only undecided ones, and they are few (one digit spans 1/16 of an octave).
+ * bucket the leading bits b0 of its k-th largest key (the level-0 digit, or 18 bits when the
+ * finer histogram covered it) and how many of the keys that share them are still wanted; for
+ * every staging segment its entries (index, value) in index order.  Entries above b0 are
+ * survivors, entries below it are not, the ones that share it are the only undecided ones, and
+ * they are few.
  *
- *   k_select_count   per segment: entries above digit b0, and the keys of the entries inside it
- *                    copied into the unused tail of the segment's own staging area
- *   k_select_finish  per bucket, one workgroup: threshold key T and tie allowance e from those
- *                    few keys (12 + 7 remaining bits, histograms in LDS); per segment the number
- *                    of survivors and of threshold ties that precede it in the bucket; per chunk
- *                    of the payload the segment that holds its first survivor
- *   k_encode         per chunk of `chunk` consecutive survivors: gathers them in index order
- *                    from the staged entries into LDS, then scale, codes, packing, indices and
- *                    the residual update, all from LDS
- *   k_write_dense    buckets whose survivors are too many to stage (a band of keys around the
- *                    threshold was staged instead, or the threshold is key 0): the survivors
- *                    are taken from the dense accumulator, one wavefront per segment; the value
- *                    coding of those buckets is k_quant's
- * Every kernel here is a handful of dependent memory round trips long, which is what a small
- * kernel costs on this GPU; tables that a kernel would otherwise search for (workgroup ->
+ *   k_select_count   per segment: entries above b0; the keys of the undecided entries go to a list
+ *                    per workgroup (read back with coalesced loads) and, as a fallback, into the
+ *                    unused tail of the segment's own staging area
+ *   k_select_finish  per bucket, one workgroup of 1024 threads: threshold key T and tie allowance
+ *                    e from those few keys (the remaining bits, histograms in LDS); per segment
+ *                    the number of survivors and of threshold ties that precede it in the bucket;
+ *                    per chunk of the payload the segment that holds its first survivor
+ *   k_encode         PATH_CAND, per chunk of `chunk` consecutive survivors: gathers them in index
+ *                    order from the staged entries into LDS, then scale, codes, packing, indices
+ *                    and the residual update, all from LDS
+ *   k_hard           PATH_BAND / PATH_ZERO (survivors too many to stage: a band of keys around
+ *                    the threshold was staged instead, or the threshold is key 0): survivors
+ *                    taken from the dense accumulator and coded in one streaming pass;
+ *                    PATH_DENSE: every radix step over the dense accumulator, barriers between
+ *   k_quant          codes the chunks k_hard wrote uncoded
+ *   k_wfix, k_whard  the same machinery for the pruning bitmap of the weight stage
+ * Every small kernel here is a handful of dependent memory round trips long, which is what a
+ * small kernel costs on this GPU; tables that a kernel would otherwise search for (workgroup ->
  * segments, chunk -> bucket, chunk -> first segment) are therefore prepared by the kernel before.
  */
 #ifndef NSML_TAIL_HPP
@@ -30,7 +34,7 @@
 
 namespace {
 
-constexpr uint32_t SEL_THREADS = 1024;     /* k_select workgroup: 16 wavefronts */
+constexpr uint32_t SEL_THREADS = 1024;     /* k_select_finish workgroup: 16 wavefronts */
 constexpr uint32_t SEL_WAVES = SEL_THREADS / 64;
 constexpr uint32_t SEL_SEGS_PER_WAVE = 4;
 constexpr uint32_t ENC_BLK = WG * 8;       /* survivors gathered in LDS at a time */
@@ -1006,17 +1010,18 @@ __device__ __forceinline__ void grid_barrier(uint32_t *bar, uint32_t target, uin
  * those afterwards (same test, see chunk_coded_by_stream).  16-bit values need no chunk and are
  * all coded here. */
 constexpr uint32_t DENC_SPANS = 4;
-constexpr uint32_t DENC_MAX_CHUNK = 256;
-constexpr uint32_t DENC_CAP = TILE + DENC_MAX_CHUNK;
+constexpr uint32_t DENC_SMALL_CHUNK = 256;         /* up to here a wavefront codes a chunk */
+constexpr uint32_t DENC_MAX_CHUNK = 2048;
+constexpr uint32_t denc_cap(bool big) { return TILE + (big ? DENC_MAX_CHUNK : DENC_SMALL_CHUNK); }
 
-template <int BITS>
+template <int BITS, bool BIG>       /* BIG: chunks of more than DENC_SMALL_CHUNK survivors */
 __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const Tables &t, const Cand &c,
                                                   uint32_t *__restrict__ idx_out, float *__restrict__ v_out,
                                                   void *__restrict__ val, float *__restrict__ scales,
                                                   float *sv, uint32_t *si, uint32_t *wtot, uint32_t *__restrict__ err,
                                                   uint32_t bid, uint32_t nblk)
 {
-    constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;
+    constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;     /* (unused for 16 / 32 bits) */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t chunk = t.chunk;
     const uint32_t n_units = (t.n_spans + DENC_SPANS - 1) / DENC_SPANS;
@@ -1142,14 +1147,20 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
                 /* consume what is complete */
                 const uint32_t total = carry + nsurv;
                 uint32_t p = 0;
-                if (BITS == 16) {
+                if (BITS >= 16) {
+                    /* no scale to wait for: every survivor is final at once */
                     for (uint32_t i = tid; i < total; i += WG) {
                         const float xv = sv[i];
                         const uint32_t li = si[i];
-                        const __half hv = __float2half_rn(xv);
-                        reinterpret_cast<__half *>(vb)[Rbase + i] = hv;
                         idx_out[Pb + Rbase + i] = li;
-                        r[lo + li] = __fsub_rn(xv, __half2float(hv));
+                        if (BITS == 16) {
+                            const __half hv = __float2half_rn(xv);
+                            reinterpret_cast<__half *>(vb)[Rbase + i] = hv;
+                            r[lo + li] = __fsub_rn(xv, __half2float(hv));
+                        } else {
+                            reinterpret_cast<float *>(vb)[Rbase + i] = xv;
+                            r[lo + li] = 0.0f;       /* value - value: nothing is left behind */
+                        }
                     }
                     p = total;
                 } else {
@@ -1168,48 +1179,78 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
                         const uint32_t avail = total - p;
                         const uint32_t nfull = avail / chunk, rem = avail - nfull * chunk;
                         const uint32_t ncode = nfull + ((rem != 0u && Rbase + total == kb) ? 1u : 0u);   /* the bucket's last chunk may be short */
-                        for (uint32_t q = wave; q < ncode; q += WG / 64) {
-                            const uint32_t base = p + q * chunk;
-                            const uint32_t cnt = min(chunk, total - base);
-                            const uint32_t rank0 = Rbase + base;
-                            float xv[2][2];
-                            uint32_t li[2][2];
+                        /* one pair of consecutive survivors of a chunk: codes, index, coding error */
+                        auto code_pair = [&](uint32_t rank0, uint32_t i0, uint32_t cnt, float scale, const float (&xv)[2],
+                                             const uint32_t (&li)[2]) {
+                            const int have = (i0 + 1 < cnt) ? 2 : 1;
+                            int qq[2] = {0, 0};
+                            float res[2] = {0.0f, 0.0f};
 #pragma unroll
-                            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                                for (int hh = 0; hh < 2; ++hh) {
-                                    const uint32_t i = 2 * (lane + u * 64) + hh;
-                                    xv[u][hh] = i < cnt ? sv[base + i] : 0.0f;
-                                    li[u][hh] = i < cnt ? si[base + i] : 0u;
+                            for (int hh = 0; hh < 2; ++hh) {
+                                if (hh >= have) continue;
+                                if (scale != 0.0f) {
+                                    float tq = rintf(__fdiv_rn(xv[hh], scale));
+                                    tq = fminf(fmaxf(tq, -QMAX), QMAX);
+                                    qq[hh] = (int)tq;
                                 }
-                            float mx = fmaxf(fmaxf(fabsf(xv[0][0]), fabsf(xv[0][1])), fmaxf(fabsf(xv[1][0]), fabsf(xv[1][1])));
+                                res[hh] = __fsub_rn(xv[hh], __fmul_rn((float)qq[hh], scale));
+                                if (BITS == 8) reinterpret_cast<int8_t *>(vb)[rank0 + i0 + hh] = (int8_t)qq[hh];
+                                idx_out[Pb + rank0 + i0 + hh] = li[hh];
+                            }
+                            if (BITS == 4) vb[(rank0 + i0) >> 1] = (uint8_t)((qq[0] & 0xF) | ((qq[1] & 0xF) << 4));
 #pragma unroll
-                            for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
-                            const float scale = mx == 0.0f ? 0.0f : __fdiv_rn(mx, QMAX);
-                            if (lane == 0) scales[Sb + rank0 / chunk] = scale;
+                            for (int hh = 0; hh < 2; ++hh)
+                                if (hh < have) r[lo + li[hh]] = res[hh];
+                        };
+                        if (!BIG) {
+                            /* chunks of up to 256: a wavefront each, two pairs per lane */
+                            for (uint32_t q = wave; q < ncode; q += WG / 64) {
+                                const uint32_t base = p + q * chunk;
+                                const uint32_t cnt = min(chunk, total - base);
+                                const uint32_t rank0 = Rbase + base;
+                                float xv[2][2];
+                                uint32_t li[2][2];
 #pragma unroll
-                            for (int u = 0; u < 2; ++u) {
-                                const uint32_t i0 = 2 * (lane + u * 64);
-                                if (i0 >= cnt) continue;
-                                const int have = (i0 + 1 < cnt) ? 2 : 1;
-                                int qq[2] = {0, 0};
-                                float res[2] = {0.0f, 0.0f};
+                                for (int u = 0; u < 2; ++u)
 #pragma unroll
-                                for (int hh = 0; hh < 2; ++hh) {
-                                    if (hh >= have) continue;
-                                    if (scale != 0.0f) {
-                                        float tq = rintf(__fdiv_rn(xv[u][hh], scale));
-                                        tq = fminf(fmaxf(tq, -QMAX), QMAX);
-                                        qq[hh] = (int)tq;
+                                    for (int hh = 0; hh < 2; ++hh) {
+                                        const uint32_t i = 2 * (lane + u * 64) + hh;
+                                        xv[u][hh] = i < cnt ? sv[base + i] : 0.0f;
+                                        li[u][hh] = i < cnt ? si[base + i] : 0u;
                                     }
-                                    res[hh] = __fsub_rn(xv[u][hh], __fmul_rn((float)qq[hh], scale));
-                                    if (BITS == 8) reinterpret_cast<int8_t *>(vb)[rank0 + i0 + hh] = (int8_t)qq[hh];
-                                    idx_out[Pb + rank0 + i0 + hh] = li[u][hh];
-                                }
-                                if (BITS == 4) vb[(rank0 + i0) >> 1] = (uint8_t)((qq[0] & 0xF) | ((qq[1] & 0xF) << 4));
+                                float mx = fmaxf(fmaxf(fabsf(xv[0][0]), fabsf(xv[0][1])), fmaxf(fabsf(xv[1][0]), fabsf(xv[1][1])));
 #pragma unroll
-                                for (int hh = 0; hh < 2; ++hh)
-                                    if (hh < have) r[lo + li[u][hh]] = res[hh];
+                                for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+                                const float scale = mx == 0.0f ? 0.0f : __fdiv_rn(mx, QMAX);
+                                if (lane == 0) scales[Sb + rank0 / chunk] = scale;
+#pragma unroll
+                                for (int u = 0; u < 2; ++u) {
+                                    const uint32_t i0 = 2 * (lane + u * 64);
+                                    if (i0 < cnt) code_pair(rank0, i0, cnt, scale, xv[u], li[u]);
+                                }
+                            }
+                        } else {
+                            /* longer chunks: the whole workgroup on one chunk after the other */
+                            for (uint32_t q = 0; q < ncode; ++q) {
+                                const uint32_t base = p + q * chunk;
+                                const uint32_t cnt = min(chunk, total - base);
+                                const uint32_t rank0 = Rbase + base;
+                                float mx = 0.0f;
+                                for (uint32_t i = tid; i < cnt; i += WG) mx = fmaxf(mx, fabsf(sv[base + i]));
+#pragma unroll
+                                for (int d = 32; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+                                float *red = reinterpret_cast<float *>(wtot);
+                                if (lane == 0) red[wave] = mx;
+                                __syncthreads();
+                                mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+                                const float scale = mx == 0.0f ? 0.0f : __fdiv_rn(mx, QMAX);
+                                if (tid == 0) scales[Sb + rank0 / chunk] = scale;
+                                for (uint32_t i0 = 2 * tid; i0 < cnt; i0 += 2 * WG) {
+                                    const float xv[2] = {sv[base + i0], i0 + 1 < cnt ? sv[base + i0 + 1] : 0.0f};
+                                    const uint32_t li[2] = {si[base + i0], i0 + 1 < cnt ? si[base + i0 + 1] : 0u};
+                                    code_pair(rank0, i0, cnt, scale, xv, li);
+                                }
+                                __syncthreads();
                             }
                         }
                         p += min(avail, ncode * chunk);
@@ -1218,11 +1259,21 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
                 __syncthreads();
                 /* the rest waits at the front for the next elements */
                 const uint32_t left = total - p;
-                float keep_v = 0.0f;
-                uint32_t keep_i = 0;
-                if (tid < left) { keep_v = sv[p + tid]; keep_i = si[p + tid]; }
+                constexpr uint32_t KEEP = (BIG ? DENC_MAX_CHUNK : DENC_SMALL_CHUNK) / WG;
+                float keep_v[KEEP];
+                uint32_t keep_i[KEEP];
+#pragma unroll
+                for (uint32_t u = 0; u < KEEP; ++u) {
+                    const uint32_t i = tid + u * WG;
+                    keep_v[u] = 0.0f; keep_i[u] = 0u;
+                    if (i < left) { keep_v[u] = sv[p + i]; keep_i[u] = si[p + i]; }
+                }
                 __syncthreads();
-                if (tid < left) { sv[tid] = keep_v; si[tid] = keep_i; }
+#pragma unroll
+                for (uint32_t u = 0; u < KEEP; ++u) {
+                    const uint32_t i = tid + u * WG;
+                    if (i < left) { sv[i] = keep_v[u]; si[i] = keep_i[u]; }
+                }
                 Rbase += p;
                 carry = left;
             }
@@ -1248,28 +1299,30 @@ __device__ __forceinline__ bool chunk_coded_by_stream(const Tables &t, const Can
     return end <= r1;
 }
 
-constexpr uint32_t HARD_WG_PER_CU = 4;      /* workgroups of k_hard per compute unit (its LDS allows no more) */
-constexpr uint32_t HARD_LDS = 2 * DENC_CAP + 2 * (WG / 64);    /* words; also holds the level-1 histogram */
+/* workgroups of k_hard per compute unit: what its LDS allows (all of them must be resident) */
+constexpr uint32_t hard_wg_per_cu(bool big) { return big ? 3u : 4u; }
+constexpr uint32_t hard_lds(bool big) { return 2 * denc_cap(big) + 2 * (WG / 64); }    /* words; also holds the level-1 histogram */
 
-template <int BITS>
-__global__ __launch_bounds__(WG, HARD_WG_PER_CU) void k_hard(float *__restrict__ r, Tables t, Cand c, uint32_t *__restrict__ f1,
+template <int BITS, bool BIG>
+__global__ __launch_bounds__(WG, hard_wg_per_cu(BIG)) void k_hard(float *__restrict__ r, Tables t, Cand c, uint32_t *__restrict__ f1,
                                              uint32_t *__restrict__ f2, uint32_t *__restrict__ idx,
                                              float *__restrict__ vdst, void *__restrict__ val,
                                              float *__restrict__ scales, uint32_t *__restrict__ err, int stream_coding, uint32_t team)
 {
-    static_assert(HARD_LDS >= NB1, "the pool must hold the level-1 histogram");
-    __shared__ uint32_t pool[HARD_LDS];
+    static_assert(hard_lds(BIG) >= NB1, "the pool must hold the level-1 histogram");
+    __shared__ uint32_t pool[hard_lds(BIG)];
     if (t.nhard[0] == 0u) return;                    /* every bucket was decided and coded from its staged elements */
     const uint32_t bid = blockIdx.x;
     uint32_t nblk = gridDim.x;
     /* band and zero-threshold buckets: survivors from the dense accumulator, threshold known */
-    if (BITS != 32 && stream_coding)
-        dense_encode_body<(BITS == 32 ? 16 : BITS)>(r, t, c, idx, vdst, val, scales, reinterpret_cast<float *>(pool),
-                                                     pool + DENC_CAP, pool + 2 * DENC_CAP, err, bid, nblk);
+    if (stream_coding)
+        dense_encode_body<BITS, BIG>(r, t, c, idx, vdst, val, scales, reinterpret_cast<float *>(pool),
+                                     pool + denc_cap(BIG), pool + 2 * denc_cap(BIG), err, bid, nblk);
     else
         write_dense_body<BITS == 32>(r, t, c, idx, vdst, (1u << PATH_BAND) | (1u << PATH_ZERO), bid, nblk);
-    /* the dense passes: the first `team` workgroups only (they are dispatched first and fit the
-     * device together whatever the others do, so their barriers cannot starve) */
+    /* the dense passes: the first `team` workgroups (all of them: the grid is sized to fit the
+     * device at once, hard_wg_per_cu workgroups per compute unit by registers and LDS, so every
+     * one of them is resident by the time the others wait for it) */
     if (t.nhard[2] == 0u || bid >= team) return;
     __syncthreads();
     nblk = team;
@@ -1299,6 +1352,7 @@ __global__ __launch_bounds__(WG, HARD_WG_PER_CU) void k_hard(float *__restrict__
  * bucket was coded from its staged elements.  Chunks of up to 256 survivors: a wavefront per
  * chunk, QUANT_PER_WAVE chunks per wavefront; longer chunks: a workgroup each. */
 constexpr uint32_t QUANT_WAVE_CHUNK = 256;
+constexpr uint32_t QUANT_BIG_PER_WG = 8;
 template <int BITS>
 __global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const uint32_t *__restrict__ idx, Tables t,
                                               Cand c, float *__restrict__ r, void *__restrict__ val,
@@ -1329,7 +1383,31 @@ __global__ __launch_bounds__(WG) void k_quant(const float *__restrict__ v, const
         const uint32_t mine = (todo_sh >> (wave * QUANT_PER_WAVE)) & ((1u << QUANT_PER_WAVE) - 1u);
         if (mine) quant_wave<BITS>(v, idx, t, r, val, scales, chunk_b, cw + wave * QUANT_PER_WAVE, mine);
     } else {
-        quant_body<BITS>(v, idx, t, r, val, scales, chunk_b, blockIdx.x);
+        /* longer chunks: QUANT_BIG_PER_WG chunks per workgroup, one after the other; which of them
+         * are still to be coded is found by one lane per chunk first */
+        __shared__ uint32_t todo_big;
+        const uint64_t cw = (uint64_t)blockIdx.x * QUANT_BIG_PER_WG;
+        if (threadIdx.x < 64) {
+            const uint64_t cid = cw + threadIdx.x;
+            bool todo = false;
+            if (threadIdx.x < QUANT_BIG_PER_WG && cid < n_chunks) {
+                const uint32_t b = chunk_b[cid];
+                const uint32_t path = t.fast[b];
+                todo = path != PATH_CAND;
+                if (todo && stream_coding && path != PATH_DENSE)
+                    todo = BITS <= 8 && !chunk_coded_by_stream(t, c, b, cid - t.C[b], chunk_seg[cid]);
+            }
+            const uint64_t bal = __ballot(todo);
+            if (threadIdx.x == 0) todo_big = (uint32_t)bal;
+        }
+        __syncthreads();
+        uint32_t mask = todo_big;
+        while (mask) {
+            const uint32_t q = (uint32_t)__builtin_ctz(mask);
+            mask &= mask - 1u;
+            __syncthreads();                         /* the previous chunk's use of LDS is over */
+            quant_body<BITS>(v, idx, t, r, val, scales, chunk_b, cw + q);
+        }
     }
 }
 

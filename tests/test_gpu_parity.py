@@ -52,11 +52,12 @@ def test_ragged_unaligned_buckets(bits):
         c.step(ratio, bits)
 
 
-@pytest.mark.parametrize("chunk", [8, 64, 256, 264])
+@pytest.mark.parametrize("chunk", [8, 64, 256, 264, 2048, 4096])
 @pytest.mark.parametrize("bits", [4, 8, 16])
-def test_high_ratios_with_small_chunks(bits, chunk):
+def test_high_ratios_and_chunk_lengths(bits, chunk):
     """Ratios from an eighth up: the survivors are written and coded from the dense accumulator
-    in one pass when a chunk has at most 256 of them (264: the two-pass variant).  Buckets from a
+    in one pass: a wavefront per chunk of up to 256 survivors, the workgroup per chunk of up to
+    2048; longer chunks (4096) take the ordered write and a coding pass of their own.  Buckets from a
     few elements to many spans, unaligned starts, an empty one; the third step runs on the
     residual of the first two, the last one on a gradient with 70 % exact zeros."""
     sizes = [5, 70_000, 0, 1_000_003, 257, 4096, 300_001, 9, 2_500_000]
