@@ -1009,7 +1009,7 @@ __device__ __forceinline__ void grid_barrier(uint32_t *bar, uint32_t target, uin
  * bucket's spans of another unit) is written uncoded to idx / v_out, and k_quant codes exactly
  * those afterwards (same test, see chunk_coded_by_stream).  16-bit values need no chunk and are
  * all coded here. */
-constexpr uint32_t DENC_SPANS = 4;
+constexpr uint32_t DENC_SPANS = 2;
 constexpr uint32_t DENC_SMALL_CHUNK = 256;         /* up to here a wavefront codes a chunk */
 constexpr uint32_t DENC_MAX_CHUNK = 2048;
 constexpr uint32_t denc_cap(bool big) { return TILE + (big ? DENC_MAX_CHUNK : DENC_SMALL_CHUNK); }
@@ -1079,7 +1079,13 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
 #pragma unroll
                     for (int j = 0; j < 4; ++j) xn[u][j] = 0.0f;
                     if (wt < nwt) {
-                        mn[u] = load_quad(r, gi, s.lo, s.hi, xn[u]);
+                        if (wb >= s.lo && wb + WTILE <= s.hi) {          /* the whole wave-tile lies inside the bucket */
+                            const f4 v = *reinterpret_cast<const f4 *>(r + gi);
+                            xn[u][0] = v.x; xn[u][1] = v.y; xn[u][2] = v.z; xn[u][3] = v.w;
+                            mn[u] = 0xFu;
+                        } else {
+                            mn[u] = load_quad(r, gi, s.lo, s.hi, xn[u]);
+                        }
                         if (t.pmask) mn[u] &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
                     }
                 }
@@ -1127,16 +1133,16 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
                 for (int u = 0; u < 4; ++u) {
                     const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
                     const uint32_t before = woff + ex[u];
-                    uint32_t pg = run_g + (before & 0xFFFFu), pe = run_e + (before >> 16);
+                    uint32_t pe = run_e + (before >> 16);
+                    /* a lane's survivors are consecutive in rank: one slot computed, then counted on */
+                    uint32_t slot = carry + (run_g + (before & 0xFFFFu) + min(e_b, pe) - Rnext);
+                    const uint32_t li0 = (uint32_t)(gi - s.lo);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const bool isg = (fg[u] >> j) & 1u, ise = (fe[u] >> j) & 1u;
-                        if (isg || (ise && pe < e_b)) {
-                            const uint32_t slot = carry + (pg + min(e_b, pe) - Rnext);
-                            sv[slot] = x[u][j];
-                            si[slot] = (uint32_t)(gi + j - s.lo);
-                        }
-                        pg += isg ? 1u : 0u;
+                        const bool ise = (fe[u] >> j) & 1u;
+                        const bool take = ((fg[u] >> j) & 1u) || (ise && pe < e_b);
+                        if (take) { sv[slot] = x[u][j]; si[slot] = li0 + j; }
+                        slot += take ? 1u : 0u;
                         pe += ise ? 1u : 0u;
                     }
                 }
