@@ -81,6 +81,7 @@ struct Tables {
     uint32_t segSh;          /* log2 of the staging segments per span (= wavefronts of the streaming pass) */
     uint32_t chunk;
     uint32_t chunkSh;        /* log2(chunk) when chunk is a power of two, else NONE */
+    uint32_t dencSpans;      /* spans per work unit of the one-pass dense encode (2 on large gradients: fewer chunks straddle units; 1 on smaller ones: more units than workgroups) */
 };
 
 /* Candidate staging: segment ss = (span << segSh) + wavefront owns entries [ss * cap, ss * cap + cnt[ss]) */

@@ -207,6 +207,7 @@ Tables tables_of(const nsml_ctx *c)
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0; t.nhard = hists_of(c, c->B).nhard;
     t.kw = c->d_kw; t.pmask = nullptr;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk; t.chunkSh = chunk_shift(c->chunk);
+    t.dencSpans = c->n_spans >= 16u * (uint32_t)c->n_cu ? 2u : 1u;
     return t;
 }
 
@@ -905,7 +906,7 @@ int nsml_decompress_static(const uint32_t *idx, const void *val, const float *sc
     memset(&t, 0, sizeof t);
     t.off = m.off; t.tile0 = m.tile0; t.span0 = m.span0; t.span_b = m.span_b;
     t.k = m.k; t.kw = m.kw; t.P = m.P; t.V = m.V; t.S = m.S; t.C = m.C;
-    t.B = B; t.n_spans = (uint32_t)ns; t.spanT = spanT; t.segSh = 2; t.chunk = chunk; t.chunkSh = chunk_shift(chunk);
+    t.B = B; t.n_spans = (uint32_t)ns; t.spanT = spanT; t.segSh = 2; t.chunk = chunk; t.chunkSh = chunk_shift(chunk); t.dencSpans = 1;
     LAUNCH(none, KID_SETUP, st, k_static_layout, 1, so, B, spanT, m.off, m.tile0, m.span0);
     LAUNCH(none, KID_SETUP, st, k_setup, 1, t, ratio, bits);
     LAUNCH(none, KID_SPANMAP, st, k_spanmap, (uint32_t)((ns + WG - 1) / WG), (const uint32_t *)m.span0, B,

@@ -1000,7 +1000,7 @@ __device__ __forceinline__ void grid_barrier(uint32_t *bar, uint32_t target, uin
  * dense accumulator and whose threshold is known (PATH_BAND, PATH_ZERO), with chunks of at most
  * DENC_MAX_CHUNK survivors.  Survivors are dense here (ratios from an eighth up, or an
  * embedding whose few non-zero rows all survive), so the work is laid out by elements: a
- * workgroup streams a unit of DENC_SPANS consecutive spans, 4096 elements at a time (one
+ * workgroup streams a unit of one or two (dencSpans) consecutive spans, 4096 elements at a time (one
  * wave-tile per wavefront); ranks come from ballots and a prefix over the four wavefronts; the
  * survivors are put into LDS in rank order behind the ones still waiting for their chunk to
  * fill up; every chunk that is complete is coded from LDS by one wavefront (absmax, scale,
@@ -1009,7 +1009,6 @@ __device__ __forceinline__ void grid_barrier(uint32_t *bar, uint32_t target, uin
  * bucket's spans of another unit) is written uncoded to idx / v_out, and k_quant codes exactly
  * those afterwards (same test, see chunk_coded_by_stream).  16-bit values need no chunk and are
  * all coded here. */
-constexpr uint32_t DENC_SPANS = 2;
 constexpr uint32_t DENC_SMALL_CHUNK = 256;         /* up to here a wavefront codes a chunk */
 constexpr uint32_t DENC_MAX_CHUNK = 2048;
 constexpr uint32_t denc_cap(bool big) { return TILE + (big ? DENC_MAX_CHUNK : DENC_SMALL_CHUNK); }
@@ -1024,7 +1023,7 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
     constexpr float QMAX = BITS == 8 ? 127.0f : 7.0f;     /* (unused for 16 / 32 bits) */
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t chunk = t.chunk;
-    const uint32_t n_units = (t.n_spans + DENC_SPANS - 1) / DENC_SPANS;
+    const uint32_t n_units = (t.n_spans + t.dencSpans - 1) / t.dencSpans;
     for (uint32_t unit = bid; unit < n_units; unit += nblk) {
         uint32_t cur_b = NONE;
         /* state of the stream: one bucket's consecutive spans inside the unit */
@@ -1042,8 +1041,8 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
             carry = 0;
             __syncthreads();
         };
-        const uint32_t sp1 = min(t.n_spans, (unit + 1) * DENC_SPANS);
-        for (uint32_t span = unit * DENC_SPANS; span < sp1; ++span) {
+        const uint32_t sp1 = min(t.n_spans, (unit + 1) * t.dencSpans);
+        for (uint32_t span = unit * t.dencSpans; span < sp1; ++span) {
             const uint32_t b = t.span_b[span];
             const uint32_t path = t.fast[b];
             if ((path != PATH_BAND && path != PATH_ZERO) || t.k[b] == 0u) {
@@ -1291,12 +1290,12 @@ __device__ __forceinline__ void dense_encode_body(float *__restrict__ r, const T
 
 /* Whether chunk cb (bucket-local) of a PATH_BAND / PATH_ZERO bucket b was coded by
  * dense_encode_body: its first survivor lies in segment s, and all of its survivors lie in the
- * spans of b inside the unit of DENC_SPANS spans that holds s. */
+ * spans of b inside the unit of dencSpans spans that holds s. */
 __device__ __forceinline__ bool chunk_coded_by_stream(const Tables &t, const Cand &c, uint32_t b, uint64_t cb, uint32_t s)
 {
     const uint32_t kb = t.k[b], e_b = t.need[b];
     const uint64_t end = min((cb + 1) * (uint64_t)t.chunk, (uint64_t)kb);
-    const uint32_t next_span = ((s >> t.segSh) / DENC_SPANS + 1u) * DENC_SPANS;
+    const uint32_t next_span = ((s >> t.segSh) / t.dencSpans + 1u) * t.dencSpans;
     uint64_t r1 = kb;
     if (next_span < t.span0[b + 1]) {
         const uint32_t sn = next_span << t.segSh;
