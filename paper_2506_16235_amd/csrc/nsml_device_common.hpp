@@ -69,6 +69,7 @@ struct Tables {
     uint32_t *subLo;         /* B   first of the SUB_DIGITS level-0 digits whose next 6 key bits the streaming pass
                               *     also counts (NONE: none) */
     uint32_t *sh;            /* B   T holds the key bits from this position up (19: the level-0 digit only; 13: six more) */
+    uint32_t *margin;        /* B   what the bucket has learned about its sample: factor on k_predict's margin (kept across calls) */
     uint32_t *why;           /* B   diagnostic: why the plan did not take the staged elements (WHY_* bits, 0 if it did) */
     uint32_t *ovf;           /* B   a staging segment of the bucket overflowed */
     uint32_t *fspan0;        /* B+1 prefix of the spans of fallback buckets */

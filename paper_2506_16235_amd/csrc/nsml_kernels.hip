@@ -93,7 +93,7 @@ struct nsml_ctx {
     uint4 *d_selw;         /* per workgroup of k_select_count: bucket, first and last segment */
     uint32_t *d_chunk_b;   /* per chunk of the payload: its bucket (fixed by layout, ratio, bits) */
     uint32_t *d_chunk_seg; /* per chunk: the staging segment that holds its first survivor */
-    uint32_t *d_H, *d_subLo, *d_sh, *d_why, *d_wredo, *d_wprevT, *d_wprevHw, *d_wnband;
+    uint32_t *d_H, *d_subLo, *d_sh, *d_why, *d_margin, *d_wredo, *d_wprevT, *d_wprevHw, *d_wnband;
     uint32_t *d_lcnt, *d_lkey;   /* k_select_count: lists of undecided keys per workgroup */
     uint64_t max_chunks; uint32_t max_sel;
     uint32_t *d_zero;      /* cleared by every compress call: histograms and overflow flags */
@@ -203,7 +203,7 @@ Tables tables_of(const nsml_ctx *c)
     t.off = c->d_off; t.tile0 = c->d_tile0; t.span0 = c->d_span0; t.samp0 = c->d_samp0;
     t.span_b = c->d_span_b;
     t.k = c->d_k; t.P = c->d_P; t.V = c->d_V; t.S = c->d_S; t.C = c->d_C;
-    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.H = c->d_H; t.fast = c->d_fast; t.subLo = c->d_subLo; t.sh = c->d_sh; t.why = c->d_why;
+    t.T = c->d_T; t.need = c->d_need; t.L = c->d_L; t.H = c->d_H; t.fast = c->d_fast; t.subLo = c->d_subLo; t.sh = c->d_sh; t.why = c->d_why; t.margin = c->d_margin;
     t.ovf = hists_of(c, c->B).ovf; t.fspan0 = c->d_fspan0; t.nhard = hists_of(c, c->B).nhard;
     t.kw = c->d_kw; t.pmask = nullptr;
     t.B = c->B; t.n_spans = c->n_spans; t.spanT = c->spanT; t.segSh = c->segSh; t.chunk = c->chunk; t.chunkSh = chunk_shift(c->chunk);
@@ -361,6 +361,7 @@ int ensure_layout(nsml_ctx *c, uint64_t n, const uint64_t *off, uint32_t B, hipS
         LAUNCH(c, KID_SPANMAP, st, k_selmap, (uint32_t)((nsel + WG - 1) / WG), (const uint32_t *)c->d_sel0,
                (const uint32_t *)c->d_span0, B, (uint32_t)nsel, segSh, c->d_selw);
     NSML_HIP(c, hipMemsetAsync(c->d_wprevT, 0xFF, sizeof(uint32_t) * B1, st));     /* other buckets: nothing remembered */
+    NSML_HIP(c, hipMemsetAsync(c->d_margin, 0, sizeof(uint32_t) * B1, st));
     NSML_HIP(c, hipStreamSynchronize(st));
 
     c->h_off.assign(off, off + B + 1);
@@ -428,7 +429,7 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     c->d_off = c->d_P = c->d_V = c->d_S = c->d_C = nullptr;
     c->d_tile0 = c->d_span0 = c->d_samp0 = c->d_span_b = c->d_k = c->d_T = c->d_need = nullptr;
     c->d_L = c->d_fast = c->d_fspan0 = c->d_zero = nullptr;
-    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = c->d_wredo = c->d_wprevT = c->d_wprevHw = c->d_wnband = nullptr;
+    c->d_sel0 = nullptr; c->d_selw = nullptr; c->d_chunk_b = c->d_chunk_seg = c->d_H = c->d_subLo = c->d_sh = c->d_why = c->d_margin = c->d_wredo = c->d_wprevT = c->d_wprevHw = c->d_wnband = nullptr;
     c->d_lcnt = c->d_lkey = nullptr;
     c->d_ccnt = c->d_cG = c->d_cE = c->d_cidx = nullptr;
     c->d_cval = nullptr; c->d_v = nullptr; c->d_ts = nullptr; c->d_span_sq = c->d_l2sq = nullptr; c->have_l2 = false;
@@ -470,7 +471,7 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_tile0, B1)); A(dev_alloc(c, &c->d_span0, B1)); A(dev_alloc(c, &c->d_samp0, B1));
     A(dev_alloc(c, &c->d_k, B1)); A(dev_alloc(c, &c->d_T, B1)); A(dev_alloc(c, &c->d_need, B1));
     A(dev_alloc(c, &c->d_L, B1)); A(dev_alloc(c, &c->d_fast, B1)); A(dev_alloc(c, &c->d_fspan0, B1));
-    A(dev_alloc(c, &c->d_sel0, B1)); A(dev_alloc(c, &c->d_H, B1)); A(dev_alloc(c, &c->d_subLo, B1)); A(dev_alloc(c, &c->d_sh, B1)); A(dev_alloc(c, &c->d_why, B1));
+    A(dev_alloc(c, &c->d_sel0, B1)); A(dev_alloc(c, &c->d_H, B1)); A(dev_alloc(c, &c->d_subLo, B1)); A(dev_alloc(c, &c->d_sh, B1)); A(dev_alloc(c, &c->d_why, B1)); A(dev_alloc(c, &c->d_margin, B1));
     A(dev_alloc(c, &c->d_span_b, mt));
     A(dev_alloc(c, &c->d_zero, zero_words(max_buckets)));
     /* segments: at most 4 per tile-sized span, or one per tile plus a partly filled span per bucket */
@@ -502,6 +503,7 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     A(dev_alloc(c, &c->d_wprevT, B1)); A(dev_alloc(c, &c->d_wprevHw, B1)); A(dev_alloc(c, &c->d_wnband, B1));
     if (rc == NSML_OK) {
         hipError_t e = hipMemset(c->d_wredo, 0, sizeof(uint32_t) * B1);
+        if (e == hipSuccess) e = hipMemset(c->d_margin, 0, sizeof(uint32_t) * B1);
         if (e == hipSuccess) e = hipMemset(c->d_wprevT, 0xFF, sizeof(uint32_t) * B1);   /* nothing remembered */
         if (e != hipSuccess) { c->last_hip = (int)e; rc = NSML_EHIP; }
     }
@@ -538,7 +540,7 @@ int nsml_destroy(nsml_ctx *c)
                     c->d_zero, c->d_ccnt, c->d_cG, c->d_cE, c->d_cidx,
                     c->d_cval, c->d_v, c->d_ts, c->d_span_sq, c->d_l2sq, c->d_pmask, c->d_kw,
                     c->d_Tw, c->d_needw, c->d_wfast,
-                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why, c->d_wredo, c->d_wprevT, c->d_wprevHw, c->d_wnband};
+                    c->d_wLo, c->d_wHi, c->d_sel0, c->d_selw, c->d_chunk_b, c->d_chunk_seg, c->d_H, c->d_lcnt, c->d_lkey, c->d_subLo, c->d_sh, c->d_why, c->d_margin, c->d_wredo, c->d_wprevT, c->d_wprevHw, c->d_wnband};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->h_flags) (void)hipHostFree(c->h_flags);
@@ -587,6 +589,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
          * had to take the dense passes), on its own set of tables */
         Tables tw = t;
         tw.k = c->d_kw; tw.T = c->d_Tw; tw.need = c->d_needw; tw.fast = c->d_wfast;
+        tw.L = c->d_wLo; tw.H = c->d_wHi;              /* the staged band of weight keys (H is never NONE here) */
         const Cand cdw = cd0;
         LAUNCH(c, KID_CLEAR, st, k_clear, clear_grid < 2048 ? clear_grid : 2048, c->d_zero, zw);
         if (!c->force_dense)
@@ -606,10 +609,10 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         /* buckets decided from their band: undecided keys, threshold key and tie count, the pruned
          * band elements' bits; buckets on the dense passes: everything in one resident launch */
         if (!c->force_dense) {
-            LAUNCH(c, KID_SELECT, st, k_select_count, c->n_sel, tw, cdw, (const uint4 *)c->d_selw, h.tail_ovf, c->d_lcnt, c->d_lkey);
+            LAUNCH(c, KID_SELECT, st, k_select_count, c->n_sel, tw, cdw, (const uint4 *)c->d_selw, h.tail_ovf, c->d_lcnt, c->d_lkey, weights);
             LAUNCHB(c, KID_FINISH, st, k_select_finish, B, SEL_THREADS, tw, cdw, (const uint32_t *)c->d_sel0, h.tail_ovf,
                     (const uint32_t *)c->d_lcnt, (const uint32_t *)c->d_lkey, (uint32_t *)nullptr, c->d_flags + 1,
-                    c->force_rescan);
+                    c->force_rescan, weights);
             LAUNCH(c, KID_WMASK, st, k_wfix, (n_ss + 15) / 16, tw, cdw, c->d_pmask);
         }
         LAUNCH(c, KID_WHARD, st, k_whard, (uint32_t)c->n_cu, weights, tw, cdw, h.f1, h.f2, c->d_pmask, c->d_flags + 1);
@@ -648,10 +651,10 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
         /* buckets decided from their staged elements: undecided keys set apart, threshold and
          * survivor order per bucket, then the payload of the candidate-path buckets */
         const uint4 *selw = c->d_selw;
-        LAUNCH(c, KID_SELECT, st, k_select_count, c->n_sel, t, cd0, selw, h.tail_ovf, c->d_lcnt, c->d_lkey);
+        LAUNCH(c, KID_SELECT, st, k_select_count, c->n_sel, t, cd0, selw, h.tail_ovf, c->d_lcnt, c->d_lkey, (const float *)residual);
         LAUNCHB(c, KID_FINISH, st, k_select_finish, B, SEL_THREADS, t, cd0, (const uint32_t *)c->d_sel0, h.tail_ovf,
                 (const uint32_t *)c->d_lcnt, (const uint32_t *)c->d_lkey, c->d_chunk_seg, c->d_flags,
-                c->force_rescan);
+                c->force_rescan, (const float *)residual);
         {
             const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
             const uint64_t nc64e = c->NC;

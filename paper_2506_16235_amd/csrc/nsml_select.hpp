@@ -93,7 +93,11 @@ __global__ __launch_bounds__(WG) void k_predict(Tables t, uint32_t *__restrict__
      * ones the pruning step kept */
     const double pop = t.pmask ? (double)t.kw[b] : (double)nb;
     const double ks = (double)k * (double)m / pop;
-    const double dev = exact ? 0.0 : 4.0 * sqrt(ks) + 4.0;
+    /* the margin: four standard deviations of a binomial sample, times what the bucket has
+     * learned (a sample of 32-element runs of a gradient whose large values come in runs has far
+     * fewer independent draws than entries; a bucket whose guess missed widens its margin) */
+    const double widen = (double)(t.margin[b] & 0xFFu ? t.margin[b] & 0xFFu : 1u);
+    const double dev = exact ? 0.0 : (4.0 * sqrt(ks) + 4.0) * widen;
     const double want_d = exact ? (double)k : ceil(ks + dev);
     const double cap_b = (double)(t.span0[b + 1] - t.span0[b]) * 4.0 * (double)t.spanT * 256.0;
     double r_up = floor(ks - dev), r_dn = ceil(ks + dev);
@@ -311,7 +315,9 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
         }
     }
     if (EMIT && lane == 0) {
-        c.cnt[ss] = min(wcount, c.cap);
+        /* the true count: more than the segment holds means "read this segment from the dense
+         * accumulator" to the kernels that follow */
+        c.cnt[ss] = wcount;
         if (wcount > c.cap) t.ovf[s.b] = 1u;
         if (H != NONE) { c.G[ss] = n_hi; c.E[ss] = n_lo; }
     }
@@ -428,13 +434,15 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, uint32_t *__restrict__ hi
         if (tid != 0) return;
         uint32_t why = 0u;
         if (!have_cand || L == NONE) why = WHY_NO_GUESS;
-        else if (ovf) why = WHY_OVERFLOW;
         else {
+            /* a staging segment that overflowed is read from the dense accumulator by the kernels
+             * that find the threshold; the survivors of such a bucket are then taken from the dense
+             * accumulator as well (PATH_BAND), since the staged entries cannot supply them all */
             const uint64_t cap_b = (uint64_t)((t.span0[b + 1] - t.span0[b]) << t.segSh) * c.cap;
             if (fine) at = at18;
-            const bool room = (uint64_t)at * 2u <= cap_b - (uint64_t)n_cand;     /* for the undecided keys in the tails */
+            const bool room = (uint64_t)n_cand <= cap_b && (uint64_t)at * 2u <= cap_b - (uint64_t)n_cand;     /* for the undecided keys in the tails */
             if (H == NONE) {
-                if (n_cand >= want && room) path = PATH_CAND;
+                if (n_cand >= want && room) path = ovf ? PATH_BAND : PATH_CAND;
                 else why = n_cand < want ? WHY_TOO_FEW : WHY_NO_ROOM;
             } else if (L == H) {
                 /* n_hi = non-zero keys among the selectable elements: if they are no more than k,
@@ -451,6 +459,15 @@ __global__ __launch_bounds__(WG) void k_plan(Tables t, uint32_t *__restrict__ hi
             if (fine && (path == PATH_CAND || path == PATH_BAND)) { T = T18; need = need18; sh = SHS; }
         }
         t.why[b] = why;
+        {
+            /* low byte: factor on the margin of k_predict (1, 2, 4, 8, 16); above it: calls since it last grew.
+             * A guess that missed doubles it, 64 calls without a miss halve it. */
+            const uint32_t mg = t.margin[b];
+            uint32_t f = mg & 0xFFu ? mg & 0xFFu : 1u, age = mg >> 8;
+            if (why == WHY_TOO_FEW || why == WHY_OUTSIDE_BAND) { f = f < 16u ? f * 2u : 16u; age = 0u; }
+            else if (++age >= 64u) { f = f > 1u ? f / 2u : 1u; age = 0u; }
+            t.margin[b] = (age << 8) | f;
+        }
         t.T[b] = T;
         t.need[b] = need;
         t.sh[b] = sh;

@@ -149,10 +149,47 @@ constexpr uint32_t LCAP = SELC_SEGS * 128;            /* list entries per workgr
 /* a list entry: the 19 key bits below the level-0 digit, and above them the segment's number inside the workgroup */
 __device__ __forceinline__ uint32_t list_entry(uint32_t key, uint32_t segl) { return (segl << SH0) | (key & ((1u << SH0) - 1u)); }
 
+/* A staging segment that overflowed (more staged elements than a quarter of what it covers: its
+ * count says so) is read from the dense accumulator instead: the elements its wavefront of the
+ * streaming pass covered, in index order, minus the pruned ones.  This is their range. */
+struct DenseSeg {
+    uint64_t e0;         /* first element (global index) */
+    uint32_t len;
+};
+__device__ __forceinline__ DenseSeg dense_seg(const Tables &t, uint32_t b, uint32_t ss)
+{
+    const uint32_t span = ss >> t.segSh, wv = ss & ((1u << t.segSh) - 1u);
+    const SpanGeo s = span_geo_b(t, b, span - t.span0[b]);
+    const uint32_t per = (t.spanT * 4u) >> t.segSh;
+    const uint32_t wt0 = wv * per, wt1 = min(s.ntiles * 4u, wt0 + per);
+    DenseSeg d;
+    d.e0 = 0; d.len = 0;
+    if (wt1 > wt0) {
+        const uint64_t a = max(s.lo, s.base + (uint64_t)wt0 * WTILE), z = min(s.hi, s.base + (uint64_t)wt1 * WTILE);
+        if (z > a) { d.e0 = a; d.len = (uint32_t)(z - a); }
+    }
+    return d;
+}
+/* whether element e (global index) of a bucket whose first tile is tile0b and starts at lo_al
+ * (its offset rounded down to a multiple of 4) is pruned */
+__device__ __forceinline__ bool pruned_elem(const uint32_t *__restrict__ pmask, uint32_t tile0b, uint64_t lo_al, uint64_t e)
+{
+    const uint64_t pos = e - lo_al;
+    return (pmask[(uint64_t)(tile0b + (uint32_t)(pos / TILE)) * (TILE / 32) + (uint32_t)((pos % TILE) >> 5)] >> (pos & 31u)) & 1u;
+}
+struct DenseSrc {
+    const float *r;              /* the dense accumulator */
+    const uint32_t *pmask;       /* NULL: nothing is pruned */
+    uint32_t tile0b;
+    uint64_t lo_al;
+};
+
 /* One wavefront's four segments of k_select_count, GROUP lanes per segment (16: all four at
- * once, 64: one after the other). */
+ * once, 64: one after the other).  mlen != 0 in the lane that describes a segment: the segment
+ * overflowed and is read from the dense accumulator (me0, mlen). */
 template <uint32_t GROUP>
 __device__ __forceinline__ void select_count_wave(const Cand &c, uint32_t b0, uint32_t sh, uint32_t wseg0, uint32_t mcnt,
+                                                  uint64_t me0, uint32_t mlen, const DenseSrc &ds,
                                                   uint32_t segl0, uint32_t *lk, uint32_t *lcur,
                                                   uint32_t &my_g, uint32_t &my_b)
 {
@@ -166,23 +203,30 @@ __device__ __forceinline__ void select_count_wave(const Cand &c, uint32_t b0, ui
 #pragma unroll
     for (uint32_t rd = 0; rd < ROUNDS; ++rd) {
         const uint32_t src = rd * SPR + sub;
-        const uint32_t cnt = __shfl(mcnt, src, 64);
+        const uint32_t staged = __shfl(mcnt, src, 64);
+        const uint32_t dlen = __shfl(mlen, src, 64);
+        const bool dense = dlen != 0u;
+        const uint64_t e0 = ((uint64_t)__shfl((uint32_t)(me0 >> 32), src, 64) << 32) | (uint64_t)__shfl((uint32_t)me0, src, 64);
+        const uint32_t cnt = dense ? dlen : staged;
         uint32_t maxcnt = cnt;
 #pragma unroll
         for (int d = 32; d >= (int)GROUP; d >>= 1) maxcnt = max(maxcnt, (uint32_t)__shfl_xor(maxcnt, d, 64));
         const uint64_t base = (uint64_t)(wseg0 + src) * c.cap;
+        const float *p = dense ? ds.r + e0 : c.val + base;
         uint32_t run_g = 0, run_b = 0;
         for (uint32_t i0 = 0; i0 < maxcnt; i0 += 2 * CU * GROUP) {
             float x[2 * CU];
 #pragma unroll
             for (uint32_t u = 0; u < 2 * CU; ++u) {
                 const uint32_t i = i0 + u * GROUP + gl;
-                x[u] = i < cnt ? c.val[base + i] : 0.0f;
+                x[u] = i < cnt ? p[i] : 0.0f;
             }
 #pragma unroll
             for (uint32_t u = 0; u < 2 * CU; ++u) {
                 const uint32_t key = keyof(x[u]);
-                const bool in = i0 + u * GROUP + gl < cnt;
+                const uint32_t i = i0 + u * GROUP + gl;
+                bool in = i < cnt;
+                if (dense && ds.pmask && in) in = !pruned_elem(ds.pmask, ds.tile0b, ds.lo_al, e0 + i);
                 const bool isg = in && (key >> sh) > b0, isb = in && (key >> sh) == b0;
                 const uint64_t ball = __ballot(isb);
                 const uint64_t bg = (__ballot(isg) >> shift) & gmask;
@@ -195,7 +239,7 @@ __device__ __forceinline__ void select_count_wave(const Cand &c, uint32_t b0, ui
                     lbase = __builtin_amdgcn_readfirstlane(lbase);
                     if (isb) {
                         const uint32_t pos = run_b + __popcll(bb & below);
-                        if (cnt + pos < c.cap) cvalu[base + c.cap - 1u - pos] = key;
+                        if (!dense && cnt + pos < c.cap) cvalu[base + c.cap - 1u - pos] = key;
                         const uint32_t lp = lbase + __popcll(ball & ((1ull << lane) - 1ull));
                         if (lp < LCAP) lk[lp] = list_entry(key, segl0 + src);
                     }
@@ -221,7 +265,7 @@ __device__ __forceinline__ void select_count_wave(const Cand &c, uint32_t b0, ui
  * segment, or all 64 on one segment after the other when a segment is long. */
 __global__ __launch_bounds__(WG) void k_select_count(Tables t, Cand c, const uint4 *__restrict__ selw,
                                                      uint32_t *__restrict__ tail_ovf, uint32_t *__restrict__ lcnt,
-                                                     uint32_t *__restrict__ lkey)
+                                                     uint32_t *__restrict__ lkey, const float *__restrict__ r)
 {
     __shared__ uint32_t lk[LCAP];
     __shared__ uint32_t lcur;
@@ -236,20 +280,32 @@ __global__ __launch_bounds__(WG) void k_select_count(Tables t, Cand c, const uin
     uint32_t mg0 = mine ? c.G[ms] : 0u;              /* band mode: elements above the band, counted by the streaming pass */
     const uint32_t path = t.fast[b], b0 = t.T[b], sh = t.sh[b];     /* b0: the key bits from position sh up */
     if (path != PATH_CAND && path != PATH_BAND) return;      /* same for the whole workgroup */
-    if (path != PATH_BAND) mg0 = 0u;
+    if (t.H[b] == NONE) mg0 = 0u;                    /* no band was staged: nothing was counted above it */
     if (tid == 0) lcur = 0u;
     __syncthreads();
-    uint32_t mx = mcnt;
+    /* an overflowed segment is read from the dense accumulator, where nothing is missing */
+    uint64_t me0 = 0;
+    uint32_t mlen = 0;
+    if (mine && mcnt > c.cap) {
+        const DenseSeg d = dense_seg(t, b, ms);
+        me0 = d.e0; mlen = d.len;
+        mg0 = 0u;                                    /* its elements above the band are counted here as well */
+    }
+    DenseSrc ds;
+    ds.r = r; ds.pmask = t.pmask; ds.tile0b = t.tile0[b]; ds.lo_al = t.off[b] & ~3ull;
+    uint32_t mx = mlen ? mlen : mcnt;
 #pragma unroll
     for (int d = 2; d >= 1; d >>= 1) mx = max(mx, (uint32_t)__shfl_xor(mx, d, 64));
     mx = __builtin_amdgcn_readfirstlane(mx);
     uint32_t my_g = 0, my_b = 0;
-    if (mx > 2 * CU * 16) select_count_wave<64>(c, b0, sh, wseg0, mcnt, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
-    else if (mx) select_count_wave<16>(c, b0, sh, wseg0, mcnt, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+    if (mx > 2 * CU * 16) select_count_wave<64>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+    else if (mx) select_count_wave<16>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
     if (mine) {
         c.G[ms] = mg0 + my_g;
         c.E[ms] = my_b;
-        if (mcnt + my_b > c.cap) tail_ovf[b] = 1u;   /* a tail did not fit: k_select_finish filters the entries again */
+        /* a tail that did not fit (or a segment without one): k_select_finish filters the entries again
+         * if it cannot use the lists */
+        if (my_b != 0u && (mlen != 0u || mcnt + my_b > c.cap)) tail_ovf[b] = 1u;
     }
     __syncthreads();
     const uint32_t total = lcur;
@@ -269,21 +325,36 @@ struct KeySource {
     const uint32_t *cnt;
     uint32_t cap, b0, sh;
     bool rescan;
-    __device__ __forceinline__ uint32_t words(uint32_t s, uint32_t bcnt) const { return rescan ? cnt[s] : bcnt; }
-    __device__ __forceinline__ uint32_t raw(uint32_t s, uint32_t i) const
-    {
-        return rescan ? (cvalu[(uint64_t)s * cap + i] & 0x7FFFFFFFu) : cvalu[(uint64_t)s * cap + cap - 1u - i];
-    }
+    const Tables *t;             /* for the segments that overflowed: they are read from the dense accumulator */
+    const float *r;
+    uint32_t b;
     __device__ __forceinline__ bool wanted(uint32_t key) const { return !rescan || (key >> sh) == b0; }
     /* f(key) for every undecided key of segment s, eight loads in flight at a time */
     template <typename F>
     __device__ __forceinline__ void for_each(uint32_t s, uint32_t bcnt, F f) const
     {
-        const uint32_t nw = words(s, bcnt);
+        const uint32_t staged = cnt[s];
+        if (rescan && staged > cap) {
+            const DenseSeg d = dense_seg(*t, b, s);
+            const uint32_t tile0b = t->tile0[b];
+            const uint64_t lo_al = t->off[b] & ~3ull;
+            for (uint32_t i = 0; i < d.len; i += 8) {
+                uint32_t kk[8];
+#pragma unroll
+                for (uint32_t u = 0; u < 8; ++u) kk[u] = i + u < d.len ? keyof(r[d.e0 + i + u]) : 0u;
+#pragma unroll
+                for (uint32_t u = 0; u < 8; ++u)
+                    if (i + u < d.len && wanted(kk[u]) && !(t->pmask && pruned_elem(t->pmask, tile0b, lo_al, d.e0 + i + u))) f(kk[u]);
+            }
+            return;
+        }
+        const uint32_t nw = rescan ? staged : bcnt;
+        const uint64_t base = (uint64_t)s * cap;
         for (uint32_t i = 0; i < nw; i += 8) {
             uint32_t kk[8];
 #pragma unroll
-            for (uint32_t u = 0; u < 8; ++u) kk[u] = i + u < nw ? raw(s, i + u) : 0u;
+            for (uint32_t u = 0; u < 8; ++u)
+                kk[u] = i + u < nw ? (rescan ? (cvalu[base + i + u] & 0x7FFFFFFFu) : cvalu[base + cap - 1u - (i + u)]) : 0u;
 #pragma unroll
             for (uint32_t u = 0; u < 8; ++u)
                 if (i + u < nw && wanted(kk[u])) f(kk[u]);
@@ -468,14 +539,15 @@ __device__ __forceinline__ void finish_from_lists(const Tables &t, const Cand &c
 __device__ __forceinline__ void finish_from_tails(const Tables &t, const Cand &c, uint32_t b, uint32_t b0, uint32_t sh,
                                                   uint32_t need0, uint32_t kb, uint32_t seg_lo, uint32_t seg_hi,
                                                   bool rescan, uint32_t *__restrict__ chunk_seg,
-                                                  const FinShared &sm, uint32_t *__restrict__ err)
+                                                  const FinShared &sm, uint32_t *__restrict__ err,
+                                                  const float *__restrict__ r)
 {
     const uint32_t tid = threadIdx.x;
     uint32_t *h1 = sm.pool, *keys = sm.pool + 8192;
     uint16_t *sbc = reinterpret_cast<uint16_t *>(sm.pool + 4096);
     KeySource ks;
     ks.cvalu = reinterpret_cast<const uint32_t *>(c.val); ks.cnt = c.cnt; ks.cap = c.cap; ks.b0 = b0; ks.sh = sh;
-    ks.rescan = rescan;
+    ks.rescan = rescan; ks.t = &t; ks.r = r; ks.b = b;
     const uint32_t m1 = (1u << (sh - SH1)) - 1u;       /* level-1 digit: key bits sh-1 .. 7 */
     const uint32_t rounds = (seg_hi - seg_lo + SEL_THREADS - 1) / SEL_THREADS;
     for (uint32_t i = tid; i < NB1; i += SEL_THREADS) h1[i] = 0u;
@@ -568,7 +640,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_finish(Tables t, Cand c,
                                                                const uint32_t *__restrict__ lcnt,
                                                                const uint32_t *__restrict__ lkey,
                                                                uint32_t *__restrict__ chunk_seg,
-                                                               uint32_t *__restrict__ err, int force_rescan)
+                                                               uint32_t *__restrict__ err, int force_rescan,
+                                                               const float *__restrict__ r)
 {
     __shared__ uint32_t pool[FIN_POOL];
     __shared__ uint32_t h2[NB2];
@@ -599,8 +672,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_finish(Tables t, Cand c,
     }
     const uint32_t nun = u1 - u0;
     const int no_list = __syncthreads_or(my_cnt == NONE);
-    if (no_list || ovf != 0u || force_rescan || nun > SEL_THREADS || seg_hi - seg_lo > FIN_MAX_SEGS)
-        finish_from_tails(t, c, b, b0, sh, need0, kb, seg_lo, seg_hi, ovf != 0u || force_rescan, chunk_seg, sm, err);
+    /* the lists hold every undecided key whenever none of them was left out; the tails are the
+     * fallback, and when a tail did not fit either (or a segment has none: it overflowed), the
+     * segments are filtered again */
+    if (no_list || force_rescan || nun > SEL_THREADS || seg_hi - seg_lo > FIN_MAX_SEGS)
+        finish_from_tails(t, c, b, b0, sh, need0, kb, seg_lo, seg_hi, ovf != 0u || force_rescan, chunk_seg, sm, err, r);
     else
         finish_from_lists(t, c, b, b0, sh, need0, kb, seg_lo, seg_hi, u0, nun, my_cnt, lkey, chunk_seg, sm, err);
 }

@@ -150,7 +150,33 @@ def test_resnet50_shaped_scaled_ef_steps():
         c.step(0.05, 8)
 
 
-@pytest.mark.parametrize("ratio", [0.1, 0.01, 0.001])
+@pytest.mark.parametrize("bits", [4, 8, 32])
+def test_clustered_survivors_overflow_staging_segments(path, bits):
+    """Survivors packed into runs longer than a staging segment holds (an embedding whose few
+    touched rows carry all the large values): those segments are read from the dense accumulator
+    instead, and the bucket's survivors are then taken from there too; no dense passes.  Three
+    steps, with the residual of the steps before."""
+    n0, n1 = 1_500_000, 40_000
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(31 + bits)
+    g = W._laplace(n0 + n1, 1e-6, gen, DEV)
+    for start in range(10_000, n0 - 5_000, 60_000):
+        g[start:start + 3_000] = W._laplace(3_000, 1e-3, gen, DEV)
+    off = np.array([0, n0, n0 + n1], dtype=np.uint64)
+    c = Case(g, off, chunk=256)
+    for step, ratio in enumerate((0.04, 0.05, 0.02)):
+        c.step(ratio, bits)
+        st = c.ctx.bucket_state(0)
+        say("clustered", bits, path, ratio, st)
+        if path == "auto":
+            assert st["path"] == 2, st               # threshold from staged + dense segments, survivors from the accumulator
+        g2 = W._laplace(n0 + n1, 1e-6, gen, DEV)
+        for start in range(10_000 + 777 * (step + 1), n0 - 5_000, 60_000):
+            g2[start:start + 3_000] = W._laplace(3_000, 1e-3, gen, DEV)
+        c.set_grad(g2)
+
+
+@pytest.mark.parametrize("ratio", [0.1, 0.05, 0.01, 0.001])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_bert_shaped_scaled(ratio, bits):
     """Configuration 3 at 1/24 scale in every tensor but with the embedding's structure kept:

@@ -98,5 +98,31 @@ def test_weights_that_move_little_between_steps(path):
     _run([300_000, 2_000_003, 70_000], 0.01, 4, 256, steps=3, seed=78, drift=1e-2)
 
 
+def test_clustered_survivors_with_pruning():
+    """Runs of large gradients longer than a staging segment holds, under pruning: the segments
+    that overflow are read from the dense accumulator, minus the pruned parameters."""
+    n0 = 1_200_000
+    off = W.offsets_of([n0, 30_001])
+    n = int(off[-1])
+    ctx = nsml.Context(n, 2, 256)
+    r = torch.zeros(n, device=DEV)
+    r_h = np.zeros(n, dtype=np.float32)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(909)
+    for step, ratio in enumerate((0.05, 0.03)):
+        g = W._laplace(n, 1e-6, gen, DEV)
+        for start in range(5_000 + 911 * step, n0 - 4_000, 50_000):
+            g[start:start + 3_500] = W._laplace(3_500, 1e-3, gen, DEV)
+        w = _rand(n, 500 + step, sigma=0.05)
+        idx, val, sc = ctx.compress_pruned(g, r, w, off, ratio, 8)
+        torch.cuda.synchronize()
+        ctx.path_stats()
+        w_idx, w_val, w_sc = oracle.compress_pruned(g.cpu().numpy(), r_h, w.cpu().numpy(), off, ratio, 8, 256, nthreads=8)
+        k_b, K, vb, ns = oracle.layout(off, ratio, 8, 256)
+        got = (idx.cpu().numpy().view(np.uint32)[:K], val.cpu().numpy()[:vb], sc.cpu().numpy()[:ns])
+        compare_payload(off, ratio, 8, 256, got, (w_idx, w_val, w_sc))
+        assert np.array_equal(r.cpu().numpy().view(np.uint32), r_h.view(np.uint32))
+
+
 def test_large_single_bucket():
     _run([5_000_000], 0.01, 8, 2048, steps=2)
