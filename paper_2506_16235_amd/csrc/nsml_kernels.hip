@@ -129,6 +129,7 @@ struct nsml_ctx {
     int persist;           /* workgroups per compute unit of the streaming pass (0: one workgroup per span) */
     int decomp_variant;    /* decompress: 1 direct stores, 0 tiles assembled in LDS, -1 by gradient size */
     int n_cu;
+    int hard_occ[2];       /* workgroups of k_hard that fit a compute unit at once (short / long chunks) */
     int whistory;          /* the weight band follows the threshold of the last call (1, default) or always comes from a sample (0) */
     int wband_miss;        /* diagnostic: the weight band is placed beside the threshold, so every bucket takes the repeat */
     int force_rescan;      /* diagnostic: k_select_finish filters the staged entries again instead of using the tails */
@@ -454,6 +455,15 @@ int nsml_create_ex(nsml_ctx **out, int device, uint64_t max_n, uint32_t max_buck
     {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->n_cu = cus;
+        /* k_hard's workgroups meet at barriers, so its grid must fit the device at once: ask the
+         * runtime how many of them a compute unit holds (the variants per width use the same LDS) */
+        int occ = 0;
+        c->hard_occ[0] = c->hard_occ[1] = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_hard<8, false>, (int)WG, 0) == hipSuccess && occ > 0)
+            c->hard_occ[0] = occ < (int)hard_wg_per_cu(false) ? occ : (int)hard_wg_per_cu(false);
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_hard<8, true>, (int)WG, 0) == hipSuccess && occ > 0)
+            c->hard_occ[1] = occ < (int)hard_wg_per_cu(true) ? occ : (int)hard_wg_per_cu(true);
+        (void)hipGetLastError();
     }
 
     /* every bucket can add one partial tile at each end */
@@ -675,7 +685,7 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
      * left uncoded */
     {
         const bool big = c->chunk > DENC_SMALL_CHUNK;
-        const uint32_t hgrid = (uint32_t)(hard_wg_per_cu(big) * c->n_cu), team = hgrid;
+        const uint32_t hgrid = (uint32_t)(c->hard_occ[big ? 1 : 0] * c->n_cu), team = hgrid;
         const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
         const int stream_coding = c->chunk <= DENC_MAX_CHUNK ? 1 : 0;
 #define NSML_HARD(BITS_, BIG_) LAUNCH(c, KID_HARD, st, (k_hard<BITS_, BIG_>), hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team)
