@@ -144,7 +144,11 @@ typedef struct nsml_ctx nsml_ctx;
  * available (there is no CPU fallback).
  * A context serialises nothing itself: its calls share the workspace and the cached tables, so
  * they must not overlap, neither from several host threads nor on different streams (use one
- * context per stream).  A change of bucket layout between calls makes the next call wait for
+ * context per stream).  Several contexts may work at the same time; the rare buckets that take the
+ * dense passes use a small resident team of workgroups with barriers between its steps (one per
+ * compute unit), sized so that the teams of a few concurrent contexts fit the device together; a
+ * barrier that cannot complete within five seconds (the device held by something else for that
+ * long) raises the consistency flag instead of waiting on.  A change of bucket layout between calls makes the next call wait for
  * the stream once, to rebuild the tables; a change of (ratio, bits) costs one small kernel. */
 int nsml_create(nsml_ctx **ctx, int device, uint64_t max_n, uint32_t max_buckets, uint32_t chunk);
 /* As nsml_create for callers that never exceed a ratio: the buffer of survivor values is sized

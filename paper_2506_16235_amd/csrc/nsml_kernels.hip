@@ -685,7 +685,10 @@ static int compress_impl(nsml_ctx *c, const float *grad, float *residual, const 
      * left uncoded */
     {
         const bool big = c->chunk > DENC_SMALL_CHUNK;
-        const uint32_t hgrid = (uint32_t)(c->hard_occ[big ? 1 : 0] * c->n_cu), team = hgrid;
+        const uint32_t hgrid = (uint32_t)(c->hard_occ[big ? 1 : 0] * c->n_cu);
+        /* the workgroups that meet at barriers: one per compute unit, so that the teams of two or
+         * three contexts working at the same time still fit the device together */
+        const uint32_t team = (uint32_t)c->n_cu < hgrid ? (uint32_t)c->n_cu : hgrid;
         const uint32_t *cb_ = c->d_chunk_b, *cs_ = c->d_chunk_seg;
         const int stream_coding = c->chunk <= DENC_MAX_CHUNK ? 1 : 0;
 #define NSML_HARD(BITS_, BIG_) LAUNCH(c, KID_HARD, st, (k_hard<BITS_, BIG_>), hgrid, residual, t, cd0, h.f1, h.f2, idx, vdst, val, scales, c->d_flags, stream_coding, team)

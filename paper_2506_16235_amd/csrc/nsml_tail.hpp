@@ -1401,9 +1401,10 @@ __global__ __launch_bounds__(WG, hard_wg_per_cu(BIG)) void k_hard(float *__restr
                                      pool + denc_cap(BIG), pool + 2 * denc_cap(BIG), err, bid, nblk);
     else
         write_dense_body<BITS == 32>(r, t, c, idx, vdst, (1u << PATH_BAND) | (1u << PATH_ZERO), bid, nblk);
-    /* the dense passes: the first `team` workgroups (all of them: the grid is sized to fit the
-     * device at once, hard_wg_per_cu workgroups per compute unit by registers and LDS, so every
-     * one of them is resident by the time the others wait for it) */
+    /* the dense passes: the first `team` workgroups only.  They are dispatched before the others
+     * of this launch, and the team is small enough (one workgroup per compute unit) to be
+     * resident at once even next to the teams of other contexts; a barrier that still cannot
+     * complete runs into its time limit and raises the consistency flag. */
     if (t.nhard[2] == 0u || bid >= team) return;
     __syncthreads();
     nblk = team;
