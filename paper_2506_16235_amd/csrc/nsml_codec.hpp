@@ -315,10 +315,13 @@ __global__ __launch_bounds__(WG) void k_tilestart_search(const uint32_t *__restr
 }
 
 /* Dense output for a span of tiles, the variant for gradients of up to a few hundred million
- * elements (256 threads): each tile is assembled in LDS (zeros, then the decoded
- * survivors that fall inside it, found through the tile-start table) and written out once with
- * aligned 16-byte stores, so no output line is touched twice and no atomics are needed.  The
- * loads of the next tile's survivors are issued before the current tile is written out. */
+ * elements and for any gradient whose tiles hold many survivors (256 threads): each tile is
+ * assembled in LDS (zeros, then the decoded survivors that fall inside it, found through the
+ * tile-start table) and written out once with aligned 16-byte stores, so no output line is
+ * touched twice and no atomics are needed.  The loads of the next tile's first survivors are
+ * issued before the current tile is written out; a very crowded tile is read four consecutive
+ * survivors per thread and load.  A bucket of which every element was sent needs neither LDS
+ * nor its index list: its output is the decoded value stream. */
 template <int BITS, bool NTS>
 __global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ idx, const void *__restrict__ val,
                                                const float *__restrict__ scales, Tables t,
@@ -334,6 +337,55 @@ __global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ 
     const float *sb = BITS <= 8 ? scales + t.S[s.b] : nullptr;
     const uint32_t nb = (uint32_t)(s.hi - s.lo);
     const uint32_t first = s.tile_g - t.tile0[s.b];
+    if (kb == nb) {
+        /* every element of the bucket was sent (ratio 1, or a bucket of one element): survivor j is
+         * element j, so the index list (which can only be 0 .. n_b - 1) is not read and the
+         * output is a plain decode of the value stream */
+        for (uint32_t ti = 0; ti < s.ntiles; ++ti) {
+            const uint64_t tb = s.base + (uint64_t)ti * TILE;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint64_t gi = tb + (uint64_t)(u * WG + tid) * 4;
+                float x[4];
+                if ((BITS == 8 || BITS == 32) && gi >= s.lo && gi + 4 <= s.hi) {
+                    /* four consecutive values in one load (the value stream of a bucket starts at
+                     * any byte, so the address is not aligned; global loads need not be) */
+                    const uint64_t j0 = gi - s.lo;
+                    if (BITS == 32) {
+                        f4 v;
+                        __builtin_memcpy(&v, vb + 4 * j0, 16);
+                        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+                    } else {
+                        uint32_t w4;
+                        __builtin_memcpy(&w4, vb + j0, 4);
+                        const uint64_t c0 = t.chunkSh < 64u ? (j0 >> t.chunkSh) : j0 / t.chunk;
+                        const uint64_t c3 = t.chunkSh < 64u ? ((j0 + 3) >> t.chunkSh) : (j0 + 3) / t.chunk;
+                        const float s0 = sb[c0], s3 = c3 == c0 ? s0 : sb[c3];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int q = (int)(int8_t)(w4 >> (8 * j));
+                            const uint64_t cj = t.chunkSh < 64u ? ((j0 + j) >> t.chunkSh) : (j0 + j) / t.chunk;
+                            x[j] = __fmul_rn((float)q, cj == c0 ? s0 : s3);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        x[j] = (gi + j >= s.lo && gi + j < s.hi) ? decode<BITS>(vb, sb, gi + j - s.lo, t.chunk, t.chunkSh) : 0.0f;
+                }
+                if (gi >= s.lo && gi + 4 <= s.hi) {
+                    const f4 v = {x[0], x[1], x[2], x[3]};
+                    if (NTS) __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(dense + gi));
+                    else *reinterpret_cast<f4 *>(dense + gi) = v;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (gi + j >= s.lo && gi + j < s.hi) dense[gi + j] = x[j];
+                }
+            }
+        }
+        return;
+    }
     if (tid <= s.ntiles) sts[tid] = min(ts[t.tile0[s.b] + s.b + first + tid], kb);
     __syncthreads();
 
@@ -360,22 +412,70 @@ __global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ 
             const uint64_t slot = (uint64_t)p_li + shift;
             if (slot < TILE) tile[slot] = p_x;
         }
-        /* more than 256 survivors in the tile (ratio above 6 %): four per thread in flight */
+        /* more than 256 survivors in the tile (ratio above 6 %): a thread takes four consecutive
+         * ones at a time, indices and codes each in one load (the addresses are not aligned; global
+         * loads need not be), two such groups in flight; the last few of a tile one by one */
         const uint32_t j0 = sts[ti], j1 = sts[ti + 1];
-        for (uint64_t jb = (uint64_t)j0 + WG; jb < j1; jb += 4 * WG) {
-            uint32_t li4[4];
-            float x4[4];
+        const uint64_t jA = (uint64_t)j0 + WG;
+        /* (groups of four only when there is at least one for every thread: otherwise a survivor per thread keeps more of them busy) */
+        const uint64_t ngrp = j1 >= jA + 4 * WG ? (j1 - jA) / 4 : 0;      /* whole groups of four */
+        for (uint64_t g0 = 0; g0 < ngrp; g0 += 2 * WG) {
+            uint32_t li4[2][4];
+            float x4[2][4];
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const uint64_t g = g0 + (uint64_t)v * WG + tid;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { li4[v][u] = NONE; x4[v][u] = 0.0f; }
+                if (g < ngrp) {
+                    const uint64_t j = jA + 4 * g;
+                    uint4 iv;
+                    __builtin_memcpy(&iv, ib + j, 16);
+                    li4[v][0] = iv.x; li4[v][1] = iv.y; li4[v][2] = iv.z; li4[v][3] = iv.w;
+                    if (BITS == 8) {
+                        uint32_t w4;
+                        __builtin_memcpy(&w4, vb + j, 4);
+                        const uint64_t c0 = t.chunkSh < 64u ? (j >> t.chunkSh) : j / t.chunk;
+                        const uint64_t c3 = t.chunkSh < 64u ? ((j + 3) >> t.chunkSh) : (j + 3) / t.chunk;
+                        const float s0 = sb[c0], s3 = c3 == c0 ? s0 : sb[c3];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const uint64_t cu = t.chunkSh < 64u ? ((j + u) >> t.chunkSh) : (j + u) / t.chunk;
+                            x4[v][u] = __fmul_rn((float)(int)(int8_t)(w4 >> (8 * u)), cu == c0 ? s0 : s3);
+                        }
+                    } else if (BITS == 32) {
+                        f4 fv;
+                        __builtin_memcpy(&fv, vb + 4 * j, 16);
+                        x4[v][0] = fv.x; x4[v][1] = fv.y; x4[v][2] = fv.z; x4[v][3] = fv.w;
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) x4[v][u] = decode<BITS>(vb, sb, j + u, t.chunk, t.chunkSh);
+                    }
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 2; ++v)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint64_t slot = (uint64_t)li4[v][u] + shift;
+                    if (li4[v][u] < nb && slot < TILE) tile[slot] = x4[v][u];
+                }
+        }
+        /* what is left (at most three after the groups; everything beyond the first 256 of a less crowded tile) */
+        for (uint64_t jb = jA + 4 * ngrp; jb < j1; jb += 4 * WG) {
+            uint32_t li1[4];
+            float x1[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint64_t j = jb + (uint64_t)u * WG + tid;
-                li4[u] = NONE;
-                x4[u] = 0.0f;
-                if (j < j1) { li4[u] = ib[j]; x4[u] = decode<BITS>(vb, sb, j, t.chunk, t.chunkSh); }
+                li1[u] = NONE;
+                x1[u] = 0.0f;
+                if (j < j1) { li1[u] = ib[j]; x1[u] = decode<BITS>(vb, sb, j, t.chunk, t.chunkSh); }
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const uint64_t slot = (uint64_t)li4[u] + shift;
-                if (li4[u] < nb && slot < TILE) tile[slot] = x4[u];
+                const uint64_t slot = (uint64_t)li1[u] + shift;
+                if (li1[u] < nb && slot < TILE) tile[slot] = x1[u];
             }
         }
         fetch(ti + 1);
