@@ -289,8 +289,9 @@ int nsml_profile_read(nsml_ctx *ctx, uint32_t *launches, double *total_ms);
 int nsml_path_stats(nsml_ctx *ctx, uint32_t *fast_buckets, uint32_t *fallback_buckets);
 /* Diagnostics: the selection state of bucket b after the last nsml_compress of the context, eight
  * words to out8 (host): how it was decided (0 dense passes, 1 candidates, 2 band, 3 zero
- * threshold), why the dense passes were taken (bits: 1 the sample gave no usable guess, 2 a
- * staging segment overflowed, 4 fewer staged elements than k, 8 no room for the undecided keys,
+ * threshold), why the dense passes were taken (bits: 1 the sample gave no usable guess, 2 not
+ * used (a staging segment that overflows is read from the dense accumulator instead), 4 fewer
+ * staged elements than k, 8 no room for the undecided keys,
  * 16 the threshold lies outside the staged band, 32 more non-zero elements than k in zero mode),
  * the staged key range [L, H) (0xFFFFFFFF: none / no upper bound), the threshold key, the number
  * of admitted elements equal to it, the bit position the threshold was known to before the
