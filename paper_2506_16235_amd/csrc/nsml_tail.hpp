@@ -187,7 +187,7 @@ struct DenseSrc {
 /* One wavefront's four segments of k_select_count, GROUP lanes per segment (16: all four at
  * once, 64: one after the other).  mlen != 0 in the lane that describes a segment: the segment
  * overflowed and is read from the dense accumulator (me0, mlen). */
-template <uint32_t GROUP>
+template <uint32_t GROUP, bool DENSE>      /* DENSE: some segment of this wavefront is read from the accumulator */
 __device__ __forceinline__ void select_count_wave(const Cand &c, uint32_t b0, uint32_t sh, uint32_t wseg0, uint32_t mcnt,
                                                   uint64_t me0, uint32_t mlen, const DenseSrc &ds,
                                                   uint32_t segl0, uint32_t *lk, uint32_t *lcur,
@@ -204,9 +204,9 @@ __device__ __forceinline__ void select_count_wave(const Cand &c, uint32_t b0, ui
     for (uint32_t rd = 0; rd < ROUNDS; ++rd) {
         const uint32_t src = rd * SPR + sub;
         const uint32_t staged = __shfl(mcnt, src, 64);
-        const uint32_t dlen = __shfl(mlen, src, 64);
-        const bool dense = dlen != 0u;
-        const uint64_t e0 = ((uint64_t)__shfl((uint32_t)(me0 >> 32), src, 64) << 32) | (uint64_t)__shfl((uint32_t)me0, src, 64);
+        const uint32_t dlen = DENSE ? __shfl(mlen, src, 64) : 0u;
+        const bool dense = DENSE && dlen != 0u;
+        const uint64_t e0 = DENSE ? ((uint64_t)__shfl((uint32_t)(me0 >> 32), src, 64) << 32) | (uint64_t)__shfl((uint32_t)me0, src, 64) : 0ull;
         const uint32_t cnt = dense ? dlen : staged;
         uint32_t maxcnt = cnt;
 #pragma unroll
@@ -298,8 +298,13 @@ __global__ __launch_bounds__(WG) void k_select_count(Tables t, Cand c, const uin
     for (int d = 2; d >= 1; d >>= 1) mx = max(mx, (uint32_t)__shfl_xor(mx, d, 64));
     mx = __builtin_amdgcn_readfirstlane(mx);
     uint32_t my_g = 0, my_b = 0;
-    if (mx > 2 * CU * 16) select_count_wave<64>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
-    else if (mx) select_count_wave<16>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+    if (__any(mlen != 0u)) {
+        if (mx > 2 * CU * 16) select_count_wave<64, true>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+        else if (mx) select_count_wave<16, true>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+    } else {
+        if (mx > 2 * CU * 16) select_count_wave<64, false>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+        else if (mx) select_count_wave<16, false>(c, b0, sh, wseg0, mcnt, me0, mlen, ds, wave * SEL_SEGS_PER_WAVE, lk, &lcur, my_g, my_b);
+    }
     if (mine) {
         c.G[ms] = mg0 + my_g;
         c.E[ms] = my_b;
