@@ -320,6 +320,38 @@ def test_context_reuse_across_layouts_and_ratios():
         c.step(ratio, bits)
 
 
+def test_two_contexts_on_two_streams_at_once(path):
+    """Two contexts working at the same time on streams of their own (the header allows it): with
+    every bucket on the dense passes both run the launch whose workgroups meet at barriers, so
+    the two teams must fit the device together.  Results of both against the oracle, five rounds."""
+    n = 3_000_000
+    off = W.offsets_of([1_000_000, 1_500_001, 499_999])
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    cases = []
+    for i in range(2):
+        g = _rand(n, 4000 + i)
+        cases.append({"ctx": nsml.Context(n, 3, 256), "g": g, "r": torch.zeros(n, device=DEV),
+                      "g_h": g.cpu().numpy(), "r_h": np.zeros(n, dtype=np.float32)})
+    torch.cuda.synchronize()
+    for rnd in range(5):
+        ratio, bits = [(0.01, 8), (0.3, 4), (0.05, 16), (1.0, 8), (0.002, 4)][rnd]
+        outs = []
+        for i, c in enumerate(cases):
+            with torch.cuda.stream(streams[i]):
+                outs.append(c["ctx"].compress(c["g"], c["r"], off, ratio, bits))
+        torch.cuda.synchronize()
+        for c, (idx, val, sc) in zip(cases, outs):
+            c["ctx"].path_stats()
+            want = oracle.compress(c["g_h"], c["r_h"], off, ratio, bits, 256, nthreads=8)
+            k_b, K, vb, ns = oracle.layout(off, ratio, bits, 256)
+            got = (idx.cpu().numpy().view(np.uint32)[:K], val.cpu().numpy()[:vb], sc.cpu().numpy()[:ns])
+            from gpu_util import compare_payload
+            compare_payload(off, ratio, bits, 256, got, want)
+            assert np.array_equal(c["r"].cpu().numpy().view(np.uint32), c["r_h"].view(np.uint32))
+    for c in cases:
+        c["ctx"].close()
+
+
 def test_gpu_argument_errors():
     ctx = nsml.Context(10_000, 2, 64)
     g = _rand(10_000, 1)
