@@ -498,7 +498,7 @@ __global__ __launch_bounds__(WG) void k_decomp_lds(const uint32_t *__restrict__ 
 }
 
 /* Dense output for a span of tiles, the variant for the largest gradients: one wavefront per
- * tile (64 x spanT threads).  A wavefront
+ * tile, 16 wavefronts per workgroup (one span of 16 tiles, two of 8, ...).  A wavefront
  * first fetches its tile's survivors (found through the tile-start table), then writes the
  * tile's 16 KiB of zeros with aligned 16-byte stores, one contiguous KiB per instruction, waits
  * for those stores, and drops the decoded survivors into place.  Both writes to a survivor's
@@ -510,8 +510,15 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_decomp(const uint32_t *_
                                                                const uint32_t *__restrict__ ts, float *__restrict__ dense)
 {
     constexpr int U = 2;                     /* survivors per lane fetched ahead of the zeros */
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
-    const SpanGeo s = span_geo(t, blockIdx.x);
+    /* a workgroup of 16 wavefronts takes as many whole spans as it has a wavefront per tile for */
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t per_wg = max(1u, (uint32_t)MAX_SEG_WAVES / t.spanT);
+    const uint32_t sub = (tid >> 6) / t.spanT;
+    const uint32_t span = blockIdx.x * per_wg + min(sub, per_wg - 1u);
+    const uint32_t wave = (tid >> 6) - min(sub, per_wg - 1u) * t.spanT;       /* wavefront within its span */
+    const uint32_t n_waves = per_wg > 1u ? t.spanT : (uint32_t)(blockDim.x >> 6);
+    if (span >= t.n_spans || (per_wg > 1u && sub >= per_wg)) return;
+    const SpanGeo s = span_geo(t, span);
     const uint32_t kb = t.k[s.b];
     const uint32_t *ib = idx + t.P[s.b];
     const uint8_t *vb = reinterpret_cast<const uint8_t *>(val) + t.V[s.b];

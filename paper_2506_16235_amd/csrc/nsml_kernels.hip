@@ -257,13 +257,15 @@ int prof_end(nsml_ctx *c, bool recorded, hipStream_t st)
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-/* Tiles per span (one span = one workgroup of the streaming kernels, four candidate
- * segments).  Small spans stream a few per cent faster, large spans mean fewer segments for
- * the candidate kernels to walk; measured on 25 M .. 6.7 G elements the totals favour this. */
+/* Tiles per span (one span = one workgroup of the streaming kernels, with four to sixteen
+ * staging segments).  Small spans stream a few per cent faster, large spans mean fewer segments
+ * for the candidate kernels to walk; measured on 25 M .. 6.7 G elements the totals favour this.
+ * (Spans of 16 tiles, one workgroup of 16 wavefronts per compute unit, lose 1 - 8 % to spans of 8
+ * with two workgroups of 8: while one of the two ends and its successor starts, the other keeps
+ * streaming.) */
 uint32_t pick_span_tiles(uint32_t n_tiles, int override_)
 {
     if (override_ >= 1 && override_ <= MAX_SPAN_TILES) return (uint32_t)override_;
-    if (n_tiles >= 16u * 4096u) return 16;
     if (n_tiles >= 8u * 2048u) return 8;
     if (n_tiles >= 4u * 1024u) return 4;
     if (n_tiles >= 2u * 512u) return 2;
@@ -749,9 +751,12 @@ static int launch_decompress(nsml_ctx *c, hipStream_t st, const Tables &t, uint6
         LAUNCH(c, KID_TILESTART, st, k_tilestart<2>, (uint32_t)want, idx, t, K, d_ts);
     }
     const uint32_t *ts = d_ts;
-    if (variant > 0 || (variant < 0 && t.spanT >= MAX_SPAN_TILES && !crowded)) {
-        /* the largest gradients at low ratios: one wavefront per tile, direct stores (plain unless asked otherwise) */
-        const uint32_t dblock = 64u * t.spanT;
+    if (variant > 0 || (variant < 0 && n_tiles >= 16u * 4096u && !crowded)) {
+        /* the largest gradients at low ratios: one wavefront per tile, direct stores (plain unless asked
+         * otherwise); 16 wavefronts per workgroup, which take 16 / spanT whole spans */
+        const uint32_t dblock = 64u * MAX_SEG_WAVES;
+        const uint32_t per_wg = MAX_SEG_WAVES / t.spanT ? MAX_SEG_WAVES / t.spanT : 1u;
+        n_spans = (n_spans + per_wg - 1) / per_wg;
         if (nt_dense > 0) {
             switch (bits) {
             case 32: LAUNCHB(c, KID_DECOMP, st, (k_decomp<32, true>), n_spans, dblock, idx, val, scales, t, ts, dense_out); break;

@@ -247,6 +247,31 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     for (uint32_t span = sp0; span < sp1; ++span) {
     double sq = 0.0;                     /* sum of grad^2 over this thread's elements */
     const SpanGeo s = span_geo(t, span);
+    /* this wavefront's wave-tiles: [wave * per, (wave + 1) * per) of the span's 4 * ntiles.  The
+     * rows of a wave-tile that lies wholly inside the bucket are requested half a wave-tile
+     * ahead: the first two before the histograms are set up, each further pair before the pair at
+     * hand is worked on, so a wavefront always has loads in flight. */
+    constexpr int FR = 2;                /* rows of 1 KiB per operand and request */
+    const uint32_t per = (t.spanT * 4u) >> t.segSh;
+    const uint32_t wt0 = wave * per;
+    const uint32_t wt1 = min(s.ntiles * 4u, wt0 + per);
+    f4 gn[FR], rn[FR];
+    auto whole = [&](uint32_t wt) {
+        const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+        return wt < wt1 && wb >= s.lo && wb + WTILE <= s.hi;
+    };
+    auto fetch = [&](uint32_t wt, int half) {
+        const uint64_t wb = s.base + (uint64_t)wt * WTILE;
+#pragma unroll
+        for (int v = 0; v < FR; ++v) {
+            const uint64_t gi = wb + (uint64_t)((half * FR + v) * 64 + lane) * 4;
+            gn[v] = (NT & 1) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi))
+                             : *reinterpret_cast<const f4 *>(g + gi);
+            rn[v] = (NT & 2) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r + gi))
+                             : *reinterpret_cast<const f4 *>(r + gi);
+        }
+    };
+    if (whole(wt0)) fetch(wt0, 0);
     if (s.b != cur_b) {
         if (cur_b != NONE) {
             __syncthreads();
@@ -267,39 +292,36 @@ __global__ __launch_bounds__(64 * MAX_SEG_WAVES) void k_ef_emit(const float *__r
     const uint64_t cbase = (uint64_t)ss * c.cap;
     uint32_t wcount = 0;
     __syncthreads();
-    /* this wavefront's wave-tiles: [wave * per, (wave + 1) * per) of the span's 4 * ntiles */
-    const uint32_t per = (t.spanT * 4u) >> t.segSh;
-    const uint32_t wt0 = wave * per;
-    const uint32_t wt1 = min(s.ntiles * 4u, wt0 + per);
     for (uint32_t wt = wt0; wt < wt1; ++wt) {
         const uint64_t wb = s.base + (uint64_t)wt * WTILE;
-        if (wb >= s.lo && wb + WTILE <= s.hi) {
+        if (whole(wt)) {
             {
-            constexpr int ROWS = 4, hb2 = 0;         /* rows of 1 KiB in flight per operand */
-            f4 gv[ROWS], rv[ROWS];
 #pragma unroll
-            for (int v = 0; v < ROWS; ++v) {
-                const uint64_t gi = wb + (uint64_t)((hb2 + v) * 64 + lane) * 4;
-                gv[v] = (NT & 1) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(g + gi))
-                                 : *reinterpret_cast<const f4 *>(g + gi);
-                rv[v] = (NT & 2) ? __builtin_nontemporal_load(reinterpret_cast<const f4 *>(r + gi))
-                                 : *reinterpret_cast<const f4 *>(r + gi);
-            }
+            for (int half = 0; half < 4 / FR; ++half) {
+                /* the sums first: they free the registers the next rows arrive in */
+                float acc[FR][4];
 #pragma unroll
-            for (int v = 0; v < ROWS; ++v) {
-                const int u = hb2 + v;
-                const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
-                float a[4];
-                a[0] = __fadd_rn(gv[v].x, rv[v].x); a[1] = __fadd_rn(gv[v].y, rv[v].y);
-                a[2] = __fadd_rn(gv[v].z, rv[v].z); a[3] = __fadd_rn(gv[v].w, rv[v].w);
-                sq += (double)(__fmaf_rn(gv[v].x, gv[v].x, __fmul_rn(gv[v].y, gv[v].y)) +
-                               __fmaf_rn(gv[v].z, gv[v].z, __fmul_rn(gv[v].w, gv[v].w)));
-                uint32_t cm = 0xFu;
-                if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
-                ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, hb, subLo, L, H, c, cbase, wcount, n_hi, n_lo);
+                for (int v = 0; v < FR; ++v) {
+                    acc[v][0] = __fadd_rn(gn[v].x, rn[v].x); acc[v][1] = __fadd_rn(gn[v].y, rn[v].y);
+                    acc[v][2] = __fadd_rn(gn[v].z, rn[v].z); acc[v][3] = __fadd_rn(gn[v].w, rn[v].w);
+                    sq += (double)(__fmaf_rn(gn[v].x, gn[v].x, __fmul_rn(gn[v].y, gn[v].y)) +
+                                   __fmaf_rn(gn[v].z, gn[v].z, __fmul_rn(gn[v].w, gn[v].w)));
+                }
+                if (half + 1 < 4 / FR) fetch(wt, half + 1);
+                else if (whole(wt + 1)) fetch(wt + 1, 0);
+#pragma unroll
+                for (int v = 0; v < FR; ++v) {
+                    const int u = half * FR + v;
+                    const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
+                    const float (&a)[4] = acc[v];
+                    uint32_t cm = 0xFu;
+                    if (PRUNE) cm &= ~pruned_bits(t.pmask, s.tile_g + (wt >> 2), (wt & 3u) * WG + u * 64 + lane);
+                    ef_row<true, EMIT, NT, PRUNE>(r, gi, a, 0xFu, cm, (uint32_t)(gi - s.lo), h, hb, subLo, L, H, c, cbase, wcount, n_hi, n_lo);
+                }
             }
             }
         } else {
+            if (whole(wt + 1)) fetch(wt + 1, 0);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint64_t gi = wb + (uint64_t)(u * 64 + lane) * 4;
