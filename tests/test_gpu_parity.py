@@ -255,6 +255,28 @@ def test_streaming_geometries(monkeypatch, span_tiles, seg_waves):
     c.step(0.45, 32)
 
 
+@pytest.mark.parametrize("span_tiles", [1, 2, 3, 4, 5, 7, 8, 12, 16])
+def test_wavefront_per_tile_decompress_at_every_span_size(monkeypatch, span_tiles):
+    """The decompress variant of the largest gradients (one wavefront per tile, 16 wavefronts per
+    workgroup, which take 16 / span whole spans) forced on a small ragged gradient: last spans
+    with fewer tiles than the others, a last workgroup with fewer spans, an empty bucket, sparse
+    and crowded tiles, every value width."""
+    monkeypatch.setitem(nsml.Context.default_options, "span_tiles", int(span_tiles))
+    monkeypatch.setitem(nsml.Context.default_options, "decomp_variant", 1)
+    sizes = [200_003, 65_536 * 3 + 1, 4_099, 0, 333_333, 70_001, 5]
+    off = W.offsets_of(sizes)
+    n = int(off[-1])
+    say("wave-per-tile decompress, span", span_tiles, n)
+    c = Case(_rand(n, 777), off, chunk=256)
+    c.step(0.002, 4)
+    c.set_grad(_rand(n, 778))
+    c.step(0.05, 8)
+    c.set_grad(_rand(n, 779))
+    c.step(0.4, 16)
+    c.set_grad(_rand(n, 780))
+    c.step(1.0, 32)
+
+
 @pytest.mark.parametrize("span_tiles", [0, 16])
 @pytest.mark.parametrize("bits", [4, 8, 16, 32])
 def test_decompress_of_a_malformed_index_list_stays_inside_the_output(monkeypatch, span_tiles, bits):
